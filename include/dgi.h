@@ -1,0 +1,220 @@
+/*
+ * dgi.h — C ABI of the layer-wise full-graph GNN inference library for MI355X (gfx950).
+ *
+ * The library runs the layer-wise schedule of the DGI paper (arXiv 2211.15082, Section 2,
+ * Algorithm 2): every layer is evaluated once over all nodes, in batches of destination
+ * nodes; a batch gathers only the 1-hop in-neighbours of its nodes (Eq. 1), so the L-hop
+ * neighbour explosion of node-wise inference (Algorithm 1) never arises.  Graph, features,
+ * weights and every intermediate embedding are resident in HBM; the "copy to the computing
+ * device" steps of Algorithm 2 therefore vanish and a batch is a range of CSR rows.
+ *
+ * Conventions
+ *   - All pointers are plain pointers.  Each argument says HOST or DEVICE.  DEVICE pointers
+ *     are HIP device allocations of the current device (e.g. a torch tensor's data_ptr()).
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls that
+ *     take a stream enqueue work on it and return without waiting unless stated otherwise.
+ *   - Matrices are row-major with an explicit leading dimension `ld` counted in ELEMENTS.
+ *   - Every call returns a dgi_status_t; nothing throws or aborts across this boundary.  The
+ *     text of the last failure on the calling thread is available from dgi_last_error().
+ *   - The library never takes ownership of caller memory.  Handles it returns are released
+ *     with the matching *_free call.
+ */
+#ifndef DGI_H
+#define DGI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DGI_VERSION_MAJOR 0
+#define DGI_VERSION_MINOR 1
+#define DGI_MAX_LAYERS 16
+
+typedef enum {
+    DGI_OK = 0,
+    DGI_ERR_INVALID_ARG = 1, /* NULL where data is required, negative size, bad range, dims that disagree */
+    DGI_ERR_BAD_GRAPH = 2,   /* indptr not monotone / indptr[0]!=0 / indptr[N]!=E / index out of [0,N) */
+    DGI_ERR_UNSUPPORTED = 3, /* dtype / aggregator / order combination the kernels do not implement */
+    DGI_ERR_OOM = 4,         /* workspace does not fit the budget even at one row per batch (Sec. 4.1) */
+    DGI_ERR_DEVICE = 5       /* a HIP call failed; dgi_last_error() holds its text */
+} dgi_status_t;
+
+typedef enum { DGI_I32 = 0, DGI_I64 = 1 } dgi_itype_t;
+typedef enum { DGI_HOST = 0, DGI_DEVICE = 1 } dgi_memloc_t;
+typedef enum { DGI_F32 = 0, DGI_BF16 = 1 } dgi_dtype_t;
+
+/* AGGREGATE of Eq. 1.  N(v) = in-neighbours of v = the entries of CSR row v.
+ *   SUM : m_v = sum_u h_u                      MEAN: m_v = (1/|N(v)|) sum_u h_u   (0 if N(v) empty)
+ *   GCN : m_v = sum_u h_u / sqrt(d_out(u) d_in(v)), degrees counted on the stored CSR, clamped >= 1
+ *   GAT : m_v = concat_h sum_u alpha^h_uv z^h_u, alpha = softmax_u LeakyReLU(<a_src^h,z^h_u> + <a_dst^h,z^h_v>)
+ * SUM/MEAN: h'_v = act(h_v W_self + m_v W_neigh + b)  (W_self may be NULL: term dropped)
+ * GCN     : h'_v = act(m_v W_neigh + b)
+ * GAT     : z = h W_neigh viewed as [heads, head_dim];  h'_v = act(m_v + b)                              */
+typedef enum { DGI_AGG_SUM = 0, DGI_AGG_MEAN = 1, DGI_AGG_GCN = 2, DGI_AGG_GAT = 3 } dgi_agg_t;
+
+typedef enum { DGI_ACT_NONE = 0, DGI_ACT_RELU = 1, DGI_ACT_ELU = 2, DGI_ACT_LEAKY_RELU = 3 } dgi_act_t;
+
+/* Whether the dense transform runs before or after the neighbour aggregation.  Both give the same
+ * result up to rounding, because aggregation is linear.  AUTO = transform first iff out_dim < in_dim
+ * (GAT is always transform-first). */
+typedef enum { DGI_ORDER_AUTO = 0, DGI_ORDER_AGG_FIRST = 1, DGI_ORDER_TRANSFORM_FIRST = 2 } dgi_order_t;
+
+/* Node renumbering used to form batches of consecutive ids that share in-neighbours (Section 4.2).
+ *   DEGREE : descending in-degree, ties by old id ("Degree Sorting" of Section 5.3)
+ *   BFS_RCM: reverse Cuthill-McKee style BFS enumeration on the undirected structure (the paper's RCMK)
+ *   RANDOM : seeded shuffle (the "Random" comparison point)                                             */
+typedef enum { DGI_REORDER_NONE = 0, DGI_REORDER_DEGREE = 1, DGI_REORDER_BFS_RCM = 2, DGI_REORDER_RANDOM = 3 } dgi_reorder_t;
+
+typedef struct dgi_graph dgi_graph_t; /* opaque; owns device copies of the CSR and degree vectors */
+
+/* One GNN layer (Eq. 1 instantiated).  All weight pointers are DEVICE pointers, row-major
+ * [in_dim x out_dim], so that a row vector h maps to h W.  Weights have dtype `feat_dtype`
+ * (fp32, or bf16 stored as uint16 bit patterns); bias and attention vectors are always fp32. */
+typedef struct {
+    int32_t agg;         /* dgi_agg_t */
+    int32_t act;         /* dgi_act_t, applied last */
+    float   act_slope;   /* LEAKY_RELU negative slope; ELU alpha */
+    int32_t in_dim;
+    int32_t out_dim;     /* GAT: heads * head_dim */
+    int32_t heads;       /* GAT only; otherwise ignored (use 1) */
+    int32_t feat_dtype;  /* dgi_dtype_t of h_in and of the weights */
+    int32_t out_dtype;   /* dgi_dtype_t of h_out */
+    int32_t order;       /* dgi_order_t */
+    const void*  W_self;   /* [in_dim x out_dim] or NULL.  SUM/MEAN only. */
+    const void*  W_neigh;  /* [in_dim x out_dim]; the only weight of GCN and GAT */
+    const float* bias;     /* [out_dim] or NULL */
+    const float* attn_src; /* [heads x head_dim], GAT only */
+    const float* attn_dst; /* [heads x head_dim], GAT only */
+    float   attn_slope;    /* LeakyReLU slope of the GAT edge score (0.2 in the usual model) */
+    int32_t reserved;
+} dgi_layer_t;
+
+/* Per-layer measurements filled by dgi_infer when opts->stats is set.  Kernel times are taken with
+ * HIP events recorded on the caller's stream around every launch of that kernel class. */
+typedef struct {
+    int32_t num_layers;
+    int32_t reserved;
+    double  total_ms;                       /* whole dgi_infer, first enqueue to last completion */
+    double  layer_ms[DGI_MAX_LAYERS];
+    double  agg_ms[DGI_MAX_LAYERS];         /* gather/aggregate (or GAT edge) kernels, summed over batches */
+    double  gemm_ms[DGI_MAX_LAYERS];        /* dense transform kernels, summed over batches */
+    int64_t agg_launches[DGI_MAX_LAYERS];
+    int64_t gemm_launches[DGI_MAX_LAYERS];
+    int64_t batches[DGI_MAX_LAYERS];
+    int64_t edges[DGI_MAX_LAYERS];          /* edges aggregated by the layer (= E for full inference) */
+    int32_t transform_first[DGI_MAX_LAYERS];
+    int32_t gather_width[DGI_MAX_LAYERS];   /* elements per gathered source row */
+    int64_t oom_retries;                    /* batches redone after halving the thresholds (Sec. 4.1) */
+    int64_t workspace_bytes;                /* peak bytes the library allocated for this call */
+} dgi_stats_t;
+
+typedef struct {
+    int64_t batch_size;            /* destination rows per batch; 0 = dynamic control of Sec. 4.1 (Eq. 2) */
+    const int32_t* perm_new_of_old;/* DEVICE, N entries, or NULL.  When set, `g` must be the reordered graph
+                                      returned by dgi_graph_reorder; x and out stay in ORIGINAL node order and
+                                      the library permutes rows on the way in and back on the way out. */
+    uint64_t mem_budget_bytes;     /* bytes the call may allocate for hidden layers + temporaries;
+                                      0 = 90 % of the currently free device memory (Sec. 4.1) */
+    dgi_stats_t* stats;            /* HOST, or NULL.  Setting it makes dgi_infer wait for completion. */
+    int64_t init_node_threshold;   /* initial n_t of Eq. 2 for batch_size==0; 0 = 65536 */
+    int64_t init_edge_threshold;   /* initial n_i of Eq. 2; 0 = init_node_threshold * average degree */
+} dgi_infer_opts_t;
+
+typedef struct {
+    int64_t num_nodes;
+    int64_t num_edges;
+    int64_t max_in_degree;
+    int64_t num_hub_rows;     /* rows long enough to be split over several workgroups */
+    int32_t indptr_type;      /* dgi_itype_t */
+    int32_t reserved;
+    uint64_t device_bytes;    /* device memory owned by the handle */
+} dgi_graph_info_t;
+
+/* ------------------------------------------------------------------------------------------------
+ * Graph (the input "G" of Section 2).  CSR keyed by DESTINATION: row v = indices[indptr[v] ..
+ * indptr[v+1]) lists the sources u of the edges u->v, i.e. the in-neighbours N(v) of Eq. 1.
+ * Duplicate entries are legal and count with multiplicity; rows need not be sorted.
+ *   indptr : N+1 entries of type `indptr_type`;  indices: E int32 entries;  both at `where`.
+ *   HOST input is copied to the device.  DEVICE input is BORROWED: the caller keeps it alive and
+ *   unchanged until dgi_graph_free.  The call validates the CSR (DGI_ERR_BAD_GRAPH otherwise),
+ *   computes in/out degrees and their inverse square roots, and finds the hub rows.  It waits
+ *   for its own work on `hip_stream` before returning.  N == 0 is legal.                         */
+dgi_status_t dgi_graph_load(int64_t num_nodes, int64_t num_edges, const void* indptr, int32_t indptr_type,
+                            const int32_t* indices, int32_t where, void* hip_stream, dgi_graph_t** out);
+dgi_status_t dgi_graph_free(dgi_graph_t* g);            /* NULL is a no-op */
+dgi_status_t dgi_graph_info(const dgi_graph_t* g, dgi_graph_info_t* info /*HOST*/);
+
+/* Copies of the handle's device vectors for inspection/tests: kind 0 = in-degree (int32), 1 = out-degree
+ * (int32), 2 = in-degree^-1/2 (fp32), 3 = out-degree^-1/2 (fp32); `dst` is a HOST buffer of N entries. */
+dgi_status_t dgi_graph_vector(const dgi_graph_t* g, int32_t kind, void* dst);
+/* Copy the handle's CSR back to HOST buffers (indptr as int64, N+1 entries; indices E entries). */
+dgi_status_t dgi_graph_csr(const dgi_graph_t* g, int64_t* indptr, int32_t* indices);
+
+/* Node reordering (Section 4.2).  Builds a renumbered copy of `g` (rows permuted, sources relabelled,
+ * each row sorted by new source id) and writes perm_new_of_old[old] = new into a buffer of N int32 at
+ * `perm_where` (HOST or DEVICE).  Any bijection leaves the inference result unchanged up to rounding;
+ * only locality differs.  The permutation is computed on the host from the handle's CSR; relabelling
+ * runs on the device.  `seed` is used by RANDOM only. */
+dgi_status_t dgi_graph_reorder(const dgi_graph_t* g, int32_t method, uint64_t seed, void* hip_stream,
+                               dgi_graph_t** g_out, int32_t* perm_new_of_old, int32_t perm_where);
+
+/* ------------------------------------------------------------------------------------------------
+ * One layer of Eq. 1 for the destination rows [dst_begin, dst_end) (lines 4-10 of Algorithm 2 for
+ * one batch).  h_in  : DEVICE, all N rows of H^{l-1}, [N x in_dim], leading dimension ld_in.
+ *              h_out : DEVICE, all N rows of H^l; only rows [dst_begin,dst_end) are written.
+ * h_in and h_out must not overlap.  `workspace` is DEVICE scratch of at least
+ * dgi_layer_workspace_bytes(...) bytes, 256-byte aligned, contents undefined before and after.
+ * A transform-first layer needs the transformed rows of every source node, so it transforms all N
+ * rows on every call: use dgi_infer, which does that once per layer, when running many batches.
+ * Fast paths need 16-byte aligned rows (pointer and ld*elemsize multiples of 16); other layouts are
+ * accepted and run on a slower element-wise gather.  An empty range, or N == 0, returns DGI_OK. */
+dgi_status_t dgi_layer_forward(const dgi_graph_t* g, const dgi_layer_t* layer, const void* h_in, int64_t ld_in,
+                               void* h_out, int64_t ld_out, int64_t dst_begin, int64_t dst_end,
+                               void* workspace, uint64_t workspace_bytes, void* hip_stream);
+dgi_status_t dgi_layer_workspace_bytes(const dgi_graph_t* g, const dgi_layer_t* layer, int64_t dst_begin,
+                                       int64_t dst_end, uint64_t* bytes /*HOST*/);
+
+/* Whole-model layer-wise inference (Algorithm 2): for l = 1..L, for every batch of destination rows,
+ * compute H^l[batch]; H^{l-1} is released when layer l is done (two ping-pong buffers).
+ *   x   : DEVICE [N x layers[0].in_dim], dtype layers[0].feat_dtype, leading dimension ld_x.
+ *   out : DEVICE [N x layers[L-1].out_dim], dtype layers[L-1].out_dtype, leading dimension ld_out.
+ *   layers[l].in_dim must equal layers[l-1].out_dim and feat_dtype must equal the previous out_dtype.
+ * The call allocates its hidden buffers and temporaries with hipMalloc within opts->mem_budget_bytes and
+ * frees them before returning (it waits for the stream when it allocated anything or stats is set).
+ * opts may be NULL (all defaults). */
+dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layers, int32_t num_layers, const void* x,
+                       int64_t ld_x, void* out, int64_t ld_out, const dgi_infer_opts_t* opts, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Host-side planning helpers (no device access; usable without a GPU).
+ *
+ * dgi_plan_batch_end: the batching rule of Section 4.1.  The in-degree prefix sum is `indptr` itself;
+ * starting at row `begin`, returns by binary search the largest `end` <= row_limit with
+ * end-begin <= n_t and indptr[end]-indptr[begin] <= n_i, but never less than begin+1 (a row whose own
+ * degree exceeds n_i forms a batch by itself).  indptr is a HOST array. */
+dgi_status_t dgi_plan_batch_end(const void* indptr, int32_t indptr_type, int64_t row_limit, int64_t begin,
+                                int64_t n_t, int64_t n_i, int64_t* end);
+/* Eq. 2: r = M / M_k; n_t <- r n_t; n_i <- r n_i (both kept >= 1).  M_k <= 0 leaves them unchanged. */
+dgi_status_t dgi_threshold_update(double M_expected, double M_k, int64_t* n_t, int64_t* n_i);
+/* Out-of-memory reaction of Section 4.1: halve both thresholds (floor, >= 1).  Returns DGI_ERR_OOM when
+ * both are already 1. */
+dgi_status_t dgi_threshold_halve(int64_t* n_t, int64_t* n_i);
+/* Number of distinct source nodes the batch [begin,end) reads (the "input set" of Section 4.2's example);
+ * HOST CSR, indptr as int64. */
+dgi_status_t dgi_batch_input_set_size(int64_t num_nodes, const int64_t* indptr, const int32_t* indices,
+                                      int64_t begin, int64_t end, int64_t* count);
+/* The permutation dgi_graph_reorder would use, computed from a HOST CSR (indptr int64). */
+dgi_status_t dgi_reorder_permutation(int64_t num_nodes, const int64_t* indptr, const int32_t* indices,
+                                     int32_t method, uint64_t seed, int32_t* perm_new_of_old);
+
+const char* dgi_status_string(dgi_status_t s);
+const char* dgi_last_error(void);  /* thread-local, never NULL */
+int32_t     dgi_version(void);     /* major*1000 + minor */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DGI_H */
