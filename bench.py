@@ -1,0 +1,159 @@
+"""Benchmark of the layer-wise full-graph inference path on one MI355X.
+
+A step is one dgi_infer call: every layer of the model over every node of the graph, in destination
+batches chosen by the library (dynamic batch-size control).  The default workload is the 3-layer GCN on
+the 2.4 M-node / 126 M-edge synthetic power-law graph (inputs generated on the GPU from seeds and
+resident in HBM before the timed region).  Prints one JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--scale 1.0] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes(n, e, width, elem, indptr_bytes, heads=0):
+    """Bytes the aggregation of one layer must move when nothing is reused: per edge one source row and
+    its index (plus the GAT score terms), per destination node its indptr entry and its output row."""
+    per_edge = width * elem + 4 + 4 * heads
+    per_node = indptr_bytes + width * elem
+    return e * per_edge + n * per_node
+
+
+def cpu_baseline(cfg, rows_sample=150_000):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: every layer of the model on
+    the first `rows_sample` destination rows of the full graph (synthetic N(0,1) inputs of each layer's
+    width stand in for the hidden layers), all host threads.  Reported as aggregated edges per second."""
+    import numpy as np
+    import torch
+    from dgi_inputs import configs, generators
+    from oracle import oracle
+
+    n = cfg["num_nodes"]
+    ip = cfg["indptr"].cpu().numpy().astype(np.int64)
+    ix = cfg["indices"].cpu().numpy()
+    rows = np.arange(min(rows_sample, n), dtype=np.int64)
+    edges = int(ip[rows[-1] + 1] - ip[rows[0]])
+    layers = configs.to_numpy_layers(cfg["layers"])
+    threads = oracle.num_threads()
+    total, agg_edges = 0.0, 0
+    for li, L in enumerate(layers):
+        d_in = L["W_neigh"].shape[0]
+        h = cfg["x"].float().cpu().numpy() if li == 0 else generators.normal_features(n, d_in, 777 + li).numpy()
+        t0 = time.perf_counter()
+        oracle.layer_forward(ip, ix, L, h, rows=rows)
+        total += time.perf_counter() - t0
+        agg_edges += edges
+        del h
+    return {"value": agg_edges / total, "unit": "edges/s", "cores": threads, "kind": "oracle",
+            "sample": "all %d layers on the first %d destination rows (%d edges per layer) of the full graph, %.1f s"
+                      % (len(layers), rows.size, edges, total)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--scale", type=float, default=1.0)
+    ap.add_argument("--batch-size", type=int, default=0, help="destination rows per batch; 0 = dynamic")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from dgi_inputs import configs
+    from paper_2211_15082_amd import binding as B
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    dev = "cuda"
+    t_gen = time.perf_counter()
+    cfg = configs.make_config(args.config, scale=args.scale, device=dev)
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t_gen
+    n = cfg["num_nodes"]
+    e = int(cfg["indices"].numel())
+    g = B.graph_load(cfg["indptr"], cfg["indices"])
+    info = g.info()
+    storage = "bf16" if cfg["x"].dtype == torch.bfloat16 else "f32"
+    structs, keep = [], []
+    for i, L in enumerate(cfg["layers"]):
+        fs = storage if i == 0 else cfg["layers"][i - 1].get("out_storage", "f32")
+        s, k = B.make_layer(L, device=dev, feat_dtype=fs)
+        structs.append(s)
+        keep.append(k)
+    x = cfg["x"].contiguous()
+    out = torch.empty(n, structs[-1].out_dim, dtype=torch.float32, device=dev)
+
+    for _ in range(args.warmup):
+        B.infer(g, structs, x, out, batch_size=args.batch_size)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    stats = []
+    for _ in range(args.steps):
+        stats.append(B.infer(g, structs, x, out, batch_size=args.batch_size, want_stats=True))
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    sec = (t1 - t0) / args.steps
+    n_layers = len(structs)
+    agg_edges = n_layers * e
+
+    # dominant kernel: the aggregation launch with the largest total time
+    agg_ms = [sum(s["agg_ms"][l] for s in stats) for l in range(n_layers)]
+    agg_launches = [sum(s["agg_launches"][l] for s in stats) for l in range(n_layers)]
+    gemm_ms = [sum(s["gemm_ms"][l] for s in stats) / args.steps for l in range(n_layers)]
+    dom = max(range(n_layers), key=lambda l: agg_ms[l])
+    width = stats[0]["gather_width"][dom]
+    L = cfg["layers"][dom]
+    is_gat = L["agg"] == "gat"
+    elem = 2 if (storage == "bf16" and (dom == 0 or cfg["layers"][dom - 1].get("out_storage") == "bf16")) else 4
+    ipb = 8 if info["indptr_type"] == 1 else 4
+    bytes_layer = algorithmic_bytes(n, e, width, elem, ipb, heads=L.get("heads", 1) if is_gat else 0)
+    avg_launch_ms = agg_ms[dom] / max(agg_launches[dom], 1)
+    achieved = bytes_layer * args.steps / (agg_ms[dom] * 1e-3) / 1e9  # GB/s over all launches of that kernel
+    result = {
+        "metric": "full-graph layer-wise inference: aggregated edges per second",
+        "value": agg_edges / sec,
+        "unit": "edges/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": sec * 1e3,
+        "inference_seconds": sec,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if storage == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": cfg["name"], "num_nodes": n, "num_edges": e, "max_in_degree": info["max_in_degree"],
+                   "hub_rows": info["num_hub_rows"], "scale": args.scale, "batch_size": args.batch_size or "dynamic",
+                   "batches_per_layer": stats[-1]["batches"], "transform_first": stats[-1]["transform_first"],
+                   "generate_seconds": round(t_gen, 2)},
+        "per_layer_ms": {"layer": [round(sum(s["layer_ms"][l] for s in stats) / args.steps, 3) for l in range(n_layers)],
+                         "aggregate": [round(a / args.steps, 3) for a in agg_ms], "gemm": [round(v, 3) for v in gemm_ms]},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "aggregation launch of layer %d (gather width %d, %d-byte elements)" % (dom + 1, width, elem),
+                     "algorithmic_bytes_per_layer_pass": bytes_layer, "avg_launch_ms": avg_launch_ms,
+                     "launches": agg_launches[dom]},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,447 @@
+// One-hop CSR gather + aggregation (the per-batch "gather N_v and H^{l-1}(N_v), run layer l" steps of
+// Algorithm 2, for the SUM / MEAN / GCN-normalised aggregators of Eq. 1).
+//
+// Mapping to CDNA4: one 64-lane wavefront per destination row.  A source row is fetched with 16-byte
+// loads; G = lanes needed to cover one row (4..64), so one load instruction of the wavefront fetches
+// 64/G different neighbours.  The row's neighbour ids are loaded 64 at a time, coalesced, one per lane,
+// and handed to the lane groups with cross-lane reads; UNROLL independent row loads are in flight per
+// lane before the first is consumed.  Each lane keeps fp32 partial sums of its 16-byte column slice;
+// the 64/G groups are combined with xor-shuffles at the end of the row.  The summation order of a row
+// depends only on (G, UNROLL), never on the batch the row is in.
+//
+// Power-law skew: rows longer than kHubDegree are skipped by the row kernel and cut into kHubChunk-edge
+// chunks, one wavefront each (hub kernel), writing fp32 partial rows; a reduce kernel adds the partials
+// of a row in chunk order and applies the epilogue.  No floating-point atomics anywhere.
+#include <algorithm>
+
+#include "dgi_internal.h"
+
+namespace dgi {
+namespace {
+
+constexpr int kWaves = 4;        // wavefronts per workgroup
+constexpr int kRowsPerWg = 16;   // destination rows per workgroup
+constexpr int kXcds = 8;         // XCDs of MI355X; workgroup i is dispatched to XCD i % 8
+constexpr int kXcdRun = 8;       // consecutive tiles handed to one XCD, so that neighbouring rows share an L2
+
+struct AggParams {
+    const void* indptr;
+    const int32_t* indices;
+    const float* rs_out;
+    const float* rs_in;
+    const void* S;
+    int64_t ld_s;
+    int width;
+    void* out;
+    int64_t ld_out;
+    int64_t out_row0;
+    int out_bf16;
+    int out_vec_ok;
+    const void* self;
+    int64_t ld_self;
+    const float* bias;
+    int act;
+    float act_slope;
+    int64_t row_begin, row_end;
+    int64_t n_tiles;
+    int skip_hubs;
+    // hub pass
+    const int64_t* hub_rows;
+    const int64_t* hub_chunk_ptr;
+    int64_t hub_begin, hub_end;
+    int64_t chunk0;
+    float* partials;
+    int wpad;
+    int64_t n_chunks;    // hub chunks in the range
+    int64_t hub_blocks;  // leading workgroups of the launch that work on hub chunks (multiple of 64)
+};
+
+__device__ __forceinline__ float bf16_to_float(uint32_t hi16) { return __uint_as_float(hi16 << 16); }
+__device__ __forceinline__ uint16_t float_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);  // round to nearest even
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float activate(float x, int act, float slope) {
+    switch (act) {
+        case DGI_ACT_RELU: return x > 0.f ? x : 0.f;
+        case DGI_ACT_ELU: return x > 0.f ? x : slope * expm1f(x);
+        case DGI_ACT_LEAKY_RELU: return x > 0.f ? x : slope * x;
+        default: return x;
+    }
+}
+
+template <typename T> struct Row;
+template <> struct Row<float> {
+    static constexpr int VEC = 4;
+    using Raw = float4;
+    static __device__ __forceinline__ Raw zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+    static __device__ __forceinline__ void unpack(const Raw& r, float* f) { f[0] = r.x; f[1] = r.y; f[2] = r.z; f[3] = r.w; }
+    static __device__ __forceinline__ float one(const float* p) { return *p; }
+};
+template <> struct Row<uint16_t> {
+    static constexpr int VEC = 8;
+    using Raw = uint4;
+    static __device__ __forceinline__ Raw zero() { return make_uint4(0u, 0u, 0u, 0u); }
+    static __device__ __forceinline__ void unpack(const Raw& r, float* f) {
+        f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
+        f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
+        f[4] = __uint_as_float(r.z << 16); f[5] = __uint_as_float(r.z & 0xffff0000u);
+        f[6] = __uint_as_float(r.w << 16); f[7] = __uint_as_float(r.w & 0xffff0000u);
+    }
+    static __device__ __forceinline__ float one(const uint16_t* p) { return bf16_to_float(*p); }
+};
+
+// Tile handled by workgroup `bid`: runs of kXcdRun consecutive tiles go to the same XCD.
+__device__ __forceinline__ int64_t xcd_tile(int64_t bid) {
+    constexpr int64_t group = (int64_t)kXcds * kXcdRun;
+    const int64_t base = bid / group * group;
+    const int64_t r = bid - base;
+    return base + (r % kXcds) * kXcdRun + r / kXcds;
+}
+
+// Adds  sum_{e in [eb,ee)} coef(indices[e]) * S[indices[e], col0 + gl*VEC .. +VEC)  into acc (per lane;
+// the 64/G lane groups hold disjoint subsets of the edges).
+template <typename T, int G, int MODE, int UNROLL>
+__device__ __forceinline__ void gather_range(const AggParams& p, int64_t eb, int64_t ee, int lane, int col0,
+                                             float (&acc)[Row<T>::VEC]) {
+    constexpr int VEC = Row<T>::VEC;
+    constexpr int NSUB = 64 / G;
+    using Raw = typename Row<T>::Raw;
+    const int sub = lane / G, gl = lane % G;
+    const int col = col0 + gl * VEC;
+    const bool col_ok = col < p.width;
+    const T* sbase = static_cast<const T*>(p.S) + col;
+    for (int64_t e0 = eb; e0 < ee; e0 += 64) {
+        const int64_t left = ee - e0;
+        const int cnt = left < 64 ? (int)left : 64;
+        const int my = lane < cnt ? p.indices[e0 + lane] : 0;
+        float myc = 1.f;
+        if (MODE == MODE_GCN) myc = lane < cnt ? p.rs_out[my] : 0.f;
+        for (int j = 0; j < cnt; j += NSUB * UNROLL) {
+            Raw raw[UNROLL];
+            float c[UNROLL];
+            int64_t off[UNROLL];
+            bool ok[UNROLL];
+#pragma unroll
+            for (int t = 0; t < UNROLL; ++t) {
+                const int k = j + t * NSUB + sub;
+                ok[t] = k < cnt;
+                const int ks = ok[t] ? k : 0;
+                int u;
+                if (G == 64) {
+                    u = __builtin_amdgcn_readlane(my, ks);
+                    c[t] = (MODE == MODE_GCN) ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(myc), ks)) : 1.f;
+                } else {
+                    u = __shfl(my, ks, 64);
+                    c[t] = (MODE == MODE_GCN) ? __shfl(myc, ks, 64) : 1.f;
+                }
+                off[t] = (int64_t)u * p.ld_s;
+            }
+            if (col_ok) {
+#pragma unroll
+                for (int t = 0; t < UNROLL; ++t) raw[t] = *reinterpret_cast<const Raw*>(sbase + off[t]);
+            } else {
+#pragma unroll
+                for (int t = 0; t < UNROLL; ++t) raw[t] = Row<T>::zero();
+            }
+#pragma unroll
+            for (int t = 0; t < UNROLL; ++t) {
+                float f[VEC];
+                Row<T>::unpack(raw[t], f);
+                const float w = ok[t] ? c[t] : 0.f;
+                if (MODE == MODE_GCN) {
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) acc[i] = ok[t] ? fmaf(w, f[i], acc[i]) : acc[i];
+                } else {
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) acc[i] += ok[t] ? f[i] : 0.f;
+                }
+            }
+        }
+    }
+}
+
+template <int G, int VEC>
+__device__ __forceinline__ void combine_groups(float (&acc)[VEC]) {
+#pragma unroll
+    for (int off = G; off < 64; off <<= 1) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] += __shfl_xor(acc[i], off, 64);
+    }
+}
+
+// scale, self addend, bias, activation, store of one output element
+template <typename T>
+__device__ __forceinline__ void finish_store(const AggParams& p, int64_t v, int c, float sum, float scale) {
+    float val = sum * scale;
+    if (p.self) val += Row<T>::one(static_cast<const T*>(p.self) + v * p.ld_self + c);
+    if (p.bias) val += p.bias[c];
+    val = activate(val, p.act, p.act_slope);
+    const int64_t o = (v - p.out_row0) * p.ld_out + c;
+    if (p.out_bf16) static_cast<uint16_t*>(p.out)[o] = float_to_bf16(val);
+    else static_cast<float*>(p.out)[o] = val;
+}
+
+template <int MODE, typename IdxT>
+__device__ __forceinline__ float row_scale(const AggParams& p, int64_t v, IdxT deg) {
+    if (MODE == MODE_MEAN) return deg > 0 ? 1.0f / (float)deg : 0.f;
+    if (MODE == MODE_GCN) return p.rs_in[v];
+    return 1.f;
+}
+
+// Workgroup `bid` of the row part: kRowsPerWg destination rows, one wavefront per row at a time.
+template <typename T, typename IdxT, int G, int MODE>
+__device__ __forceinline__ void rows_tile(const AggParams& p, int64_t bid) {
+    constexpr int VEC = Row<T>::VEC;
+    constexpr int UNROLL = (G == 64) ? 8 : 4;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t tile = xcd_tile(bid);
+    if (tile >= p.n_tiles) return;
+    const IdxT* indptr = static_cast<const IdxT*>(p.indptr);
+    const int sub = lane / G, gl = lane % G;
+    const int64_t v0 = p.row_begin + tile * kRowsPerWg;
+    for (int r = wave; r < kRowsPerWg; r += kWaves) {
+        const int64_t v = v0 + r;
+        if (v >= p.row_end) break;
+        const IdxT eb = indptr[v], ee = indptr[v + 1];
+        const IdxT deg = ee - eb;
+        if (p.skip_hubs && deg > (IdxT)kHubDegree) continue;
+        const float scale = row_scale<MODE, IdxT>(p, v, deg);
+        for (int col0 = 0; col0 < p.width; col0 += G * VEC) {
+            float acc[VEC];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+            gather_range<T, G, MODE, UNROLL>(p, (int64_t)eb, (int64_t)ee, lane, col0, acc);
+            combine_groups<G, VEC>(acc);
+            const int c = col0 + gl * VEC;
+            if (sub == 0 && c < p.width) {
+                const bool plain = !p.self && !p.bias && p.act == DGI_ACT_NONE;
+                if (plain && p.out_vec_ok && c + VEC <= p.width) {
+                    const int64_t o = (v - p.out_row0) * p.ld_out + c;
+                    if (p.out_bf16) {
+                        uint32_t w[VEC / 2];
+#pragma unroll
+                        for (int i = 0; i < VEC / 2; ++i)
+                            w[i] = (uint32_t)float_to_bf16(acc[2 * i] * scale) | ((uint32_t)float_to_bf16(acc[2 * i + 1] * scale) << 16);
+#pragma unroll
+                        for (int i = 0; i < VEC / 2; i += 2)
+                            *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + o + 2 * i) = make_uint2(w[i], w[i + 1]);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < VEC; i += 4)
+                            *reinterpret_cast<float4*>(static_cast<float*>(p.out) + o + i) =
+                                make_float4(acc[i] * scale, acc[i + 1] * scale, acc[i + 2] * scale, acc[i + 3] * scale);
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i)
+                        if (c + i < p.width) finish_store<T>(p, v, c + i, acc[i], scale);
+                }
+            }
+        }
+    }
+}
+
+// One wavefront per kHubChunk-edge chunk of a hub row: fp32 partial row, no scale.
+template <typename T, typename IdxT, int G, int MODE>
+__device__ __forceinline__ void hub_chunk(const AggParams& p, int64_t block) {
+    constexpr int VEC = Row<T>::VEC;
+    constexpr int UNROLL = (G == 64) ? 8 : 4;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t qi = block * kWaves + wave;
+    if (qi >= p.n_chunks) return;
+    const int64_t q = p.chunk0 + qi;
+    int64_t lo = p.hub_begin, hi = p.hub_end;  // largest h in [lo,hi) with hub_chunk_ptr[h] <= q
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (p.hub_chunk_ptr[mid] <= q) lo = mid; else hi = mid;
+    }
+    const int64_t v = p.hub_rows[lo];
+    const IdxT* indptr = static_cast<const IdxT*>(p.indptr);
+    const int64_t rb = (int64_t)indptr[v], re = (int64_t)indptr[v + 1];
+    const int64_t eb = rb + (q - p.hub_chunk_ptr[lo]) * kHubChunk;
+    const int64_t ee = eb + kHubChunk < re ? eb + kHubChunk : re;
+    const int sub = lane / G, gl = lane % G;
+    for (int col0 = 0; col0 < p.width; col0 += G * VEC) {
+        float acc[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+        gather_range<T, G, MODE, UNROLL>(p, eb, ee, lane, col0, acc);
+        combine_groups<G, VEC>(acc);
+        const int c = col0 + gl * VEC;
+        if (sub == 0 && c < p.width) {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i)
+                if (c + i < p.wpad) p.partials[qi * p.wpad + c + i] = acc[i];
+        }
+    }
+}
+
+// The aggregation launch: the first hub_blocks workgroups take the hub chunks (the longest work items go
+// first), the rest take row tiles.
+template <typename T, typename IdxT, int G, int MODE>
+__global__ __launch_bounds__(kWaves * 64) void agg_kernel(AggParams p) {
+    const int64_t bid = blockIdx.x;
+    if (bid < p.hub_blocks) hub_chunk<T, IdxT, G, MODE>(p, bid);
+    else rows_tile<T, IdxT, G, MODE>(p, bid - p.hub_blocks);
+}
+
+// One wavefront per hub row: add its partial rows in chunk order, then the epilogue.
+template <typename T, typename IdxT, int MODE>
+__global__ __launch_bounds__(kWaves * 64) void agg_hub_reduce_kernel(AggParams p) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t h = p.hub_begin + (int64_t)blockIdx.x * kWaves + wave;
+    if (h >= p.hub_end) return;
+    const int64_t v = p.hub_rows[h];
+    const IdxT* indptr = static_cast<const IdxT*>(p.indptr);
+    const IdxT deg = indptr[v + 1] - indptr[v];
+    const float scale = row_scale<MODE, IdxT>(p, v, deg);
+    const int64_t q0 = p.hub_chunk_ptr[h] - p.chunk0, q1 = p.hub_chunk_ptr[h + 1] - p.chunk0;
+    for (int c = lane; c < p.width; c += 64) {
+        float s = 0.f;
+        for (int64_t q = q0; q < q1; ++q) s += p.partials[q * p.wpad + c];
+        finish_store<T>(p, v, c, s, scale);
+    }
+}
+
+// Fallback for layouts without 16-byte aligned rows: one wavefront per row, one element per lane.
+template <typename T, typename IdxT, int MODE>
+__global__ __launch_bounds__(kWaves * 64) void agg_rows_generic_kernel(AggParams p) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t v = p.row_begin + (int64_t)blockIdx.x * kWaves + wave;
+    if (v >= p.row_end) return;
+    const IdxT* indptr = static_cast<const IdxT*>(p.indptr);
+    const int64_t eb = (int64_t)indptr[v], ee = (int64_t)indptr[v + 1];
+    const float scale = row_scale<MODE, IdxT>(p, v, (IdxT)(ee - eb));
+    const T* S = static_cast<const T*>(p.S);
+    for (int c = lane; c < p.width; c += 64) {
+        float s = 0.f;
+        for (int64_t e = eb; e < ee; ++e) {
+            const int64_t u = p.indices[e];
+            const float w = (MODE == MODE_GCN) ? p.rs_out[u] : 1.f;
+            s = fmaf(w, Row<T>::one(S + u * p.ld_s + c), s);
+        }
+        finish_store<T>(p, v, c, s, scale);
+    }
+}
+
+template <typename T, typename IdxT, int G, int MODE>
+dgi_status_t launch_fast(const AggParams& p0, const dgi_graph* g, hipStream_t stream) {
+    AggParams p = p0;
+    const int64_t rows = p.row_end - p.row_begin;
+    p.n_tiles = (rows + kRowsPerWg - 1) / kRowsPerWg;
+    constexpr int64_t kGroup = (int64_t)kXcds * kXcdRun;
+    // hub rows inside the range
+    const auto& hr = g->h_hub_rows;
+    const int64_t hb = std::lower_bound(hr.begin(), hr.end(), p.row_begin) - hr.begin();
+    const int64_t he = std::lower_bound(hr.begin(), hr.end(), p.row_end) - hr.begin();
+    p.skip_hubs = (he > hb) ? 1 : 0;
+    p.hub_begin = hb;
+    p.hub_end = he;
+    if (p.skip_hubs) {
+        DGI_REQUIRE(p.partials != nullptr, DGI_ERR_INVALID_ARG, "hub rows in range but no partial buffer");
+        p.chunk0 = g->h_hub_chunk_ptr[hb];
+        p.n_chunks = g->h_hub_chunk_ptr[he] - p.chunk0;
+        p.hub_blocks = round_up((p.n_chunks + kWaves - 1) / kWaves, kGroup);
+    }
+    const int64_t grid = p.hub_blocks + round_up(p.n_tiles, kGroup);
+    DGI_REQUIRE(grid < (int64_t)1 << 31, DGI_ERR_INVALID_ARG, "row range too large for one launch");
+    hipLaunchKernelGGL((agg_kernel<T, IdxT, G, MODE>), dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
+    DGI_HIP(hipGetLastError());
+    return DGI_OK;
+}
+
+// Second stage for the hub rows of the range (no-op when there are none).
+template <typename T, typename IdxT, int MODE>
+dgi_status_t launch_hub_reduce(const AggParams& p0, const dgi_graph* g, hipStream_t stream) {
+    AggParams p = p0;
+    const auto& hr = g->h_hub_rows;
+    const int64_t hb = std::lower_bound(hr.begin(), hr.end(), p.row_begin) - hr.begin();
+    const int64_t he = std::lower_bound(hr.begin(), hr.end(), p.row_end) - hr.begin();
+    if (he <= hb) return DGI_OK;
+    p.hub_begin = hb;
+    p.hub_end = he;
+    p.chunk0 = g->h_hub_chunk_ptr[hb];
+    hipLaunchKernelGGL((agg_hub_reduce_kernel<T, IdxT, MODE>), dim3((unsigned)((he - hb + kWaves - 1) / kWaves)),
+                       dim3(kWaves * 64), 0, stream, p);
+    DGI_HIP(hipGetLastError());
+    return DGI_OK;
+}
+
+template <typename T, typename IdxT, int MODE>
+dgi_status_t dispatch_g(const AggParams& p, const dgi_graph* g, bool fast, int stage, hipStream_t stream) {
+    if (stage == 1) return fast ? launch_hub_reduce<T, IdxT, MODE>(p, g, stream) : DGI_OK;
+    if (!fast) {
+        const int64_t rows = p.row_end - p.row_begin;
+        hipLaunchKernelGGL((agg_rows_generic_kernel<T, IdxT, MODE>), dim3((unsigned)((rows + kWaves - 1) / kWaves)),
+                           dim3(kWaves * 64), 0, stream, p);
+        DGI_HIP(hipGetLastError());
+        return DGI_OK;
+    }
+    const int lanes = (p.width + Row<T>::VEC - 1) / Row<T>::VEC;
+    if (lanes <= 4) return launch_fast<T, IdxT, 4, MODE>(p, g, stream);
+    if (lanes <= 8) return launch_fast<T, IdxT, 8, MODE>(p, g, stream);
+    if (lanes <= 16) return launch_fast<T, IdxT, 16, MODE>(p, g, stream);
+    if (lanes <= 32) return launch_fast<T, IdxT, 32, MODE>(p, g, stream);
+    return launch_fast<T, IdxT, 64, MODE>(p, g, stream);
+}
+
+template <typename T, typename IdxT>
+dgi_status_t dispatch_mode(const AggParams& p, const dgi_graph* g, int mode, bool fast, int stage, hipStream_t stream) {
+    switch (mode) {
+        case MODE_SUM: return dispatch_g<T, IdxT, MODE_SUM>(p, g, fast, stage, stream);
+        case MODE_MEAN: return dispatch_g<T, IdxT, MODE_MEAN>(p, g, fast, stage, stream);
+        case MODE_GCN: return dispatch_g<T, IdxT, MODE_GCN>(p, g, fast, stage, stream);
+    }
+    set_error("unknown aggregation mode %d", mode);
+    return DGI_ERR_INVALID_ARG;
+}
+
+}  // namespace
+
+uint64_t agg_hub_partial_bytes(const dgi_graph* g, int64_t row_begin, int64_t row_end, int width) {
+    const auto& hr = g->h_hub_rows;
+    const int64_t hb = std::lower_bound(hr.begin(), hr.end(), row_begin) - hr.begin();
+    const int64_t he = std::lower_bound(hr.begin(), hr.end(), row_end) - hr.begin();
+    if (he <= hb) return 0;
+    const int64_t chunks = g->h_hub_chunk_ptr[he] - g->h_hub_chunk_ptr[hb];
+    return (uint64_t)chunks * (uint64_t)round_up(width, 8) * sizeof(float);
+}
+
+dgi_status_t launch_aggregate(const AggArgs& a, int stage, hipStream_t stream) {
+    if (a.row_end <= a.row_begin) return DGI_OK;
+    const dgi_graph* g = a.g;
+    DGI_REQUIRE(a.row_begin >= 0 && a.row_end <= g->N, DGI_ERR_INVALID_ARG, "aggregate: row range outside the graph");
+    DGI_REQUIRE(a.width > 0 && a.ld_s >= a.width && a.ld_out >= a.width, DGI_ERR_INVALID_ARG, "aggregate: bad width / ld");
+    AggParams p{};
+    p.indptr = g->d_indptr;
+    p.indices = g->d_indices;
+    p.rs_out = g->d_rs_out;
+    p.rs_in = g->d_rs_in;
+    p.S = a.S; p.ld_s = a.ld_s; p.width = a.width;
+    p.out = a.out; p.ld_out = a.ld_out; p.out_row0 = a.out_row0;
+    p.out_bf16 = a.out_dtype == DGI_BF16;
+    p.self = a.self; p.ld_self = a.ld_self;
+    p.bias = a.bias; p.act = a.act; p.act_slope = a.act_slope;
+    p.row_begin = a.row_begin; p.row_end = a.row_end;
+    p.partials = a.hub_partials;
+    p.hub_rows = g->d_hub_rows;
+    p.hub_chunk_ptr = g->d_hub_chunk_ptr;
+    p.wpad = (int)round_up(a.width, 8);
+    const int sbytes = a.s_dtype == DGI_BF16 ? 2 : 4, obytes = a.out_dtype == DGI_BF16 ? 2 : 4;
+    // fast path: every 16-byte lane load stays inside its (aligned) row
+    const bool fast = ((uintptr_t)a.S % 16 == 0) && ((a.ld_s * sbytes) % 16 == 0) &&
+                      (round_up(a.width, 16 / sbytes) <= a.ld_s);
+    p.out_vec_ok = ((uintptr_t)a.out % 16 == 0) && ((a.ld_out * obytes) % 16 == 0);
+    const bool i64 = g->itype == DGI_I64;
+    if (a.s_dtype == DGI_BF16) {
+        return i64 ? dispatch_mode<uint16_t, int64_t>(p, g, a.mode, fast, stage, stream)
+                   : dispatch_mode<uint16_t, int32_t>(p, g, a.mode, fast, stage, stream);
+    }
+    return i64 ? dispatch_mode<float, int64_t>(p, g, a.mode, fast, stage, stream)
+               : dispatch_mode<float, int32_t>(p, g, a.mode, fast, stage, stream);
+}
+
+}  // namespace dgi

@@ -1,0 +1,494 @@
+// C ABI entry points for one layer (dgi_layer_forward) and the whole layer-wise schedule (dgi_infer,
+// Algorithm 2 of the DGI paper), plus the host-side batch planner of Section 4.1.
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstring>
+#include <unordered_set>
+
+#include "dgi_internal.h"
+
+namespace dgi {
+
+static thread_local char g_error[512] = "";
+
+void set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+}
+
+namespace {
+
+int elem_bytes(int dtype) { return dtype == DGI_BF16 ? 2 : 4; }
+
+// How one layer is laid out and executed.
+struct LayerPlan {
+    bool transform_first = false;
+    bool gat = false;
+    bool has_self = false;
+    int E = 4;            // elements per 16 bytes of the feature dtype
+    int eb = 4;           // bytes per feature element
+    int K1p = 0;          // column of the packed weight where the second K block starts
+    int64_t ldw = 0;      // packed weight leading dimension (elements)
+    int w_rows = 0;       // packed weight rows (= GEMM output columns)
+    uint64_t wt_bytes = 0;
+    int mode = MODE_SUM;
+    // transform-first: Z = H Wt^T for all nodes
+    int z_cols = 0;       // GEMM output columns
+    int64_t z_ld = 0;
+    int z_neigh_col = 0;  // first column of the neighbour block in Z
+    int z_dtype = DGI_F32;
+    // aggregate-first: AGG tile of the batch
+    int64_t agg_ld = 0;
+};
+
+dgi_status_t validate_layer(const dgi_layer_t* L) {
+    DGI_REQUIRE(L != nullptr, DGI_ERR_INVALID_ARG, "layer is NULL");
+    DGI_REQUIRE(L->agg >= DGI_AGG_SUM && L->agg <= DGI_AGG_GAT, DGI_ERR_INVALID_ARG, "unknown aggregator %d", L->agg);
+    DGI_REQUIRE(L->act >= DGI_ACT_NONE && L->act <= DGI_ACT_LEAKY_RELU, DGI_ERR_INVALID_ARG, "unknown activation %d", L->act);
+    DGI_REQUIRE(L->in_dim > 0 && L->out_dim > 0, DGI_ERR_INVALID_ARG, "layer dims must be positive");
+    DGI_REQUIRE(L->W_neigh != nullptr, DGI_ERR_INVALID_ARG, "W_neigh is NULL");
+    DGI_REQUIRE((L->feat_dtype == DGI_F32 || L->feat_dtype == DGI_BF16) && (L->out_dtype == DGI_F32 || L->out_dtype == DGI_BF16),
+                DGI_ERR_INVALID_ARG, "unknown dtype");
+    DGI_REQUIRE(L->order >= DGI_ORDER_AUTO && L->order <= DGI_ORDER_TRANSFORM_FIRST, DGI_ERR_INVALID_ARG, "unknown order %d", L->order);
+    if (L->agg == DGI_AGG_GAT) {
+        DGI_REQUIRE(L->heads >= 1 && L->out_dim % L->heads == 0, DGI_ERR_INVALID_ARG, "GAT: out_dim must be heads*head_dim");
+        DGI_REQUIRE(L->attn_src && L->attn_dst, DGI_ERR_INVALID_ARG, "GAT: attention vectors are NULL");
+        DGI_REQUIRE(L->feat_dtype == DGI_F32, DGI_ERR_UNSUPPORTED, "GAT runs on fp32 features only");
+        DGI_REQUIRE(L->order != DGI_ORDER_AGG_FIRST, DGI_ERR_UNSUPPORTED, "GAT is transform-first by definition");
+    }
+    return DGI_OK;
+}
+
+dgi_status_t plan_layer(const dgi_layer_t* L, LayerPlan* P) {
+    DGI_TRY(validate_layer(L));
+    LayerPlan p;
+    p.eb = elem_bytes(L->feat_dtype);
+    p.E = 16 / p.eb;
+    p.gat = L->agg == DGI_AGG_GAT;
+    p.has_self = (L->agg == DGI_AGG_SUM || L->agg == DGI_AGG_MEAN) && L->W_self != nullptr;
+    p.mode = L->agg == DGI_AGG_MEAN ? MODE_MEAN : L->agg == DGI_AGG_GCN ? MODE_GCN : MODE_SUM;
+    p.transform_first = p.gat || L->order == DGI_ORDER_TRANSFORM_FIRST ||
+                        (L->order == DGI_ORDER_AUTO && L->out_dim < L->in_dim);
+    const int in_p = (int)round_up(L->in_dim, p.E);
+    if (p.gat) {
+        p.K1p = in_p; p.ldw = in_p;
+        p.w_rows = L->out_dim + 2 * L->heads;
+        p.z_cols = p.w_rows; p.z_ld = round_up(p.z_cols, 4); p.z_neigh_col = 0; p.z_dtype = DGI_F32;
+    } else if (p.transform_first) {
+        p.K1p = in_p; p.ldw = in_p;
+        p.z_neigh_col = p.has_self ? (int)round_up(L->out_dim, p.E) : 0;
+        p.w_rows = p.z_neigh_col + L->out_dim;
+        p.z_cols = p.w_rows; p.z_ld = round_up(p.z_cols, p.E); p.z_dtype = L->feat_dtype;
+    } else {
+        p.K1p = p.has_self ? in_p : 0;
+        p.ldw = p.K1p + in_p;
+        p.w_rows = L->out_dim;
+        p.agg_ld = in_p;
+    }
+    p.wt_bytes = (uint64_t)round_up((int64_t)p.w_rows * p.ldw * p.eb, 256);
+    *P = p;
+    return DGI_OK;
+}
+
+// Packed, transposed weights for the layer's GEMM (zero padded).
+dgi_status_t prepare_weights(const dgi_layer_t* L, const LayerPlan& P, void* Wt, hipStream_t s) {
+    DGI_TRY(launch_fill_zero(Wt, P.wt_bytes, s));
+    if (P.gat) {
+        DGI_TRY(launch_pack_weight(L->W_neigh, L->feat_dtype, L->in_dim, L->out_dim, Wt, P.ldw, 0, s));
+        return launch_pack_gat_attn((const float*)L->W_neigh, L->in_dim, L->heads, L->out_dim / L->heads, L->attn_src,
+                                    L->attn_dst, (float*)Wt, P.ldw, s);
+    }
+    if (P.transform_first) {
+        if (P.has_self) DGI_TRY(launch_pack_weight(L->W_self, L->feat_dtype, L->in_dim, L->out_dim, Wt, P.ldw, 0, s));
+        char* neigh = (char*)Wt + (int64_t)P.z_neigh_col * P.ldw * P.eb;
+        return launch_pack_weight(L->W_neigh, L->feat_dtype, L->in_dim, L->out_dim, neigh, P.ldw, 0, s);
+    }
+    if (P.has_self) DGI_TRY(launch_pack_weight(L->W_self, L->feat_dtype, L->in_dim, L->out_dim, Wt, P.ldw, 0, s));
+    return launch_pack_weight(L->W_neigh, L->feat_dtype, L->in_dim, L->out_dim, Wt, P.ldw, P.K1p, s);
+}
+
+// Transform-first: Z[r,:] = H[r,:] Wt^T for rows [r0,r1) of the graph.
+dgi_status_t run_transform(const dgi_layer_t* L, const LayerPlan& P, const void* h_in, int64_t ld_in, const void* Wt,
+                           void* Z, int64_t r0, int64_t r1, hipStream_t s) {
+    GemmArgs ga;
+    ga.dtype = L->feat_dtype;
+    ga.A1 = (const char*)h_in + r0 * ld_in * P.eb; ga.ld_a1 = ld_in; ga.K1 = L->in_dim;
+    ga.Wt = Wt; ga.ldw = P.ldw; ga.K1p = P.K1p;
+    ga.Y = (char*)Z + r0 * P.z_ld * elem_bytes(P.z_dtype); ga.ld_y = P.z_ld; ga.out_dtype = P.z_dtype;
+    ga.M = r1 - r0; ga.Nout = P.z_cols;
+    return launch_gemm(ga, s);
+}
+
+uint64_t batch_temp_bytes(const dgi_graph* g, const dgi_layer_t* L, const LayerPlan& P, int64_t b, int64_t e) {
+    uint64_t bytes = 0;
+    if (!P.gat) bytes += round_up((int64_t)agg_hub_partial_bytes(g, b, e, P.transform_first ? L->out_dim : L->in_dim), 256);
+    if (!P.transform_first) bytes += (uint64_t)round_up((e - b) * P.agg_ld * P.eb, 256);
+    return bytes;
+}
+
+struct KernelTimer;  // defined below
+
+// One batch of destination rows [b,e): the body of the inner loop of Algorithm 2.
+dgi_status_t run_batch(const dgi_graph* g, const dgi_layer_t* L, const LayerPlan& P, const void* h_in, int64_t ld_in,
+                       void* h_out, int64_t ld_out, int64_t b, int64_t e, const void* Wt, const void* Z, void* temp,
+                       hipStream_t s, KernelTimer* timer);
+
+// HIP-event timing of kernel classes on the caller's stream.
+struct KernelTimer {
+    struct Span { hipEvent_t a, b; int layer; int kind; };
+    std::vector<Span> spans;
+    hipStream_t stream;
+    int layer = 0;
+    explicit KernelTimer(hipStream_t s) : stream(s) {}
+    ~KernelTimer() { for (auto& sp : spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); } }
+    dgi_status_t begin(int kind) {
+        Span sp{nullptr, nullptr, layer, kind};
+        DGI_HIP(hipEventCreate(&sp.a));
+        DGI_HIP(hipEventCreate(&sp.b));
+        spans.push_back(sp);
+        DGI_HIP(hipEventRecord(sp.a, stream));
+        return DGI_OK;
+    }
+    dgi_status_t end() { DGI_HIP(hipEventRecord(spans.back().b, stream)); return DGI_OK; }
+};
+enum { SPAN_AGG = 0, SPAN_GEMM = 1, SPAN_LAYER = 2, SPAN_TOTAL = 3 };
+
+dgi_status_t run_batch(const dgi_graph* g, const dgi_layer_t* L, const LayerPlan& P, const void* h_in, int64_t ld_in,
+                       void* h_out, int64_t ld_out, int64_t b, int64_t e, const void* Wt, const void* Z, void* temp,
+                       hipStream_t s, KernelTimer* timer) {
+    if (e <= b) return DGI_OK;
+    const int ob = elem_bytes(L->out_dtype);
+    if (P.gat) {
+        GatArgs a;
+        a.g = g; a.Zx = (const float*)Z; a.ld_z = P.z_ld; a.heads = L->heads; a.head_dim = L->out_dim / L->heads;
+        a.attn_slope = L->attn_slope;
+        a.out = (char*)h_out + b * ld_out * ob; a.ld_out = ld_out; a.out_row0 = b; a.out_dtype = L->out_dtype;
+        a.bias = L->bias; a.act = L->act; a.act_slope = L->act_slope; a.row_begin = b; a.row_end = e;
+        if (timer) DGI_TRY(timer->begin(SPAN_AGG));
+        DGI_TRY(launch_gat(a, s));
+        if (timer) DGI_TRY(timer->end());
+        return DGI_OK;
+    }
+    const uint64_t part_bytes = round_up((int64_t)agg_hub_partial_bytes(g, b, e, P.transform_first ? L->out_dim : L->in_dim), 256);
+    AggArgs a;
+    a.g = g; a.mode = P.mode; a.row_begin = b; a.row_end = e;
+    a.hub_partials = part_bytes ? (float*)temp : nullptr;
+    if (P.transform_first) {
+        const int zb = elem_bytes(P.z_dtype);
+        a.S = (const char*)Z + (int64_t)P.z_neigh_col * zb; a.ld_s = P.z_ld; a.s_dtype = P.z_dtype; a.width = L->out_dim;
+        a.self = P.has_self ? Z : nullptr; a.ld_self = P.z_ld;
+        a.out = (char*)h_out + b * ld_out * ob; a.ld_out = ld_out; a.out_row0 = b; a.out_dtype = L->out_dtype;
+        a.bias = L->bias; a.act = L->act; a.act_slope = L->act_slope;
+        if (timer) DGI_TRY(timer->begin(SPAN_AGG));
+        DGI_TRY(launch_aggregate(a, 0, s));
+        if (timer) DGI_TRY(timer->end());
+        return launch_aggregate(a, 1, s);
+    }
+    void* agg = (char*)temp + part_bytes;
+    a.S = h_in; a.ld_s = ld_in; a.s_dtype = L->feat_dtype; a.width = L->in_dim;
+    a.out = agg; a.ld_out = P.agg_ld; a.out_row0 = b; a.out_dtype = L->feat_dtype;
+    if (timer) DGI_TRY(timer->begin(SPAN_AGG));
+    DGI_TRY(launch_aggregate(a, 0, s));
+    if (timer) DGI_TRY(timer->end());
+    DGI_TRY(launch_aggregate(a, 1, s));
+    GemmArgs ga;
+    ga.dtype = L->feat_dtype;
+    if (P.has_self) {
+        ga.A1 = (const char*)h_in + b * ld_in * P.eb; ga.ld_a1 = ld_in; ga.K1 = L->in_dim;
+        ga.A2 = agg; ga.ld_a2 = P.agg_ld; ga.K2 = L->in_dim;
+    } else {
+        ga.A1 = agg; ga.ld_a1 = P.agg_ld; ga.K1 = L->in_dim;
+    }
+    ga.Wt = Wt; ga.ldw = P.ldw; ga.K1p = P.K1p;
+    ga.bias = L->bias; ga.act = L->act; ga.act_slope = L->act_slope;
+    ga.Y = (char*)h_out + b * ld_out * ob; ga.ld_y = ld_out; ga.out_dtype = L->out_dtype;
+    ga.M = e - b; ga.Nout = L->out_dim;
+    if (timer) DGI_TRY(timer->begin(SPAN_GEMM));
+    DGI_TRY(launch_gemm(ga, s));
+    if (timer) DGI_TRY(timer->end());
+    return DGI_OK;
+}
+
+// Workspace of dgi_layer_forward: [ packed weights | Z (transform-first, all N rows) | batch temporaries ]
+struct ForwardLayout { uint64_t wt_off, z_off, temp_off, total; };
+ForwardLayout forward_layout(const dgi_graph* g, const dgi_layer_t* L, const LayerPlan& P, int64_t b, int64_t e) {
+    ForwardLayout f{};
+    f.wt_off = 0;
+    f.z_off = P.wt_bytes;
+    const uint64_t zbytes = P.transform_first ? (uint64_t)round_up(g->N * P.z_ld * elem_bytes(P.z_dtype), 256) : 0;
+    f.temp_off = f.z_off + zbytes;
+    f.total = f.temp_off + batch_temp_bytes(g, L, P, b, e) + 256;
+    return f;
+}
+
+dgi_status_t check_matrix(const void* p, int64_t ld, int dim, const char* what) {
+    DGI_REQUIRE(p != nullptr, DGI_ERR_INVALID_ARG, "%s is NULL", what);
+    DGI_REQUIRE(ld >= dim, DGI_ERR_INVALID_ARG, "%s: leading dimension %lld < width %d", what, (long long)ld, dim);
+    return DGI_OK;
+}
+
+}  // namespace
+}  // namespace dgi
+
+using namespace dgi;
+
+extern "C" const char* dgi_last_error(void) { return dgi::g_error; }
+extern "C" int32_t dgi_version(void) { return DGI_VERSION_MAJOR * 1000 + DGI_VERSION_MINOR; }
+extern "C" const char* dgi_status_string(dgi_status_t s) {
+    switch (s) {
+        case DGI_OK: return "ok";
+        case DGI_ERR_INVALID_ARG: return "invalid argument";
+        case DGI_ERR_BAD_GRAPH: return "malformed graph";
+        case DGI_ERR_UNSUPPORTED: return "unsupported combination";
+        case DGI_ERR_OOM: return "out of device memory";
+        case DGI_ERR_DEVICE: return "device error";
+    }
+    return "unknown status";
+}
+
+extern "C" dgi_status_t dgi_layer_workspace_bytes(const dgi_graph_t* g, const dgi_layer_t* layer, int64_t dst_begin,
+                                                  int64_t dst_end, uint64_t* bytes) {
+    DGI_REQUIRE(g && bytes, DGI_ERR_INVALID_ARG, "layer_workspace_bytes: NULL argument");
+    DGI_REQUIRE(dst_begin >= 0 && dst_end >= dst_begin && dst_end <= g->N, DGI_ERR_INVALID_ARG, "bad destination range");
+    LayerPlan P;
+    DGI_TRY(plan_layer(layer, &P));
+    *bytes = forward_layout(g, layer, P, dst_begin, dst_end).total;
+    return DGI_OK;
+}
+
+extern "C" dgi_status_t dgi_layer_forward(const dgi_graph_t* g, const dgi_layer_t* layer, const void* h_in, int64_t ld_in,
+                                          void* h_out, int64_t ld_out, int64_t dst_begin, int64_t dst_end, void* workspace,
+                                          uint64_t workspace_bytes, void* hip_stream) {
+    DGI_REQUIRE(g != nullptr, DGI_ERR_INVALID_ARG, "graph is NULL");
+    LayerPlan P;
+    DGI_TRY(plan_layer(layer, &P));
+    DGI_REQUIRE(dst_begin >= 0 && dst_end >= dst_begin && dst_end <= g->N, DGI_ERR_INVALID_ARG,
+                "bad destination range [%lld,%lld) for %lld nodes", (long long)dst_begin, (long long)dst_end, (long long)g->N);
+    if (g->N == 0 || dst_end == dst_begin) return DGI_OK;
+    DGI_TRY(check_matrix(h_in, ld_in, layer->in_dim, "h_in"));
+    DGI_TRY(check_matrix(h_out, ld_out, layer->out_dim, "h_out"));
+    const ForwardLayout f = forward_layout(g, layer, P, dst_begin, dst_end);
+    DGI_REQUIRE(workspace != nullptr && workspace_bytes >= f.total, DGI_ERR_INVALID_ARG,
+                "workspace too small: %llu bytes given, %llu needed", (unsigned long long)workspace_bytes, (unsigned long long)f.total);
+    DGI_REQUIRE((uintptr_t)workspace % 256 == 0, DGI_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    char* ws = static_cast<char*>(workspace);
+    DGI_TRY(prepare_weights(layer, P, ws + f.wt_off, s));
+    if (P.transform_first) DGI_TRY(run_transform(layer, P, h_in, ld_in, ws + f.wt_off, ws + f.z_off, 0, g->N, s));
+    return run_batch(g, layer, P, h_in, ld_in, h_out, ld_out, dst_begin, dst_end, ws + f.wt_off, ws + f.z_off, ws + f.temp_off, s, nullptr);
+}
+
+extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layers, int32_t num_layers, const void* x,
+                                  int64_t ld_x, void* out, int64_t ld_out, const dgi_infer_opts_t* opts, void* hip_stream) {
+    DGI_REQUIRE(g != nullptr && layers != nullptr, DGI_ERR_INVALID_ARG, "infer: NULL argument");
+    DGI_REQUIRE(num_layers >= 1 && num_layers <= DGI_MAX_LAYERS, DGI_ERR_INVALID_ARG, "infer: 1..%d layers supported", DGI_MAX_LAYERS);
+    std::vector<LayerPlan> plans((size_t)num_layers);
+    for (int l = 0; l < num_layers; ++l) {
+        DGI_TRY(plan_layer(&layers[l], &plans[l]));
+        if (l > 0) {
+            DGI_REQUIRE(layers[l].in_dim == layers[l - 1].out_dim, DGI_ERR_INVALID_ARG, "layer %d: in_dim != previous out_dim", l);
+            DGI_REQUIRE(layers[l].feat_dtype == layers[l - 1].out_dtype, DGI_ERR_INVALID_ARG, "layer %d: feat_dtype != previous out_dtype", l);
+        }
+    }
+    dgi_infer_opts_t o{};
+    if (opts) o = *opts;
+    DGI_REQUIRE(o.batch_size >= 0, DGI_ERR_INVALID_ARG, "infer: negative batch_size");
+    if (o.stats) { std::memset(o.stats, 0, sizeof(dgi_stats_t)); o.stats->num_layers = num_layers; }
+    const int64_t N = g->N;
+    if (N == 0) return DGI_OK;
+    const dgi_layer_t& L0 = layers[0];
+    const dgi_layer_t& LL = layers[num_layers - 1];
+    DGI_TRY(check_matrix(x, ld_x, L0.in_dim, "x"));
+    DGI_TRY(check_matrix(out, ld_out, LL.out_dim, "out"));
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+    // ---- memory plan -------------------------------------------------------------------------------
+    uint64_t budget = o.mem_budget_bytes;
+    if (budget == 0) {
+        size_t free_b = 0, total_b = 0;
+        DGI_HIP(hipMemGetInfo(&free_b, &total_b));
+        budget = (uint64_t)(0.9 * (double)free_b);
+    }
+    uint64_t hidden_bytes = 0;  // one ping-pong buffer
+    for (int l = 0; l + 1 < num_layers; ++l) {
+        const int eb = elem_bytes(layers[l].out_dtype);
+        hidden_bytes = std::max<uint64_t>(hidden_bytes, (uint64_t)round_up(N * round_up(layers[l].out_dim, 16 / eb) * eb, 256));
+    }
+    const int n_hidden = num_layers >= 3 ? 2 : (num_layers == 2 ? 1 : 0);
+    const bool permuted = o.perm_new_of_old != nullptr;
+    const int xb = elem_bytes(L0.feat_dtype), yb = elem_bytes(LL.out_dtype);
+    const int64_t ld_xp = round_up(L0.in_dim, 16 / xb), ld_yp = round_up(LL.out_dim, 16 / yb);
+    const uint64_t xp_bytes = permuted ? (uint64_t)round_up(N * ld_xp * xb, 256) : 0;
+    const uint64_t yp_bytes = permuted ? (uint64_t)round_up(N * ld_yp * yb, 256) : 0;
+    uint64_t fixed_max = 0, temp_full_max = 0;
+    for (int l = 0; l < num_layers; ++l) {
+        const LayerPlan& P = plans[l];
+        uint64_t fixed = P.wt_bytes;
+        if (P.transform_first) fixed += (uint64_t)round_up(N * P.z_ld * elem_bytes(P.z_dtype), 256);
+        fixed_max = std::max(fixed_max, fixed);
+        temp_full_max = std::max(temp_full_max, batch_temp_bytes(g, &layers[l], P, 0, N));
+    }
+    const uint64_t persistent = hidden_bytes * n_hidden + xp_bytes + yp_bytes + fixed_max;
+    DGI_REQUIRE(budget > persistent + 4096, DGI_ERR_OOM,
+                "memory budget %llu bytes cannot hold the hidden layers and per-layer buffers (%llu bytes)",
+                (unsigned long long)budget, (unsigned long long)persistent);
+    // Expected consumption M of Eq. 2 for the batch temporaries: what is left of the budget (the budget is
+    // already 90 % of free memory when it was not given), but no more than one whole-graph batch needs.
+    const uint64_t temp_cap = std::max<uint64_t>(std::min<uint64_t>(budget - persistent, temp_full_max), 256);
+
+    char* arena = nullptr;
+    const uint64_t arena_bytes = persistent + temp_cap + 1024;
+    DGI_HIP(hipMalloc(reinterpret_cast<void**>(&arena), arena_bytes));
+    struct Free { char* p; ~Free() { (void)hipFree(p); } } arena_guard{arena};
+    uint64_t off = 0;
+    auto carve = [&](uint64_t bytes) { char* p = arena + off; off += (uint64_t)round_up((int64_t)bytes, 256); return p; };
+    char* hid[2] = {nullptr, nullptr};
+    for (int i = 0; i < n_hidden; ++i) hid[i] = carve(hidden_bytes);
+    char* xp = permuted ? carve(xp_bytes) : nullptr;
+    char* yp = permuted ? carve(yp_bytes) : nullptr;
+    char* fixed = carve(fixed_max);
+    char* temp = carve(temp_cap);
+    if (o.stats) o.stats->workspace_bytes = (int64_t)arena_bytes;
+
+    KernelTimer timer(s);
+    KernelTimer* tm = o.stats ? &timer : nullptr;
+    if (tm) { tm->layer = -1; DGI_TRY(tm->begin(SPAN_TOTAL)); }
+
+    const void* cur = x;
+    int64_t ld_cur = ld_x;
+    if (permuted) {  // rows to the reordered numbering: xp[perm[r]] = x[r]
+        DGI_TRY(launch_permute_rows(x, ld_x, xp, ld_xp, N, L0.in_dim, xb, o.perm_new_of_old, false, s));
+        cur = xp; ld_cur = ld_xp;
+    }
+    const double avg_deg = N > 0 ? (double)g->E / (double)N : 0.0;
+    for (int l = 0; l < num_layers; ++l) {
+        const dgi_layer_t& L = layers[l];
+        const LayerPlan& P = plans[l];
+        const bool last = l == num_layers - 1;
+        void* dst; int64_t ld_dst;
+        if (last) { dst = permuted ? (void*)yp : out; ld_dst = permuted ? ld_yp : ld_out; }
+        else { dst = hid[l % 2]; ld_dst = round_up(L.out_dim, 16 / elem_bytes(L.out_dtype)); }
+        if (tm) { tm->layer = l; DGI_TRY(tm->begin(SPAN_LAYER)); }
+        const size_t layer_span = tm ? tm->spans.size() - 1 : 0;
+        char* Wt = fixed;
+        char* Z = fixed + P.wt_bytes;
+        DGI_TRY(prepare_weights(&L, P, Wt, s));
+        if (P.transform_first) {
+            if (tm) DGI_TRY(tm->begin(SPAN_GEMM));
+            DGI_TRY(run_transform(&L, P, cur, ld_cur, Wt, Z, 0, N, s));
+            if (tm) DGI_TRY(tm->end());
+        }
+        // ---- batches of destination rows (Section 4.1) ----------------------------------------------
+        int64_t n_t = o.batch_size > 0 ? o.batch_size : (o.init_node_threshold > 0 ? o.init_node_threshold : 65536);
+        int64_t n_i = o.batch_size > 0 ? INT64_MAX / 4
+                                       : (o.init_edge_threshold > 0 ? o.init_edge_threshold : (int64_t)std::max(1.0, (double)n_t * std::max(avg_deg, 1.0)));
+        int64_t b = 0, batches = 0;
+        while (b < N) {
+            int64_t e = 0;
+            DGI_TRY(dgi_plan_batch_end(g->h_indptr.data(), DGI_I64, N, b, std::max<int64_t>(n_t, 1), std::max<int64_t>(n_i, 0), &e));
+            const uint64_t need = batch_temp_bytes(g, &L, P, b, e);
+            if (need > temp_cap) {  // the batch would not fit: the out-of-memory reaction of Section 4.1
+                if (o.stats) o.stats->oom_retries += 1;
+                dgi_status_t hs = dgi_threshold_halve(&n_t, &n_i);
+                if (hs != DGI_OK || e - b <= 1) {
+                    set_error("layer %d: a single destination row needs %llu bytes of temporaries, budget leaves %llu", l,
+                              (unsigned long long)need, (unsigned long long)temp_cap);
+                    return DGI_ERR_OOM;
+                }
+                n_t = std::min(n_t, std::max<int64_t>((e - b) / 2, 1));
+                continue;
+            }
+            DGI_TRY(run_batch(g, &L, P, cur, ld_cur, dst, ld_dst, b, e, Wt, Z, temp, s, tm));
+            ++batches;
+            if (o.batch_size == 0) {
+                if (need == 0) { n_t = N; n_i = std::max<int64_t>(g->E, 1); }  // nothing to bound
+                else DGI_TRY(dgi_threshold_update((double)temp_cap, (double)need, &n_t, &n_i));
+            }
+            b = e;
+        }
+        if (tm) { DGI_HIP(hipEventRecord(tm->spans[layer_span].b, s)); }
+        if (o.stats) {
+            o.stats->batches[l] = batches;
+            o.stats->edges[l] = g->E;
+            o.stats->transform_first[l] = P.transform_first ? 1 : 0;
+            o.stats->gather_width[l] = P.gat ? (int)P.z_ld : (P.transform_first ? L.out_dim : L.in_dim);
+        }
+        cur = dst; ld_cur = ld_dst;  // H^{l-1} is dead from here on: its buffer is the next layer's output
+    }
+    if (permuted)  // back to the caller's numbering: out[r] = yp[perm[r]]
+        DGI_TRY(launch_permute_rows(yp, ld_yp, out, ld_out, N, LL.out_dim, yb, o.perm_new_of_old, true, s));
+    if (tm) DGI_HIP(hipEventRecord(tm->spans[0].b, s));
+    DGI_HIP(hipStreamSynchronize(s));
+    if (o.stats) {
+        for (const auto& sp : timer.spans) {
+            float ms = 0.f;
+            DGI_HIP(hipEventElapsedTime(&ms, sp.a, sp.b));
+            if (sp.kind == SPAN_TOTAL) o.stats->total_ms = ms;
+            else if (sp.kind == SPAN_LAYER) o.stats->layer_ms[sp.layer] = ms;
+            else if (sp.kind == SPAN_AGG) { o.stats->agg_ms[sp.layer] += ms; o.stats->agg_launches[sp.layer] += 1; }
+            else if (sp.kind == SPAN_GEMM) { o.stats->gemm_ms[sp.layer] += ms; o.stats->gemm_launches[sp.layer] += 1; }
+        }
+    }
+    return DGI_OK;
+}
+
+// ---- host-side planning helpers ---------------------------------------------------------------------
+extern "C" dgi_status_t dgi_plan_batch_end(const void* indptr, int32_t indptr_type, int64_t row_limit, int64_t begin,
+                                           int64_t n_t, int64_t n_i, int64_t* end) {
+    DGI_REQUIRE(indptr && end, DGI_ERR_INVALID_ARG, "plan_batch_end: NULL argument");
+    DGI_REQUIRE(begin >= 0 && begin < row_limit, DGI_ERR_INVALID_ARG, "plan_batch_end: begin outside [0,row_limit)");
+    DGI_REQUIRE(n_t >= 1 && n_i >= 0, DGI_ERR_INVALID_ARG, "plan_batch_end: thresholds must be positive");
+    auto at = [&](int64_t i) { return indptr_type == DGI_I64 ? ((const int64_t*)indptr)[i] : (int64_t)((const int32_t*)indptr)[i]; };
+    const int64_t hi_lim = std::min(row_limit, begin + n_t);
+    const int64_t cap = at(begin) + n_i;
+    // binary search on the in-degree prefix sum: largest end in [begin+1, hi_lim] with at(end) <= cap
+    int64_t lo = begin + 1, hi = hi_lim;
+    if (at(lo) > cap) { *end = lo; return DGI_OK; }  // one row alone exceeds n_i: it forms a batch by itself
+    while (lo < hi) {
+        const int64_t mid = lo + (hi - lo + 1) / 2;
+        if (at(mid) <= cap) lo = mid; else hi = mid - 1;
+    }
+    *end = lo;
+    return DGI_OK;
+}
+
+extern "C" dgi_status_t dgi_threshold_update(double M_expected, double M_k, int64_t* n_t, int64_t* n_i) {
+    DGI_REQUIRE(n_t && n_i, DGI_ERR_INVALID_ARG, "threshold_update: NULL argument");
+    if (!(M_k > 0.0) || !(M_expected > 0.0)) return DGI_OK;
+    const double r = M_expected / M_k;
+    auto scale = [&](int64_t v) {
+        const double x = std::floor(r * (double)v);
+        if (x < 1.0) return (int64_t)1;
+        if (x > 4.0e18) return (int64_t)4000000000000000000ll;
+        return (int64_t)x;
+    };
+    *n_t = scale(*n_t);
+    *n_i = scale(*n_i);
+    return DGI_OK;
+}
+
+extern "C" dgi_status_t dgi_threshold_halve(int64_t* n_t, int64_t* n_i) {
+    DGI_REQUIRE(n_t && n_i, DGI_ERR_INVALID_ARG, "threshold_halve: NULL argument");
+    if (*n_t <= 1 && *n_i <= 1) { set_error("thresholds cannot be halved below one"); return DGI_ERR_OOM; }
+    *n_t = std::max<int64_t>(*n_t / 2, 1);
+    *n_i = std::max<int64_t>(*n_i / 2, 1);
+    return DGI_OK;
+}
+
+extern "C" dgi_status_t dgi_batch_input_set_size(int64_t num_nodes, const int64_t* indptr, const int32_t* indices,
+                                                 int64_t begin, int64_t end, int64_t* count) {
+    DGI_REQUIRE(indptr && count && (indices || indptr[num_nodes] == 0), DGI_ERR_INVALID_ARG, "batch_input_set_size: NULL argument");
+    DGI_REQUIRE(begin >= 0 && end >= begin && end <= num_nodes, DGI_ERR_INVALID_ARG, "batch_input_set_size: bad range");
+    std::unordered_set<int32_t> seen;
+    for (int64_t e = indptr[begin]; e < indptr[end]; ++e) seen.insert(indices[e]);
+    *count = (int64_t)seen.size();
+    return DGI_OK;
+}
+
+extern "C" dgi_status_t dgi_reorder_permutation(int64_t num_nodes, const int64_t* indptr, const int32_t* indices,
+                                                int32_t method, uint64_t seed, int32_t* perm_new_of_old) {
+    return reorder_permutation(num_nodes, indptr, indices, method, seed, perm_new_of_old);
+}

@@ -1,0 +1,314 @@
+// Dense transform of a layer (the w^l part of Eq. 1) on the MFMA matrix cores, with the bias and the
+// activation fused into the epilogue so they run once per node in the producing layer.
+//
+//   Y[r, n] = act( sum_k A1[r,k] Wt[n,k] + sum_k A2[r,k] Wt[n,K1p+k] + bias[n] )
+//
+// A1|A2 is the row-wise concatenation [h_v | m_v] of GraphSAGE (A2 may be absent); Wt is the weight
+// packed transposed, [Nout x ldw] with K contiguous, so both MFMA operands are read from LDS rows of
+// the same shape.  fp32 data uses v_mfma_f32_32x32x2_f32, bf16 data v_mfma_f32_32x32x16_bf16, both with
+// fp32 accumulators.  A workgroup of 4 wavefronts owns a BM x BN output tile; each k-step stages a
+// 128-byte slab of every tile row in LDS (global -> registers -> LDS, the next slab's global loads are
+// in flight while the current one is multiplied).  LDS rows are padded by 16 bytes so that the 16-byte
+// fragment reads of 8 consecutive lanes cover all banks.
+#include "dgi_internal.h"
+
+namespace dgi {
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+struct GemmParams {
+    const void* A1; int64_t ld_a1; int K1; int a1_vec;
+    const void* A2; int64_t ld_a2; int K2; int a2_vec;
+    const void* Wt; int64_t ldw; int K1p;
+    const float* bias;
+    int act; float act_slope;
+    void* Y; int64_t ld_y; int out_bf16;
+    int64_t M; int Nout;
+    int tiles_n;
+};
+
+__device__ __forceinline__ uint16_t f2bf(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float act_fn(float x, int act, float slope) {
+    switch (act) {
+        case DGI_ACT_RELU: return x > 0.f ? x : 0.f;
+        case DGI_ACT_ELU: return x > 0.f ? x : slope * expm1f(x);
+        case DGI_ACT_LEAKY_RELU: return x > 0.f ? x : slope * x;
+        default: return x;
+    }
+}
+
+// 16 bytes of row `row` starting at element k of a [rows x K] matrix; zero outside [0,rows) x [0,K).
+template <typename T>
+__device__ __forceinline__ uint4 load_chunk(const T* base, int64_t ld, int64_t row, int64_t rows, int k, int K, bool vec_ok) {
+    constexpr int E = 16 / sizeof(T);
+    uint4 z = make_uint4(0u, 0u, 0u, 0u);
+    if (row >= rows || k >= K) return z;
+    const T* p = base + row * ld + k;
+    if (vec_ok && k + E <= K) return *reinterpret_cast<const uint4*>(p);
+    alignas(16) T tmp[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) tmp[e] = (k + e < K) ? p[e] : T(0);
+    return *reinterpret_cast<uint4*>(tmp);
+}
+
+template <typename T, int WGM, int WGN, int TM, int TN>
+__global__ __launch_bounds__(256) void gemm_kernel(GemmParams p) {
+    constexpr int E = 16 / sizeof(T);      // elements per 16-byte chunk
+    constexpr int BK = 8 * E;              // 128 bytes of K per step
+    constexpr int LDS_LD = BK + E;         // padded row, in elements
+    constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
+    constexpr int A_CHUNKS = BM * 8 / 256, B_CHUNKS = BN * 8 / 256;
+    static_assert(WGM * WGN == 4, "4 wavefronts per workgroup");
+    __shared__ __attribute__((aligned(16))) T As[BM * LDS_LD];
+    __shared__ __attribute__((aligned(16))) T Bs[BN * LDS_LD];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int64_t tile_m = blockIdx.x / p.tiles_n;
+    const int tile_n = blockIdx.x % p.tiles_n;
+    const int64_t m0 = tile_m * BM;
+    const int n0 = tile_n * BN;
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int S1 = (p.K1 + BK - 1) / BK;
+    const int S2 = p.A2 ? (p.K2 + BK - 1) / BK : 0;
+    const int S = S1 + S2;
+    uint4 ra[A_CHUNKS], rb[B_CHUNKS];
+
+    auto load_step = [&](int s) {
+        const bool second = s >= S1;
+        const T* A = static_cast<const T*>(second ? p.A2 : p.A1);
+        const int64_t lda = second ? p.ld_a2 : p.ld_a1;
+        const int K = second ? p.K2 : p.K1;
+        const bool vec = second ? p.a2_vec : p.a1_vec;
+        const int k0 = (second ? s - S1 : s) * BK;
+        const int wcol = second ? p.K1p : 0;
+#pragma unroll
+        for (int i = 0; i < A_CHUNKS; ++i) {
+            const int c = tid + 256 * i;
+            ra[i] = load_chunk<T>(A, lda, m0 + c / 8, p.M, k0 + (c % 8) * E, K, vec);
+        }
+        const T* W = static_cast<const T*>(p.Wt) + wcol;
+#pragma unroll
+        for (int i = 0; i < B_CHUNKS; ++i) {
+            const int c = tid + 256 * i;
+            const int n = n0 + c / 8, k = k0 + (c % 8) * E;
+            // the packed weight is zero-padded to a multiple of E after each block, so a chunk that starts
+            // below K may be read whole
+            rb[i] = (n < p.Nout && k < K) ? *reinterpret_cast<const uint4*>(W + (int64_t)n * p.ldw + k) : make_uint4(0u, 0u, 0u, 0u);
+        }
+    };
+    auto store_step = [&]() {
+#pragma unroll
+        for (int i = 0; i < A_CHUNKS; ++i) {
+            const int c = tid + 256 * i;
+            *reinterpret_cast<uint4*>(&As[(c / 8) * LDS_LD + (c % 8) * E]) = ra[i];
+        }
+#pragma unroll
+        for (int i = 0; i < B_CHUNKS; ++i) {
+            const int c = tid + 256 * i;
+            *reinterpret_cast<uint4*>(&Bs[(c / 8) * LDS_LD + (c % 8) * E]) = rb[i];
+        }
+    };
+
+    if (S > 0) {
+        load_step(0);
+        store_step();
+    }
+    __syncthreads();
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    for (int s = 0; s < S; ++s) {
+        if (s + 1 < S) load_step(s + 1);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {  // BK = 4 sub-steps of 2E elements
+            uint4 fa[TM], fb[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                fa[i] = *reinterpret_cast<const uint4*>(&As[((wm * TM + i) * 32 + lrow) * LDS_LD + kk * 2 * E + lhalf * E]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                fb[j] = *reinterpret_cast<const uint4*>(&Bs[((wn * TN + j) * 32 + lrow) * LDS_LD + kk * 2 * E + lhalf * E]);
+            if constexpr (sizeof(T) == 4) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) {
+                            const float a = __uint_as_float(e == 0 ? fa[i].x : e == 1 ? fa[i].y : e == 2 ? fa[i].z : fa[i].w);
+                            const float b = __uint_as_float(e == 0 ? fb[j].x : e == 1 ? fb[j].y : e == 2 ? fb[j].z : fb[j].w);
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[i][j], 0, 0, 0);
+                        }
+            } else {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        bf16x8 a, b;
+                        __builtin_memcpy(&a, &fa[i], 16);
+                        __builtin_memcpy(&b, &fb[j], 16);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i][j], 0, 0, 0);
+                    }
+            }
+        }
+        __syncthreads();
+        if (s + 1 < S) {
+            store_step();
+            __syncthreads();
+        }
+    }
+
+    // epilogue: lane holds column (lane % 32) of rows 8*(r/4) + 4*(lane/32) + r%4 of each 32x32 block
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = n0 + (wn * TN + j) * 32 + lrow;
+            if (n >= p.Nout) continue;
+            const float b = p.bias ? p.bias[n] : 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t m = m0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * lhalf + (r % 4);
+                if (m >= p.M) continue;
+                const float v = act_fn(acc[i][j][r] + b, p.act, p.act_slope);
+                if (p.out_bf16) static_cast<uint16_t*>(p.Y)[m * p.ld_y + n] = f2bf(v);
+                else static_cast<float*>(p.Y)[m * p.ld_y + n] = v;
+            }
+        }
+}
+
+template <typename T>
+__global__ void pack_weight_kernel(const T* W, int K, int Nout, T* Wt, int64_t ldw, int koff) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)K * Nout) return;
+    const int k = (int)(i / Nout), n = (int)(i % Nout);
+    Wt[(int64_t)n * ldw + koff + k] = W[i];
+}
+
+__global__ void pack_gat_attn_kernel(const float* W, int K, int heads, int F, const float* a_src, const float* a_dst,
+                                     float* Wt, int64_t ldw) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= K * heads * 2) return;
+    const int k = i / (heads * 2), hh = i % (heads * 2);
+    const int h = hh % heads;
+    const float* a = (hh < heads ? a_src : a_dst) + h * F;
+    float s = 0.f;
+    for (int f = 0; f < F; ++f) s = fmaf(W[(int64_t)k * heads * F + h * F + f], a[f], s);
+    Wt[(int64_t)(heads * F + hh) * ldw + k] = s;
+}
+
+__global__ void fill_zero_kernel(uint32_t* p, uint64_t words) {
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < words; i += (uint64_t)gridDim.x * blockDim.x) p[i] = 0u;
+}
+
+// rows of `width` elements; one thread per 4-byte (fp32) or 2-byte (bf16) element, coalesced along the row
+template <typename T>
+__global__ void permute_rows_kernel(const T* in, int64_t ld_in, T* out, int64_t ld_out, int64_t rows, int width,
+                                    const int32_t* perm, int gather) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= rows * width) return;
+    const int64_t r = i / width;
+    const int c = (int)(i % width);
+    const int64_t pr = perm[r];
+    if (gather) out[r * ld_out + c] = in[pr * ld_in + c];
+    else out[pr * ld_out + c] = in[r * ld_in + c];
+}
+
+template <typename T, int WGM, int WGN, int TM, int TN>
+dgi_status_t launch_cfg(GemmParams p, hipStream_t stream) {
+    constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
+    const int64_t tiles_m = (p.M + BM - 1) / BM;
+    p.tiles_n = (p.Nout + BN - 1) / BN;
+    const int64_t grid = tiles_m * p.tiles_n;
+    DGI_REQUIRE(grid < (int64_t)1 << 31, DGI_ERR_INVALID_ARG, "gemm: too many tiles for one launch");
+    hipLaunchKernelGGL((gemm_kernel<T, WGM, WGN, TM, TN>), dim3((unsigned)grid), dim3(256), 0, stream, p);
+    DGI_HIP(hipGetLastError());
+    return DGI_OK;
+}
+
+}  // namespace
+
+dgi_status_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
+    if (a.M <= 0 || a.Nout <= 0) return DGI_OK;
+    const int eb = a.dtype == DGI_BF16 ? 2 : 4, E = 16 / eb;
+    DGI_REQUIRE(a.A1 && a.Wt && a.Y, DGI_ERR_INVALID_ARG, "gemm: null operand");
+    DGI_REQUIRE((uintptr_t)a.Wt % 16 == 0 && a.ldw % E == 0 && a.K1p % E == 0, DGI_ERR_INVALID_ARG, "gemm: packed weight misaligned");
+    GemmParams p{};
+    p.A1 = a.A1; p.ld_a1 = a.ld_a1; p.K1 = a.K1;
+    p.a1_vec = ((uintptr_t)a.A1 % 16 == 0) && (a.ld_a1 % E == 0);
+    p.A2 = a.K2 > 0 ? a.A2 : nullptr; p.ld_a2 = a.ld_a2; p.K2 = a.K2;
+    p.a2_vec = p.A2 && ((uintptr_t)a.A2 % 16 == 0) && (a.ld_a2 % E == 0);
+    p.Wt = a.Wt; p.ldw = a.ldw; p.K1p = a.K1p;
+    p.bias = a.bias; p.act = a.act; p.act_slope = a.act_slope;
+    p.Y = a.Y; p.ld_y = a.ld_y; p.out_bf16 = a.out_dtype == DGI_BF16;
+    p.M = a.M; p.Nout = a.Nout;
+    if (a.dtype == DGI_BF16) {
+        if (a.Nout <= 64) return launch_cfg<uint16_t, 4, 1, 1, 2>(p, stream);
+        return launch_cfg<uint16_t, 2, 2, 2, 2>(p, stream);
+    }
+    if (a.Nout <= 64) return launch_cfg<float, 4, 1, 1, 2>(p, stream);
+    return launch_cfg<float, 2, 2, 2, 2>(p, stream);
+}
+
+dgi_status_t launch_pack_weight(const void* W, int dtype, int K, int Nout, void* Wt, int64_t ldw, int koff, hipStream_t stream) {
+    const int64_t n = (int64_t)K * Nout;
+    if (n == 0) return DGI_OK;
+    const unsigned grid = (unsigned)((n + 255) / 256);
+    if (dtype == DGI_BF16)
+        hipLaunchKernelGGL(pack_weight_kernel<uint16_t>, dim3(grid), dim3(256), 0, stream, (const uint16_t*)W, K, Nout, (uint16_t*)Wt, ldw, koff);
+    else
+        hipLaunchKernelGGL(pack_weight_kernel<float>, dim3(grid), dim3(256), 0, stream, (const float*)W, K, Nout, (float*)Wt, ldw, koff);
+    DGI_HIP(hipGetLastError());
+    return DGI_OK;
+}
+
+dgi_status_t launch_pack_gat_attn(const float* W, int K, int heads, int F, const float* a_src, const float* a_dst,
+                                  float* Wt, int64_t ldw, hipStream_t stream) {
+    const int n = K * heads * 2;
+    hipLaunchKernelGGL(pack_gat_attn_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, W, K, heads, F, a_src, a_dst, Wt, ldw);
+    DGI_HIP(hipGetLastError());
+    return DGI_OK;
+}
+
+dgi_status_t launch_fill_zero(void* ptr, uint64_t bytes, hipStream_t stream) {
+    if (bytes == 0) return DGI_OK;
+    DGI_REQUIRE((uintptr_t)ptr % 4 == 0 && bytes % 4 == 0, DGI_ERR_INVALID_ARG, "fill_zero: needs 4-byte granularity");
+    const uint64_t words = bytes / 4;
+    uint64_t grid = (words + 255) / 256;
+    if (grid > 65536) grid = 65536;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)grid), dim3(256), 0, stream, (uint32_t*)ptr, words);
+    DGI_HIP(hipGetLastError());
+    return DGI_OK;
+}
+
+dgi_status_t launch_permute_rows(const void* in, int64_t ld_in, void* out, int64_t ld_out, int64_t rows, int width,
+                                 int elem_bytes, const int32_t* perm, bool gather, hipStream_t stream) {
+    const int64_t n = rows * width;
+    if (n == 0) return DGI_OK;
+    const int64_t grid = (n + 255) / 256;
+    DGI_REQUIRE(grid < (int64_t)1 << 31, DGI_ERR_INVALID_ARG, "permute_rows: matrix too large for one launch");
+    if (elem_bytes == 2)
+        hipLaunchKernelGGL(permute_rows_kernel<uint16_t>, dim3((unsigned)grid), dim3(256), 0, stream, (const uint16_t*)in, ld_in,
+                           (uint16_t*)out, ld_out, rows, width, perm, gather ? 1 : 0);
+    else
+        hipLaunchKernelGGL(permute_rows_kernel<float>, dim3((unsigned)grid), dim3(256), 0, stream, (const float*)in, ld_in,
+                           (float*)out, ld_out, rows, width, perm, gather ? 1 : 0);
+    DGI_HIP(hipGetLastError());
+    return DGI_OK;
+}
+
+}  // namespace dgi

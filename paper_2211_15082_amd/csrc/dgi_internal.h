@@ -1,0 +1,149 @@
+// Internal declarations shared by the translation units of libdgi (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <string>
+#include <vector>
+
+#include "dgi.h"
+
+namespace dgi {
+
+// ---- error reporting -------------------------------------------------------------------------
+void set_error(const char* fmt, ...);
+#define DGI_HIP(call)                                                                          \
+    do {                                                                                       \
+        hipError_t _e = (call);                                                                \
+        if (_e != hipSuccess) {                                                                \
+            ::dgi::set_error("%s failed: %s (%s:%d)", #call, hipGetErrorString(_e), __FILE__,  \
+                             __LINE__);                                                        \
+            return (_e == hipErrorOutOfMemory) ? DGI_ERR_OOM : DGI_ERR_DEVICE;                 \
+        }                                                                                      \
+    } while (0)
+#define DGI_TRY(expr)                       \
+    do {                                    \
+        dgi_status_t _s = (expr);           \
+        if (_s != DGI_OK) return _s;        \
+    } while (0)
+#define DGI_REQUIRE(cond, status, ...)      \
+    do {                                    \
+        if (!(cond)) {                      \
+            ::dgi::set_error(__VA_ARGS__);  \
+            return (status);                \
+        }                                   \
+    } while (0)
+
+// Rows with more in-edges than kHubDegree are split into chunks of kHubChunk edges, each reduced by
+// its own wavefront into an fp32 partial row; a second kernel adds the partials in chunk order, so the
+// result does not depend on scheduling.
+constexpr int64_t kHubDegree = 1024;
+constexpr int64_t kHubChunk = 512;
+
+}  // namespace dgi
+
+struct dgi_graph {
+    int64_t N = 0, E = 0;
+    int32_t itype = DGI_I32;
+    const void* d_indptr = nullptr;     // device, itype entries
+    const int32_t* d_indices = nullptr; // device
+    bool own_csr = false;               // device CSR allocated by the handle
+    int32_t* d_deg_out = nullptr;
+    float* d_rs_in = nullptr;           // in-degree^-1/2, degree clamped to >= 1
+    float* d_rs_out = nullptr;
+    // hub rows (in-degree > kHubDegree), ascending row id
+    int64_t* d_hub_rows = nullptr;      // [n_hubs]
+    int64_t* d_hub_chunk_ptr = nullptr; // [n_hubs + 1] prefix of chunk counts
+    std::vector<int64_t> h_indptr;      // host copy, always int64
+    std::vector<int64_t> h_hub_rows;
+    std::vector<int64_t> h_hub_chunk_ptr;
+    int64_t max_in_degree = 0;
+    uint64_t device_bytes = 0;
+    int device = 0;
+};
+
+namespace dgi {
+
+// ---- kernel launch descriptors ------------------------------------------------------------------
+enum : int { MODE_SUM = 0, MODE_MEAN = 1, MODE_GCN = 2 };
+
+// Gather/aggregate of destination rows [row_begin,row_end):
+//   out[v - out_row0, c] = act( scale_v * sum_{u in N(v)} coef_u * S[u, c] + self[v, c] + bias[c] )
+// SUM: scale 1; MEAN: 1/deg (0 for empty rows); GCN: coef_u = rs_out[u], scale_v = rs_in[v].
+struct AggArgs {
+    const dgi_graph* g = nullptr;
+    int mode = MODE_SUM;
+    const void* S = nullptr;  // source rows, element (u, c) at S[u * ld_s + c]
+    int64_t ld_s = 0;
+    int s_dtype = DGI_F32;
+    int width = 0;            // columns gathered
+    void* out = nullptr;      // element (v, c) at out[(v - out_row0) * ld_out + c]
+    int64_t ld_out = 0;
+    int64_t out_row0 = 0;
+    int out_dtype = DGI_F32;
+    const void* self = nullptr; // optional addend rows, dtype s_dtype, element (v, c) at self[v * ld_self + c]
+    int64_t ld_self = 0;
+    const float* bias = nullptr;
+    int act = DGI_ACT_NONE;
+    float act_slope = 0.f;
+    int64_t row_begin = 0, row_end = 0;
+    float* hub_partials = nullptr;  // fp32 [chunks in range x width_padded], needed when the range holds hub rows
+};
+uint64_t agg_hub_partial_bytes(const dgi_graph* g, int64_t row_begin, int64_t row_end, int width);
+// stage 0: the gather launch (row tiles + hub chunks); stage 1: the second-stage reduce of the hub rows
+// in the range (a no-op when there are none).  Callers run stage 0 then stage 1.
+dgi_status_t launch_aggregate(const AggArgs& a, int stage, hipStream_t stream);
+
+// GAT edge pass over rows [row_begin,row_end).  Zx row u = [ z (heads*F) | el (heads) | er (heads) | pad ].
+struct GatArgs {
+    const dgi_graph* g = nullptr;
+    const float* Zx = nullptr;
+    int64_t ld_z = 0;
+    int heads = 1, head_dim = 0;
+    float attn_slope = 0.2f;
+    void* out = nullptr;
+    int64_t ld_out = 0;
+    int64_t out_row0 = 0;
+    int out_dtype = DGI_F32;
+    const float* bias = nullptr;
+    int act = DGI_ACT_NONE;
+    float act_slope = 0.f;
+    int64_t row_begin = 0, row_end = 0;
+};
+dgi_status_t launch_gat(const GatArgs& a, hipStream_t stream);
+
+// Y[r, n] = act( sum_k A1[r,k] Wt[n,k] + sum_k A2[r,k] Wt[n,K1p+k] + bias[n] ),  r in [0,M), n in [0,Nout).
+// Wt is the packed transposed weight [Nout x ldw] (K contiguous); the A2 block starts at column K1p.
+struct GemmArgs {
+    int dtype = DGI_F32;        // dtype of A1, A2 and Wt
+    const void* A1 = nullptr; int64_t ld_a1 = 0; int K1 = 0;
+    const void* A2 = nullptr; int64_t ld_a2 = 0; int K2 = 0;
+    const void* Wt = nullptr; int64_t ldw = 0; int K1p = 0;
+    const float* bias = nullptr;
+    int act = DGI_ACT_NONE; float act_slope = 0.f;
+    void* Y = nullptr; int64_t ld_y = 0; int out_dtype = DGI_F32;
+    int64_t M = 0; int Nout = 0;
+};
+dgi_status_t launch_gemm(const GemmArgs& a, hipStream_t stream);
+
+// Wt[n, koff + k] = W[k, n] for k < K, n < Nout (W row-major [K x Nout]); dtype preserved.
+dgi_status_t launch_pack_weight(const void* W, int dtype, int K, int Nout, void* Wt, int64_t ldw, int koff,
+                                hipStream_t stream);
+// GAT: Wt rows [HF, HF+heads) = W a_src^h, rows [HF+heads, HF+2 heads) = W a_dst^h  (fp32 only).
+dgi_status_t launch_pack_gat_attn(const float* W, int K, int heads, int F, const float* a_src, const float* a_dst,
+                                  float* Wt, int64_t ldw, hipStream_t stream);
+dgi_status_t launch_fill_zero(void* p, uint64_t bytes, hipStream_t stream);
+// out[perm ? perm[r] : r] rows <- in rows (gather_inverse=false: out[perm[r]] = in[r]; true: out[r] = in[perm[r]])
+dgi_status_t launch_permute_rows(const void* in, int64_t ld_in, void* out, int64_t ld_out, int64_t rows, int width,
+                                 int elem_bytes, const int32_t* perm, bool gather, hipStream_t stream);
+
+// host-side permutations (dgi_reorder.cpp)
+dgi_status_t reorder_permutation(int64_t N, const int64_t* indptr, const int32_t* indices, int method, uint64_t seed,
+                                 int32_t* perm_new_of_old);
+
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+}  // namespace dgi
