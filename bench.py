@@ -28,10 +28,28 @@ def algorithmic_bytes(n, e, width, elem, indptr_bytes, heads=0):
     return e * per_edge + n * per_node
 
 
-def cpu_baseline(cfg, rows_sample=150_000):
+def measured_traffic(workload, layer):
+    """HBM bytes per launch of the dominant kernel as measured offline with rocprofv3 --pmc (FETCH_SIZE and
+    WRITE_SIZE, each scaled by a plain copy of known size).  The figure lives in a text summary under
+    profiles/ as a line `TRAFFIC_BYTES_PER_LAUNCH | <workload> | layer <k> | <bytes>`; None if absent."""
+    path = os.path.join(ROOT, "profiles")
+    if not os.path.isdir(path):
+        return None
+    for name in sorted(os.listdir(path)):
+        if not name.endswith(".txt"):
+            continue
+        for line in open(os.path.join(path, name)):
+            f = [x.strip() for x in line.split("|")]
+            if len(f) == 4 and f[0] == "TRAFFIC_BYTES_PER_LAUNCH" and f[1] == workload and f[2] == "layer %d" % layer:
+                return float(f[3])
+    return None
+
+
+def cpu_baseline(cfg, target_seconds=15.0):
     """The CPU oracle, as it stands, on a bounded sample of the same workload: every layer of the model on
-    the first `rows_sample` destination rows of the full graph (synthetic N(0,1) inputs of each layer's
-    width stand in for the hidden layers), all host threads.  Reported as aggregated edges per second."""
+    the first R destination rows of the full graph (synthetic N(0,1) inputs of each layer's width stand in
+    for the hidden layers), all host threads.  R is sized from a short calibration pass so that the sample
+    takes about `target_seconds`.  Reported as aggregated edges per second."""
     import numpy as np
     import torch
     from dgi_inputs import configs, generators
@@ -40,19 +58,28 @@ def cpu_baseline(cfg, rows_sample=150_000):
     n = cfg["num_nodes"]
     ip = cfg["indptr"].cpu().numpy().astype(np.int64)
     ix = cfg["indices"].cpu().numpy()
-    rows = np.arange(min(rows_sample, n), dtype=np.int64)
-    edges = int(ip[rows[-1] + 1] - ip[rows[0]])
     layers = configs.to_numpy_layers(cfg["layers"])
     threads = oracle.num_threads()
-    total, agg_edges = 0.0, 0
+    inputs = []
     for li, L in enumerate(layers):
         d_in = L["W_neigh"].shape[0]
-        h = cfg["x"].float().cpu().numpy() if li == 0 else generators.normal_features(n, d_in, 777 + li).numpy()
-        t0 = time.perf_counter()
-        oracle.layer_forward(ip, ix, L, h, rows=rows)
-        total += time.perf_counter() - t0
-        agg_edges += edges
-        del h
+        inputs.append(cfg["x"].float().cpu().numpy() if li == 0 else generators.normal_features(n, d_in, 777 + li).numpy())
+
+    def run(count):
+        rows = np.arange(count, dtype=np.int64)
+        t = 0.0
+        for L, h in zip(layers, inputs):
+            t0 = time.perf_counter()
+            oracle.layer_forward(ip, ix, L, h, rows=rows)
+            t += time.perf_counter() - t0
+        return t, int(ip[count] - ip[0])
+
+    probe = min(n, 20_000)
+    t_probe, _ = run(probe)
+    count = int(min(n, max(probe, probe * target_seconds / max(t_probe, 1e-3))))
+    total, edges = run(count)
+    agg_edges = edges * len(layers)
+    rows = np.arange(count)
     return {"value": agg_edges / total, "unit": "edges/s", "cores": threads, "kind": "oracle",
             "sample": "all %d layers on the first %d destination rows (%d edges per layer) of the full graph, %.1f s"
                       % (len(layers), rows.size, edges, total)}
@@ -67,6 +94,8 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0)
     ap.add_argument("--batch-size", type=int, default=0, help="destination rows per batch; 0 = dynamic")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run three plain 1 GiB device copies (known traffic, for scaling profiler byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -108,6 +137,13 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     sec = (t1 - t0) / args.steps
+    if args.calibration_copy:
+        a = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
     n_layers = len(structs)
     agg_edges = n_layers * e
 
@@ -145,10 +181,11 @@ def main():
         "per_layer_ms": {"layer": [round(sum(s["layer_ms"][l] for s in stats) / args.steps, 3) for l in range(n_layers)],
                          "aggregate": [round(a / args.steps, 3) for a in agg_ms], "gemm": [round(v, 3) for v in gemm_ms]},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(cfg["name"], dom + 1),
                      "kernel": "aggregation launch of layer %d (gather width %d, %d-byte elements)" % (dom + 1, width, elem),
-                     "algorithmic_bytes_per_layer_pass": bytes_layer, "avg_launch_ms": avg_launch_ms,
-                     "launches": agg_launches[dom]},
+                     "algorithmic_bytes_per_launch": bytes_layer * args.steps / max(agg_launches[dom], 1),
+                     "avg_launch_ms": avg_launch_ms, "launches": agg_launches[dom],
+                     "launches_per_layer_pass": agg_launches[dom] / args.steps},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg)
