@@ -85,6 +85,55 @@ def cpu_baseline(cfg, target_seconds=15.0):
                       % (len(layers), rows.size, edges, total)}
 
 
+def input_set_total(indptr, indices, batch):
+    """Sum over consecutive-id batches of the number of distinct source rows the batch reads (the quantity
+    node reordering is meant to shrink); torch tensors on the GPU."""
+    import torch
+    n = indptr.numel() - 1
+    total = 0
+    for b in range(0, n, batch):
+        e = min(n, b + batch)
+        total += int(torch.unique(indices[int(indptr[b]):int(indptr[e])]).numel())
+    return total
+
+
+def ablation(args, cfg, g, structs, x, out, B):
+    """Reordering / batching ablation: shuffled ids vs the library's reorderings, at fixed and dynamic
+    destination-batch sizes.  Reordering time is reported separately (once per graph)."""
+    import torch
+    n = cfg["num_nodes"]
+    variants = [("shuffled ids", g, None, 0.0)]
+    for method in ("bfs_rcm", "degree"):
+        t0 = time.perf_counter()
+        g2, perm = B.graph_reorder(g, method)
+        torch.cuda.synchronize()
+        variants.append((method, g2, perm, time.perf_counter() - t0))
+        print("[bench] reorder %s: %.1f s" % (method, variants[-1][3]), file=sys.stderr, flush=True)
+    runs = []
+    for name, gv, perm, t_reorder in variants:
+        ip, ix = gv.csr()
+        ip_d, ix_d = torch.from_numpy(ip).cuda(), torch.from_numpy(ix).cuda()
+        inputs = {bs: input_set_total(ip_d, ix_d, bs) for bs in (1 << 16, 1 << 20)}
+        del ip_d, ix_d
+        for bs in (1 << 16, 1 << 20, 0):
+            B.infer(gv, structs, x, out, batch_size=bs, perm_new_of_old=perm)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            st = None
+            for _ in range(args.steps):
+                st = B.infer(gv, structs, x, out, batch_size=bs, perm_new_of_old=perm, want_stats=True)
+            torch.cuda.synchronize()
+            sec = (time.perf_counter() - t0) / args.steps
+            runs.append({"ids": name, "batch_size": bs or "dynamic", "ms": round(sec * 1e3, 3),
+                         "agg_ms": [round(v, 3) for v in st["agg_ms"]], "gemm_ms": [round(v, 3) for v in st["gemm_ms"]],
+                         "batches": st["batches"], "distinct_inputs_over_batches": inputs.get(bs),
+                         "reorder_seconds": round(t_reorder, 2)})
+            print("[bench] %s" % json.dumps(runs[-1]), file=sys.stderr, flush=True)
+        gv.release_workspace()
+    print(json.dumps({"ablation": cfg["name"], "num_nodes": n, "num_edges": int(cfg["indices"].numel()), "steps": args.steps,
+                      "note": "ms includes permuting X in and the output back for the reordered variants", "runs": runs}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -94,6 +143,7 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0)
     ap.add_argument("--batch-size", type=int, default=0, help="destination rows per batch; 0 = dynamic")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--ablation", action="store_true", help="reordering x batch-size ablation instead of the timed run")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run three plain 1 GiB device copies (known traffic, for scaling profiler byte counters)")
     args = ap.parse_args()
@@ -110,9 +160,10 @@ def main():
         sys.exit(3)
     dev = "cuda"
     t_gen = time.perf_counter()
-    cfg = configs.make_config(args.config, scale=args.scale, device=dev)
+    cfg = configs.make_config(args.config, scale=args.scale, device=dev, verbose=True)
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
+    torch.cuda.empty_cache()  # hand the generator's scratch back so the library sees the free memory
     n = cfg["num_nodes"]
     e = int(cfg["indices"].numel())
     g = B.graph_load(cfg["indptr"], cfg["indices"])
@@ -127,6 +178,9 @@ def main():
     x = cfg["x"].contiguous()
     out = torch.empty(n, structs[-1].out_dim, dtype=torch.float32, device=dev)
 
+    if args.ablation:
+        ablation(args, cfg, g, structs, x, out, B)
+        return
     for _ in range(args.warmup):
         B.infer(g, structs, x, out, batch_size=args.batch_size)
     torch.cuda.synchronize()

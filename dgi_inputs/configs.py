@@ -66,7 +66,8 @@ def products_like_graph(scale, device, indptr_dtype=torch.int64):
     return n, indptr, indices
 
 
-def make_config(k, scale=1.0, device="cpu"):
+def make_config(k, scale=1.0, device="cpu", verbose=False):
+    G.VERBOSE = verbose
     gs, fs, ws = SEEDS[k]
     if k == 1:
         n, m = max(64, int(10_000 * scale)), max(128, int(100_000 * scale))
@@ -91,6 +92,7 @@ def make_config(k, scale=1.0, device="cpu"):
         src, dst = G.cap_in_degree(src, dst, n, cap)
         indptr, indices = G.build_csr(src, dst, n, torch.int64)
         del src, dst
+        G._log("features")
         x = G.normal_features(n, 128, fs, device, torch.bfloat16)
         layers = _sage_layers([128, 128, 128, 172], ws, device, storage="bf16")
         name = "cfg4 GraphSAGE-mean bf16 128-128-128-172"

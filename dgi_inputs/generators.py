@@ -14,8 +14,19 @@ After generation the node ids are shuffled with a seeded permutation, because ge
 sorted by expected degree (or by block), a locality real datasets do not have.
 """
 import math
+import sys
+import time
 
 import torch
+
+VERBOSE = False
+_t0 = [time.perf_counter()]
+
+
+def _log(msg):
+    """Progress line for the long generations (a quiet multi-minute run looks hung to a job supervisor)."""
+    if VERBOSE:
+        print("[dgi_inputs %7.1fs] %s" % (time.perf_counter() - _t0[0], msg), file=sys.stderr, flush=True)
 
 
 def _gen(seed, device):
@@ -48,9 +59,24 @@ def power_law_cdf(n, gamma, max_expected_degree, endpoints, device):
     return cdf / cdf[-1], i0
 
 
+_CHUNK = 1 << 27
+
+
 def _draw_nodes(cdf, count, gen):
-    u = torch.rand(count, dtype=torch.float64, device=cdf.device, generator=gen)
-    return torch.searchsorted(cdf, u).clamp_(max=cdf.numel() - 1)
+    out = torch.empty(count, dtype=torch.int64, device=cdf.device)
+    for lo in range(0, count, _CHUNK):
+        hi = min(count, lo + _CHUNK)
+        u = torch.rand(hi - lo, dtype=torch.float64, device=cdf.device, generator=gen)
+        torch.searchsorted(cdf, u, out=out[lo:hi])
+    return out.clamp_(max=cdf.numel() - 1)
+
+
+def _systematic_subset(sorted_keys, m):
+    """m of the keys, evenly spaced through the sorted list (an unbiased thinning of the edge set that
+    needs no 2^31-element random permutation)."""
+    total = sorted_keys.numel()
+    idx = ((torch.arange(m, dtype=torch.float64, device=sorted_keys.device) + 0.5) * (total / m)).to(torch.int64)
+    return sorted_keys[idx.clamp_(max=total - 1)]
 
 
 def _distinct_pairs(draw, n, m, gen, undirected):
@@ -59,20 +85,26 @@ def _distinct_pairs(draw, n, m, gen, undirected):
     need = m
     for _ in range(64):
         k = int(need * 1.15) + 1024
+        _log("drawing %d candidate pairs" % k)
         a, b = draw(k), draw(k)
-        ok = a != b
-        a, b = a[ok], b[ok]
         if undirected:
-            a, b = torch.minimum(a, b), torch.maximum(a, b)
-        keys = torch.unique(torch.cat([keys, a * n + b]))
+            lo_, hi_ = torch.minimum(a, b), torch.maximum(a, b)
+            a, b = lo_, hi_
+            del lo_, hi_
+        new = a * n + b
+        new = new[a != b]
+        del a, b
+        _log("deduplicating")
+        keys = torch.unique(torch.cat([keys, new]))
+        del new
         if keys.numel() >= m:
             break
         need = m - keys.numel()
     if keys.numel() < m:
         raise RuntimeError("could not draw enough distinct pairs")
     if keys.numel() > m:
-        sel = torch.randperm(keys.numel(), device=keys.device, generator=gen)[:m]
-        keys = keys[sel]
+        keys = _systematic_subset(keys, m)
+    _log("%d distinct pairs" % keys.numel())
     return keys // n, keys % n
 
 
@@ -141,7 +173,7 @@ def sbm_power_law_blocks(n, blocks, m, p_intra, seed, device="cpu", size_exponen
             break
         need = m - keys.numel()
     if keys.numel() > m:
-        keys = keys[torch.randperm(keys.numel(), device=device, generator=gen)[:m]]
+        keys = _systematic_subset(keys, m)
     src, dst = keys // n, keys % n
     if shuffle:
         src, dst = shuffle_ids(src, dst, n, seed + 7919)
@@ -150,17 +182,19 @@ def sbm_power_law_blocks(n, blocks, m, p_intra, seed, device="cpu", size_exponen
 
 def cap_in_degree(src, dst, n, cap):
     """Drop the in-edges of any destination beyond its first `cap` in sorted source order."""
+    _log("capping in-degrees at %d" % cap)
     key = dst * n + src
     key, _ = torch.sort(key)
-    dst_s = key // n
-    first = torch.searchsorted(dst_s, dst_s, right=False)
-    rank = torch.arange(key.numel(), device=key.device) - first
+    deg = torch.bincount(key // n, minlength=n)
+    first = torch.cumsum(deg, 0) - deg                      # first edge of every destination
+    rank = torch.arange(key.numel(), device=key.device) - torch.repeat_interleave(first, deg)
     key = key[rank < cap]
     return key % n, key // n
 
 
 def build_csr(src, dst, n, indptr_dtype=torch.int64):
     """CSR keyed by destination, rows sorted by source id.  Returns (indptr[n+1], indices[E] int32)."""
+    _log("building CSR of %d edges" % src.numel())
     key = dst.to(torch.int64) * n + src.to(torch.int64)
     key, _ = torch.sort(key)
     indices = (key % n).to(torch.int32)

@@ -144,7 +144,9 @@ typedef struct {
  *   for its own work on `hip_stream` before returning.  N == 0 is legal.                         */
 dgi_status_t dgi_graph_load(int64_t num_nodes, int64_t num_edges, const void* indptr, int32_t indptr_type,
                             const int32_t* indices, int32_t where, void* hip_stream, dgi_graph_t** out);
-dgi_status_t dgi_graph_free(dgi_graph_t* g);            /* NULL is a no-op */
+dgi_status_t dgi_graph_free(dgi_graph_t* g);            /* NULL is a no-op; also frees the cached workspace */
+/* Frees the workspace dgi_infer keeps in the handle between calls (waits for the device first). */
+dgi_status_t dgi_graph_release_workspace(dgi_graph_t* g);
 dgi_status_t dgi_graph_info(const dgi_graph_t* g, dgi_graph_info_t* info /*HOST*/);
 
 /* Copies of the handle's device vectors for inspection/tests: kind 0 = in-degree (int32), 1 = out-degree
@@ -182,8 +184,11 @@ dgi_status_t dgi_layer_workspace_bytes(const dgi_graph_t* g, const dgi_layer_t* 
  *   x   : DEVICE [N x layers[0].in_dim], dtype layers[0].feat_dtype, leading dimension ld_x.
  *   out : DEVICE [N x layers[L-1].out_dim], dtype layers[L-1].out_dtype, leading dimension ld_out.
  *   layers[l].in_dim must equal layers[l-1].out_dim and feat_dtype must equal the previous out_dtype.
- * The call allocates its hidden buffers and temporaries with hipMalloc within opts->mem_budget_bytes and
- * frees them before returning (it waits for the stream when it allocated anything or stats is set).
+ * The call takes its hidden buffers and temporaries (Algorithm 2's H^l and per-batch buffers) from one
+ * arena within opts->mem_budget_bytes.  The arena is allocated with hipMalloc on the first call, kept in
+ * the graph handle and reused by later calls (reallocated when a call needs more, or far less under a
+ * smaller budget); dgi_graph_release_workspace or dgi_graph_free returns it.  Calls on one graph handle
+ * are serialised by a lock.  The call waits for its work on the stream before returning.
  * opts may be NULL (all defaults). */
 dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layers, int32_t num_layers, const void* x,
                        int64_t ld_x, void* out, int64_t ld_out, const dgi_infer_opts_t* opts, void* hip_stream);

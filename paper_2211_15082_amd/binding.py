@@ -70,7 +70,7 @@ class GraphInfoStruct(ctypes.Structure):
 
 
 EXPORTS = [
-    "dgi_graph_load", "dgi_graph_free", "dgi_graph_info", "dgi_graph_vector", "dgi_graph_csr", "dgi_graph_reorder",
+    "dgi_graph_load", "dgi_graph_free", "dgi_graph_release_workspace", "dgi_graph_info", "dgi_graph_vector", "dgi_graph_csr", "dgi_graph_reorder",
     "dgi_layer_forward", "dgi_layer_workspace_bytes", "dgi_infer", "dgi_plan_batch_end", "dgi_threshold_update",
     "dgi_threshold_halve", "dgi_batch_input_set_size", "dgi_reorder_permutation", "dgi_status_string",
     "dgi_last_error", "dgi_version",
@@ -139,6 +139,9 @@ class Graph:
             self.free()
         except Exception:
             pass
+
+    def release_workspace(self):
+        _check(_lib.dgi_graph_release_workspace(self.handle))
 
     def info(self):
         s = GraphInfoStruct()

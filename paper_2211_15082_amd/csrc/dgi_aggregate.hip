@@ -102,10 +102,11 @@ __device__ __forceinline__ int64_t xcd_tile(int64_t bid) {
 }
 
 // Adds  sum_{e in [eb,ee)} coef(indices[e]) * S[indices[e], col0 + gl*VEC .. +VEC)  into acc (per lane;
-// the 64/G lane groups hold disjoint subsets of the edges).
+// the 64/G lane groups hold disjoint subsets of the edges).  When `preloaded` is set, `first_my` holds
+// indices[eb + lane] (0 beyond the row) fetched earlier by the caller.
 template <typename T, int G, int MODE, int UNROLL>
 __device__ __forceinline__ void gather_range(const AggParams& p, int64_t eb, int64_t ee, int lane, int col0,
-                                             float (&acc)[Row<T>::VEC]) {
+                                             float (&acc)[Row<T>::VEC], bool preloaded = false, int first_my = 0) {
     constexpr int VEC = Row<T>::VEC;
     constexpr int NSUB = 64 / G;
     using Raw = typename Row<T>::Raw;
@@ -116,7 +117,9 @@ __device__ __forceinline__ void gather_range(const AggParams& p, int64_t eb, int
     for (int64_t e0 = eb; e0 < ee; e0 += 64) {
         const int64_t left = ee - e0;
         const int cnt = left < 64 ? (int)left : 64;
-        const int my = lane < cnt ? p.indices[e0 + lane] : 0;
+        int my;
+        if (preloaded && e0 == eb) my = first_my;
+        else my = lane < cnt ? p.indices[e0 + lane] : 0;
         float myc = 1.f;
         if (MODE == MODE_GCN) myc = lane < cnt ? p.rs_out[my] : 0.f;
         for (int j = 0; j < cnt; j += NSUB * UNROLL) {
@@ -124,19 +127,13 @@ __device__ __forceinline__ void gather_range(const AggParams& p, int64_t eb, int
             float c[UNROLL];
             int64_t off[UNROLL];
             bool ok[UNROLL];
+            int ks[UNROLL];
 #pragma unroll
             for (int t = 0; t < UNROLL; ++t) {
                 const int k = j + t * NSUB + sub;
                 ok[t] = k < cnt;
-                const int ks = ok[t] ? k : 0;
-                int u;
-                if (G == 64) {
-                    u = __builtin_amdgcn_readlane(my, ks);
-                    c[t] = (MODE == MODE_GCN) ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(myc), ks)) : 1.f;
-                } else {
-                    u = __shfl(my, ks, 64);
-                    c[t] = (MODE == MODE_GCN) ? __shfl(myc, ks, 64) : 1.f;
-                }
+                ks[t] = ok[t] ? k : 0;
+                const int u = (G == 64) ? __builtin_amdgcn_readlane(my, ks[t]) : __shfl(my, ks[t], 64);
                 off[t] = (int64_t)u * p.ld_s;
             }
             if (col_ok) {
@@ -146,14 +143,21 @@ __device__ __forceinline__ void gather_range(const AggParams& p, int64_t eb, int
 #pragma unroll
                 for (int t = 0; t < UNROLL; ++t) raw[t] = Row<T>::zero();
             }
+            // the per-source coefficients are handed out only now, so the row loads above do not wait for them
+#pragma unroll
+            for (int t = 0; t < UNROLL; ++t) {
+                if (MODE == MODE_GCN)
+                    c[t] = (G == 64) ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(myc), ks[t])) : __shfl(myc, ks[t], 64);
+                else
+                    c[t] = 1.f;
+            }
 #pragma unroll
             for (int t = 0; t < UNROLL; ++t) {
                 float f[VEC];
                 Row<T>::unpack(raw[t], f);
-                const float w = ok[t] ? c[t] : 0.f;
                 if (MODE == MODE_GCN) {
 #pragma unroll
-                    for (int i = 0; i < VEC; ++i) acc[i] = ok[t] ? fmaf(w, f[i], acc[i]) : acc[i];
+                    for (int i = 0; i < VEC; ++i) acc[i] = ok[t] ? fmaf(c[t], f[i], acc[i]) : acc[i];
                 } else {
 #pragma unroll
                     for (int i = 0; i < VEC; ++i) acc[i] += ok[t] ? f[i] : 0.f;
@@ -191,29 +195,55 @@ __device__ __forceinline__ float row_scale(const AggParams& p, int64_t v, IdxT d
     return 1.f;
 }
 
-// Workgroup `bid` of the row part: kRowsPerWg destination rows, one wavefront per row at a time.
+template <typename IdxT>
+__device__ __forceinline__ IdxT bcast_lane(IdxT x, int src) {
+    if (sizeof(IdxT) == 8) {
+        const uint64_t u = (uint64_t)x;
+        const uint32_t lo = (uint32_t)__shfl((int)(uint32_t)u, src, 64), hi = (uint32_t)__shfl((int)(uint32_t)(u >> 32), src, 64);
+        return (IdxT)(((uint64_t)hi << 32) | lo);
+    }
+    return (IdxT)__shfl((int)x, src, 64);
+}
+
+// Workgroup `bid` of the row part: kRowsPerWg destination rows; each wavefront owns kRowsPerWg / kWaves
+// consecutive rows, reads their indptr entries with one load, and fetches the first 64 neighbour ids of the
+// next row while it gathers the current one (a row costs one dependent memory latency instead of three).
 template <typename T, typename IdxT, int G, int MODE>
 __device__ __forceinline__ void rows_tile(const AggParams& p, int64_t bid) {
     constexpr int VEC = Row<T>::VEC;
     constexpr int UNROLL = (G == 64) ? 8 : 4;
+    constexpr int RPW = kRowsPerWg / kWaves;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t tile = xcd_tile(bid);
     if (tile >= p.n_tiles) return;
     const IdxT* indptr = static_cast<const IdxT*>(p.indptr);
     const int sub = lane / G, gl = lane % G;
-    const int64_t v0 = p.row_begin + tile * kRowsPerWg;
-    for (int r = wave; r < kRowsPerWg; r += kWaves) {
-        const int64_t v = v0 + r;
+    const int64_t vw = p.row_begin + tile * kRowsPerWg + wave * RPW;
+    if (vw >= p.row_end) return;
+    IdxT ipv = 0;
+    if (lane <= RPW) {
+        const int64_t i = vw + lane;
+        ipv = indptr[i < p.row_end ? i : p.row_end];  // rows past the range read as empty
+    }
+    IdxT bound[RPW + 1];
+#pragma unroll
+    for (int i = 0; i <= RPW; ++i) bound[i] = bcast_lane<IdxT>(ipv, i);
+    int nxt = (int64_t)lane < (int64_t)(bound[1] - bound[0]) ? p.indices[(int64_t)bound[0] + lane] : 0;
+#pragma unroll
+    for (int r = 0; r < RPW; ++r) {
+        const int64_t v = vw + r;
         if (v >= p.row_end) break;
-        const IdxT eb = indptr[v], ee = indptr[v + 1];
+        const IdxT eb = bound[r], ee = bound[r + 1];
         const IdxT deg = ee - eb;
+        const int cur = nxt;
+        if (r + 1 < RPW) nxt = (int64_t)lane < (int64_t)(bound[r + 2 <= RPW ? r + 2 : RPW] - ee) ? p.indices[(int64_t)ee + lane] : 0;
         if (p.skip_hubs && deg > (IdxT)kHubDegree) continue;
         const float scale = row_scale<MODE, IdxT>(p, v, deg);
         for (int col0 = 0; col0 < p.width; col0 += G * VEC) {
             float acc[VEC];
 #pragma unroll
             for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
-            gather_range<T, G, MODE, UNROLL>(p, (int64_t)eb, (int64_t)ee, lane, col0, acc);
+            gather_range<T, G, MODE, UNROLL>(p, (int64_t)eb, (int64_t)ee, lane, col0, acc, true, cur);
             combine_groups<G, VEC>(acc);
             const int c = col0 + gl * VEC;
             if (sub == 0 && c < p.width) {
@@ -347,7 +377,8 @@ dgi_status_t launch_fast(const AggParams& p0, const dgi_graph* g, hipStream_t st
         p.hub_blocks = round_up((p.n_chunks + kWaves - 1) / kWaves, kGroup);
     }
     const int64_t grid = p.hub_blocks + round_up(p.n_tiles, kGroup);
-    DGI_REQUIRE(grid < (int64_t)1 << 31, DGI_ERR_INVALID_ARG, "row range too large for one launch");
+    DGI_REQUIRE(grid * kWaves * 64 < (int64_t)1 << 32, DGI_ERR_INVALID_ARG,
+                "row range too large for one launch (2^32 threads): use smaller destination batches");
     hipLaunchKernelGGL((agg_kernel<T, IdxT, G, MODE>), dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
     DGI_HIP(hipGetLastError());
     return DGI_OK;
@@ -374,10 +405,16 @@ template <typename T, typename IdxT, int MODE>
 dgi_status_t dispatch_g(const AggParams& p, const dgi_graph* g, bool fast, int stage, hipStream_t stream) {
     if (stage == 1) return fast ? launch_hub_reduce<T, IdxT, MODE>(p, g, stream) : DGI_OK;
     if (!fast) {
-        const int64_t rows = p.row_end - p.row_begin;
-        hipLaunchKernelGGL((agg_rows_generic_kernel<T, IdxT, MODE>), dim3((unsigned)((rows + kWaves - 1) / kWaves)),
-                           dim3(kWaves * 64), 0, stream, p);
-        DGI_HIP(hipGetLastError());
+        // 64 threads per row: keep each launch below 2^32 threads
+        for (int64_t r0 = p.row_begin; r0 < p.row_end; r0 += (int64_t)1 << 25) {
+            AggParams q = p;
+            q.row_begin = r0;
+            q.row_end = std::min(p.row_end, r0 + ((int64_t)1 << 25));
+            const int64_t rows = q.row_end - q.row_begin;
+            hipLaunchKernelGGL((agg_rows_generic_kernel<T, IdxT, MODE>), dim3((unsigned)((rows + kWaves - 1) / kWaves)),
+                               dim3(kWaves * 64), 0, stream, q);
+            DGI_HIP(hipGetLastError());
+        }
         return DGI_OK;
     }
     const int lanes = (p.width + Row<T>::VEC - 1) / Row<T>::VEC;

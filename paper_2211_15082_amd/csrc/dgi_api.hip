@@ -23,6 +23,10 @@ namespace {
 
 int elem_bytes(int dtype) { return dtype == DGI_BF16 ? 2 : 4; }
 
+// A dispatch holds fewer than 2^32 threads; the widest kernels here spend 64 threads per row, so a launch
+// never covers more than this many rows (dgi_infer splits batches and transforms accordingly).
+constexpr int64_t kMaxRowsPerLaunch = (int64_t)1 << 25;
+
 // How one layer is laid out and executed.
 struct LayerPlan {
     bool transform_first = false;
@@ -113,13 +117,18 @@ dgi_status_t prepare_weights(const dgi_layer_t* L, const LayerPlan& P, void* Wt,
 // Transform-first: Z[r,:] = H[r,:] Wt^T for rows [r0,r1) of the graph.
 dgi_status_t run_transform(const dgi_layer_t* L, const LayerPlan& P, const void* h_in, int64_t ld_in, const void* Wt,
                            void* Z, int64_t r0, int64_t r1, hipStream_t s) {
-    GemmArgs ga;
-    ga.dtype = L->feat_dtype;
-    ga.A1 = (const char*)h_in + r0 * ld_in * P.eb; ga.ld_a1 = ld_in; ga.K1 = L->in_dim;
-    ga.Wt = Wt; ga.ldw = P.ldw; ga.K1p = P.K1p;
-    ga.Y = (char*)Z + r0 * P.z_ld * elem_bytes(P.z_dtype); ga.ld_y = P.z_ld; ga.out_dtype = P.z_dtype;
-    ga.M = r1 - r0; ga.Nout = P.z_cols;
-    return launch_gemm(ga, s);
+    // row chunks keep every launch far below the 2^32-thread limit of a dispatch
+    for (int64_t c0 = r0; c0 < r1; c0 += kMaxRowsPerLaunch) {
+        const int64_t c1 = std::min(r1, c0 + kMaxRowsPerLaunch);
+        GemmArgs ga;
+        ga.dtype = L->feat_dtype;
+        ga.A1 = (const char*)h_in + c0 * ld_in * P.eb; ga.ld_a1 = ld_in; ga.K1 = L->in_dim;
+        ga.Wt = Wt; ga.ldw = P.ldw; ga.K1p = P.K1p;
+        ga.Y = (char*)Z + c0 * P.z_ld * elem_bytes(P.z_dtype); ga.ld_y = P.z_ld; ga.out_dtype = P.z_dtype;
+        ga.M = c1 - c0; ga.Nout = P.z_cols;
+        DGI_TRY(launch_gemm(ga, s));
+    }
+    return DGI_OK;
 }
 
 uint64_t batch_temp_bytes(const dgi_graph* g, const dgi_layer_t* L, const LayerPlan& P, int64_t b, int64_t e) {
@@ -249,6 +258,18 @@ extern "C" const char* dgi_status_string(dgi_status_t s) {
     return "unknown status";
 }
 
+extern "C" dgi_status_t dgi_graph_release_workspace(dgi_graph_t* g) {
+    if (!g) return DGI_OK;
+    std::lock_guard<std::mutex> ws_lock(g->ws_mutex);
+    if (g->ws_ptr) {
+        DGI_HIP(hipDeviceSynchronize());
+        (void)hipFree(g->ws_ptr);
+        g->ws_ptr = nullptr;
+        g->ws_bytes = 0;
+    }
+    return DGI_OK;
+}
+
 extern "C" dgi_status_t dgi_layer_workspace_bytes(const dgi_graph_t* g, const dgi_layer_t* layer, int64_t dst_begin,
                                                   int64_t dst_end, uint64_t* bytes) {
     DGI_REQUIRE(g && bytes, DGI_ERR_INVALID_ARG, "layer_workspace_bytes: NULL argument");
@@ -306,11 +327,12 @@ extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layer
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
 
     // ---- memory plan -------------------------------------------------------------------------------
+    std::lock_guard<std::mutex> ws_lock(g->ws_mutex);  // one dgi_infer at a time per graph handle
     uint64_t budget = o.mem_budget_bytes;
     if (budget == 0) {
         size_t free_b = 0, total_b = 0;
         DGI_HIP(hipMemGetInfo(&free_b, &total_b));
-        budget = (uint64_t)(0.9 * (double)free_b);
+        budget = (uint64_t)(0.9 * (double)(free_b + g->ws_bytes));  // the cached arena counts as available
     }
     uint64_t hidden_bytes = 0;  // one ping-pong buffer
     for (int l = 0; l + 1 < num_layers; ++l) {
@@ -339,10 +361,14 @@ extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layer
     // already 90 % of free memory when it was not given), but no more than one whole-graph batch needs.
     const uint64_t temp_cap = std::max<uint64_t>(std::min<uint64_t>(budget - persistent, temp_full_max), 256);
 
-    char* arena = nullptr;
     const uint64_t arena_bytes = persistent + temp_cap + 1024;
-    DGI_HIP(hipMalloc(reinterpret_cast<void**>(&arena), arena_bytes));
-    struct Free { char* p; ~Free() { (void)hipFree(p); } } arena_guard{arena};
+    if (g->ws_bytes < arena_bytes || g->ws_bytes > arena_bytes + arena_bytes / 2 + ((uint64_t)64 << 20)) {
+        // (re)allocate: too small, or far larger than this call may use under its budget
+        if (g->ws_ptr) { DGI_HIP(hipStreamSynchronize(s)); (void)hipFree(g->ws_ptr); g->ws_ptr = nullptr; g->ws_bytes = 0; }
+        DGI_HIP(hipMalloc(reinterpret_cast<void**>(&g->ws_ptr), arena_bytes));
+        g->ws_bytes = arena_bytes;
+    }
+    char* arena = g->ws_ptr;
     uint64_t off = 0;
     auto carve = [&](uint64_t bytes) { char* p = arena + off; off += (uint64_t)round_up((int64_t)bytes, 256); return p; };
     char* hid[2] = {nullptr, nullptr};
@@ -388,7 +414,8 @@ extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layer
         int64_t b = 0, batches = 0;
         while (b < N) {
             int64_t e = 0;
-            DGI_TRY(dgi_plan_batch_end(g->h_indptr.data(), DGI_I64, N, b, std::max<int64_t>(n_t, 1), std::max<int64_t>(n_i, 0), &e));
+            DGI_TRY(dgi_plan_batch_end(g->h_indptr.data(), DGI_I64, N, b, std::min(std::max<int64_t>(n_t, 1), kMaxRowsPerLaunch * 4),
+                                       std::max<int64_t>(n_i, 0), &e));
             const uint64_t need = batch_temp_bytes(g, &L, P, b, e);
             if (need > temp_cap) {  // the batch would not fit: the out-of-memory reaction of Section 4.1
                 if (o.stats) o.stats->oom_retries += 1;

@@ -176,7 +176,7 @@ template <typename IdxT, int G>
 dgi_status_t launch_g(const GatParams& p, hipStream_t stream) {
     const int64_t rows = p.row_end - p.row_begin;
     const int64_t grid = (rows + kRowsPerWg - 1) / kRowsPerWg;
-    DGI_REQUIRE(grid < (int64_t)1 << 31, DGI_ERR_INVALID_ARG, "gat: row range too large for one launch");
+    DGI_REQUIRE(grid * kWaves * 64 < (int64_t)1 << 32, DGI_ERR_INVALID_ARG, "gat: row range too large for one launch");
     hipLaunchKernelGGL((gat_rows_kernel<IdxT, G>), dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
     DGI_HIP(hipGetLastError());
     return DGI_OK;
@@ -185,10 +185,15 @@ dgi_status_t launch_g(const GatParams& p, hipStream_t stream) {
 template <typename IdxT>
 dgi_status_t dispatch(const GatParams& p, bool fast, hipStream_t stream) {
     if (!fast) {
-        const int64_t rows = p.row_end - p.row_begin;
-        hipLaunchKernelGGL((gat_rows_generic_kernel<IdxT>), dim3((unsigned)((rows + kWaves - 1) / kWaves)), dim3(kWaves * 64), 0,
-                           stream, p);
-        DGI_HIP(hipGetLastError());
+        for (int64_t r0 = p.row_begin; r0 < p.row_end; r0 += (int64_t)1 << 25) {  // < 2^32 threads per launch
+            GatParams q = p;
+            q.row_begin = r0;
+            q.row_end = p.row_end < r0 + ((int64_t)1 << 25) ? p.row_end : r0 + ((int64_t)1 << 25);
+            const int64_t rows = q.row_end - q.row_begin;
+            hipLaunchKernelGGL((gat_rows_generic_kernel<IdxT>), dim3((unsigned)((rows + kWaves - 1) / kWaves)), dim3(kWaves * 64), 0,
+                               stream, q);
+            DGI_HIP(hipGetLastError());
+        }
         return DGI_OK;
     }
     const int lanes = (p.HF + 3) / 4;

@@ -10,6 +10,8 @@
 // 128-byte slab of every tile row in LDS (global -> registers -> LDS, the next slab's global loads are
 // in flight while the current one is multiplied).  LDS rows are padded by 16 bytes so that the 16-byte
 // fragment reads of 8 consecutive lanes cover all banks.
+#include <algorithm>
+
 #include "dgi_internal.h"
 
 namespace dgi {
@@ -219,13 +221,14 @@ __global__ void fill_zero_kernel(uint32_t* p, uint64_t words) {
 template <typename T>
 __global__ void permute_rows_kernel(const T* in, int64_t ld_in, T* out, int64_t ld_out, int64_t rows, int width,
                                     const int32_t* perm, int gather) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= rows * width) return;
-    const int64_t r = i / width;
-    const int c = (int)(i % width);
-    const int64_t pr = perm[r];
-    if (gather) out[r * ld_out + c] = in[pr * ld_in + c];
-    else out[pr * ld_out + c] = in[r * ld_in + c];
+    const int64_t total = rows * width;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t r = i / width;
+        const int c = (int)(i % width);
+        const int64_t pr = perm[r];
+        if (gather) out[r * ld_out + c] = in[pr * ld_in + c];
+        else out[pr * ld_out + c] = in[r * ld_in + c];
+    }
 }
 
 template <typename T, int WGM, int WGN, int TM, int TN>
@@ -234,7 +237,7 @@ dgi_status_t launch_cfg(GemmParams p, hipStream_t stream) {
     const int64_t tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.Nout + BN - 1) / BN;
     const int64_t grid = tiles_m * p.tiles_n;
-    DGI_REQUIRE(grid < (int64_t)1 << 31, DGI_ERR_INVALID_ARG, "gemm: too many tiles for one launch");
+    DGI_REQUIRE(grid * 256 < (int64_t)1 << 32, DGI_ERR_INVALID_ARG, "gemm: too many tiles for one launch");
     hipLaunchKernelGGL((gemm_kernel<T, WGM, WGN, TM, TN>), dim3((unsigned)grid), dim3(256), 0, stream, p);
     DGI_HIP(hipGetLastError());
     return DGI_OK;
@@ -256,11 +259,14 @@ dgi_status_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
     p.bias = a.bias; p.act = a.act; p.act_slope = a.act_slope;
     p.Y = a.Y; p.ld_y = a.ld_y; p.out_bf16 = a.out_dtype == DGI_BF16;
     p.M = a.M; p.Nout = a.Nout;
+    // 128-wide column tiles: a 256-wide tile would read A once but leaves one wavefront per SIMD and measured slower
     if (a.dtype == DGI_BF16) {
         if (a.Nout <= 64) return launch_cfg<uint16_t, 4, 1, 1, 2>(p, stream);
+        if (a.Nout > 128 && a.Nout <= 192) return launch_cfg<uint16_t, 2, 2, 2, 3>(p, stream);
         return launch_cfg<uint16_t, 2, 2, 2, 2>(p, stream);
     }
     if (a.Nout <= 64) return launch_cfg<float, 4, 1, 1, 2>(p, stream);
+    if (a.Nout > 128 && a.Nout <= 192) return launch_cfg<float, 2, 2, 2, 3>(p, stream);
     return launch_cfg<float, 2, 2, 2, 2>(p, stream);
 }
 
@@ -299,8 +305,8 @@ dgi_status_t launch_permute_rows(const void* in, int64_t ld_in, void* out, int64
                                  int elem_bytes, const int32_t* perm, bool gather, hipStream_t stream) {
     const int64_t n = rows * width;
     if (n == 0) return DGI_OK;
-    const int64_t grid = (n + 255) / 256;
-    DGI_REQUIRE(grid < (int64_t)1 << 31, DGI_ERR_INVALID_ARG, "permute_rows: matrix too large for one launch");
+    // a launch may not exceed 2^32 threads in total: cap the grid and stride
+    const int64_t grid = std::min<int64_t>((n + 255) / 256, (int64_t)1 << 22);
     if (elem_bytes == 2)
         hipLaunchKernelGGL(permute_rows_kernel<uint16_t>, dim3((unsigned)grid), dim3(256), 0, stream, (const uint16_t*)in, ld_in,
                            (uint16_t*)out, ld_out, rows, width, perm, gather ? 1 : 0);

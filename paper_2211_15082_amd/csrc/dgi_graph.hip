@@ -34,12 +34,13 @@ template <typename IdxT>
 __global__ void relabel_rows_kernel(const IdxT* indptr_old, const int32_t* indices_old, const IdxT* indptr_new,
                                     const int32_t* old_of_new, const int32_t* perm_new_of_old, int64_t N, int32_t* indices_new) {
     const int lane = threadIdx.x & 63;
-    const int64_t r = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    if (r >= N) return;
-    const int64_t o = old_of_new[r];
-    const int64_t src = (int64_t)indptr_old[o], dst = (int64_t)indptr_new[r];
-    const int64_t deg = (int64_t)indptr_old[o + 1] - src;
-    for (int64_t i = lane; i < deg; i += 64) indices_new[dst + i] = perm_new_of_old[indices_old[src + i]];
+    const int64_t waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    for (int64_t r = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; r < N; r += waves) {
+        const int64_t o = old_of_new[r];
+        const int64_t src = (int64_t)indptr_old[o], dst = (int64_t)indptr_new[r];
+        const int64_t deg = (int64_t)indptr_old[o + 1] - src;
+        for (int64_t i = lane; i < deg; i += 64) indices_new[dst + i] = perm_new_of_old[indices_old[src + i]];
+    }
 }
 
 template <typename T>
@@ -134,6 +135,7 @@ extern "C" dgi_status_t dgi_graph_free(dgi_graph_t* g) {
     (void)hipFree(g->d_rs_out);
     (void)hipFree(g->d_hub_rows);
     (void)hipFree(g->d_hub_chunk_ptr);
+    (void)hipFree(g->ws_ptr);
     delete g;
     return DGI_OK;
 }
@@ -268,7 +270,7 @@ extern "C" dgi_status_t dgi_graph_reorder(const dgi_graph_t* g, int32_t method, 
         if (!chk(hipMemcpyAsync(d_perm, perm.data(), N * 4, hipMemcpyHostToDevice, stream), "upload") ||
             !chk(hipMemcpyAsync(d_oon, old_of_new.data(), N * 4, hipMemcpyHostToDevice, stream), "upload"))
             return fail(DGI_ERR_DEVICE);
-        const int64_t blocks = (N * 64 + 255) / 256;
+        const int64_t blocks = std::min<int64_t>((N * 64 + 255) / 256, (int64_t)1 << 22);  // < 2^32 threads per launch
         if (g->itype == DGI_I64)
             hipLaunchKernelGGL(relabel_rows_kernel<int64_t>, dim3((unsigned)blocks), dim3(256), 0, stream, (const int64_t*)g->d_indptr,
                                g->d_indices, (const int64_t*)dip, d_oon, d_perm, N, d_unsorted);

@@ -6,6 +6,7 @@
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -63,6 +64,11 @@ struct dgi_graph {
     int64_t max_in_degree = 0;
     uint64_t device_bytes = 0;
     int device = 0;
+    // dgi_infer's arena (hidden layers + temporaries), kept between calls: allocating and freeing tens of
+    // gigabytes costs far more than the inference itself.  Guarded by ws_mutex for the whole call.
+    mutable std::mutex ws_mutex;
+    mutable char* ws_ptr = nullptr;
+    mutable uint64_t ws_bytes = 0;
 };
 
 namespace dgi {

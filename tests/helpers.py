@@ -52,3 +52,57 @@ def act_np(x, act, slope=1.0):
     if act == "leaky_relu":
         return np.where(x > 0, x, slope * x)
     return x
+
+
+# ---- node-wise evaluation of sampled targets on a big graph (Algorithm 1, with the per-layer target sets
+# V^l of Section 3.3): only index plumbing lives here, the arithmetic is the oracle's. ---------------------
+def _gather_rows(indptr, indices, rows):
+    """Concatenated in-neighbour lists of `rows` (torch tensors, any device) and the per-row counts."""
+    import torch
+    start = indptr[rows].to(torch.int64)
+    cnt = indptr[rows + 1].to(torch.int64) - start
+    total = int(cnt.sum())
+    if total == 0:
+        return indices.new_empty(0, dtype=torch.int64), cnt
+    seg_first = torch.cumsum(cnt, 0) - cnt
+    pos = torch.arange(total, device=indptr.device) - torch.repeat_interleave(seg_first, cnt)
+    return indices[torch.repeat_interleave(start, cnt) + pos].to(torch.int64), cnt
+
+
+def nodewise_oracle(indptr, indices, x, layers_np, targets, num_layers, x_is_bf16=False):
+    """Final-layer rows of `targets`, computed by the CPU oracle from the targets' L-hop in-neighbourhood
+    only.  indptr / indices / x: torch tensors of the FULL graph (on the GPU for the big configs);
+    layers_np: numpy layer dicts.  Works for aggregators that use no global out-degree (sum, mean, gat)."""
+    import numpy as np
+    import torch
+    from oracle import oracle
+    dev = indptr.device
+    n = indptr.numel() - 1
+    targets = torch.as_tensor(targets, dtype=torch.int64, device=dev)
+    # need[l] = nodes whose layer-l embedding is required; need[L] = targets, need[l-1] = need[l] ∪ N(need[l])
+    need = [None] * (num_layers + 1)
+    need[num_layers] = torch.unique(targets)
+    for l in range(num_layers, 0, -1):
+        nb, _ = _gather_rows(indptr, indices, need[l])
+        need[l - 1] = torch.unique(torch.cat([need[l], nb]))
+    U = need[0]                                   # sorted global ids of every node touched
+    # sub-CSR over U: rows of need[1] are complete (all their in-neighbours are in U); other rows are empty
+    interior = need[1]
+    nb, cnt = _gather_rows(indptr, indices, interior)
+    deg = torch.zeros(U.numel(), dtype=torch.int64, device=dev)
+    deg[torch.searchsorted(U, interior)] = cnt
+    sub_indptr = torch.zeros(U.numel() + 1, dtype=torch.int64, device=dev)
+    torch.cumsum(deg, 0, out=sub_indptr[1:])
+    # rows are written in ascending local id == ascending global id == the order of `interior`
+    sub_indices = torch.searchsorted(U, nb).to(torch.int32)
+    ip, ix = sub_indptr.cpu().numpy(), sub_indices.cpu().numpy()
+    h = x[U].float().cpu().numpy()
+    for l in range(1, num_layers + 1):
+        rows_local = torch.searchsorted(U, need[l]).cpu().numpy()
+        part = oracle.layer_forward(ip, ix, layers_np[l - 1], h, rows=rows_local)
+        if l == num_layers:
+            full = {int(g): part[i] for i, g in enumerate(need[l].cpu().numpy())}
+            return np.stack([full[int(t)] for t in targets.cpu().numpy()])
+        nxt = np.zeros((U.numel(), part.shape[1]), dtype=np.float32)
+        nxt[rows_local] = part
+        h = nxt
