@@ -20,11 +20,12 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
 
-def algorithmic_bytes(n, e, width, elem, indptr_bytes, heads=0):
+def algorithmic_bytes(n, e, width, elem, indptr_bytes, heads=0, out_width=None, out_elem=None, self_width=0):
     """Bytes the aggregation of one layer must move when nothing is reused: per edge one source row and
-    its index (plus the GAT score terms), per destination node its indptr entry and its output row."""
+    its index (plus the GAT score terms), per destination node its indptr entry and its output row (for
+    the fused kernel the output row is the layer output, plus the node's own input row for GraphSAGE)."""
     per_edge = width * elem + 4 + 4 * heads
-    per_node = indptr_bytes + width * elem
+    per_node = indptr_bytes + (width * elem if out_width is None else out_width * out_elem) + self_width * elem
     return e * per_edge + n * per_node
 
 
@@ -45,7 +46,7 @@ def measured_traffic(workload, layer):
     return None
 
 
-def cpu_baseline(cfg, target_seconds=15.0):
+def cpu_baseline(cfg, target_seconds=30.0):
     """The CPU oracle, as it stands, on a bounded sample of the same workload: every layer of the model on
     the first R destination rows of the full graph (synthetic N(0,1) inputs of each layer's width stand in
     for the hidden layers), all host threads.  R is sized from a short calibration pass so that the sample
@@ -211,7 +212,16 @@ def main():
     is_gat = L["agg"] == "gat"
     elem = 2 if (storage == "bf16" and (dom == 0 or cfg["layers"][dom - 1].get("out_storage") == "bf16")) else 4
     ipb = 8 if info["indptr_type"] == 1 else 4
-    bytes_layer = algorithmic_bytes(n, e, width, elem, ipb, heads=L.get("heads", 1) if is_gat else 0)
+    fused = bool(stats[0]["fused"][dom])
+    if fused:
+        # the fused kernel gathers the edges of the non-hub rows; hub rows arrive pre-aggregated (fp32) from the
+        # hub pre-pass, whose time is reported separately
+        out_elem = 2 if L.get("out_storage") == "bf16" else 4
+        bytes_layer = algorithmic_bytes(n, e - info["num_hub_edges"], width, elem, ipb, out_width=int(L["W_neigh"].shape[1]),
+                                        out_elem=out_elem, self_width=width if L.get("W_self") is not None else 0)
+        bytes_layer += info["num_hub_rows"] * width * 4
+    else:
+        bytes_layer = algorithmic_bytes(n, e, width, elem, ipb, heads=L.get("heads", 1) if is_gat else 0)
     avg_launch_ms = agg_ms[dom] / max(agg_launches[dom], 1)
     achieved = bytes_layer * args.steps / (agg_ms[dom] * 1e-3) / 1e9  # GB/s over all launches of that kernel
     result = {
@@ -229,14 +239,16 @@ def main():
         "dtype": "bf16" if storage == "bf16" else "f32",
         "data": "synthetic",
         "config": {"workload": cfg["name"], "num_nodes": n, "num_edges": e, "max_in_degree": info["max_in_degree"],
-                   "hub_rows": info["num_hub_rows"], "scale": args.scale, "batch_size": args.batch_size or "dynamic",
-                   "batches_per_layer": stats[-1]["batches"], "transform_first": stats[-1]["transform_first"],
+                   "hub_rows": info["num_hub_rows"], "hub_edges": info["num_hub_edges"], "scale": args.scale, "batch_size": args.batch_size or "dynamic",
+                   "batches_per_layer": stats[-1]["batches"], "transform_first": stats[-1]["transform_first"], "fused": stats[-1]["fused"],
                    "generate_seconds": round(t_gen, 2)},
         "per_layer_ms": {"layer": [round(sum(s["layer_ms"][l] for s in stats) / args.steps, 3) for l in range(n_layers)],
-                         "aggregate": [round(a / args.steps, 3) for a in agg_ms], "gemm": [round(v, 3) for v in gemm_ms]},
+                         "aggregate": [round(a / args.steps, 3) for a in agg_ms], "gemm": [round(v, 3) for v in gemm_ms],
+                         "hub_prepass": [round(sum(s["hub_ms"][l] for s in stats) / args.steps, 3) for l in range(n_layers)]},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(cfg["name"], dom + 1),
-                     "kernel": "aggregation launch of layer %d (gather width %d, %d-byte elements)" % (dom + 1, width, elem),
+                     "kernel": "%s launch of layer %d (gather width %d, %d-byte elements)"
+                               % ("fused aggregate+transform" if fused else "aggregation", dom + 1, width, elem),
                      "algorithmic_bytes_per_launch": bytes_layer * args.steps / max(agg_launches[dom], 1),
                      "avg_launch_ms": avg_launch_ms, "launches": agg_launches[dom],
                      "launches_per_layer_pass": agg_launches[dom] / args.steps},

@@ -59,8 +59,15 @@ typedef enum { DGI_ACT_NONE = 0, DGI_ACT_RELU = 1, DGI_ACT_ELU = 2, DGI_ACT_LEAK
 
 /* Whether the dense transform runs before or after the neighbour aggregation.  Both give the same
  * result up to rounding, because aggregation is linear.  AUTO = transform first iff out_dim < in_dim
- * (GAT is always transform-first). */
-typedef enum { DGI_ORDER_AUTO = 0, DGI_ORDER_AGG_FIRST = 1, DGI_ORDER_TRANSFORM_FIRST = 2 } dgi_order_t;
+ * (GAT is always transform-first).  An aggregate-first layer runs either as one kernel that keeps the
+ * aggregated tile in LDS and feeds it to the matrix cores (FUSED), or as an aggregation kernel followed by a
+ * GEMM (SPLIT); AUTO and AGG_FIRST choose between the two from the graph's average degree and the layer
+ * widths.  FUSED falls back to SPLIT for layouts the fused kernel does not take (rows not 16-byte aligned,
+ * in_dim not a multiple of 16 bytes or at most 8 x 16 bytes, tile larger than LDS). */
+typedef enum {
+    DGI_ORDER_AUTO = 0, DGI_ORDER_AGG_FIRST = 1, DGI_ORDER_TRANSFORM_FIRST = 2,
+    DGI_ORDER_AGG_FIRST_FUSED = 3, DGI_ORDER_AGG_FIRST_SPLIT = 4
+} dgi_order_t;
 
 /* Node renumbering used to form batches of consecutive ids that share in-neighbours (Section 4.2).
  *   DEGREE : descending in-degree, ties by old id ("Degree Sorting" of Section 5.3)
@@ -99,7 +106,9 @@ typedef struct {
     int32_t reserved;
     double  total_ms;                       /* whole dgi_infer, first enqueue to last completion */
     double  layer_ms[DGI_MAX_LAYERS];
-    double  agg_ms[DGI_MAX_LAYERS];         /* gather/aggregate (or GAT edge) kernels, summed over batches */
+    double  agg_ms[DGI_MAX_LAYERS];         /* the layer's main gather kernel (aggregate, fused aggregate+transform, or
+                                               GAT edge kernel), summed over batches; one launch per batch */
+    double  hub_ms[DGI_MAX_LAYERS];         /* fused layers only: the hub pre-pass (chunk launch + reduce), summed over batches */
     double  gemm_ms[DGI_MAX_LAYERS];        /* dense transform kernels, summed over batches */
     int64_t agg_launches[DGI_MAX_LAYERS];
     int64_t gemm_launches[DGI_MAX_LAYERS];
@@ -107,6 +116,7 @@ typedef struct {
     int64_t edges[DGI_MAX_LAYERS];          /* edges aggregated by the layer (= E for full inference) */
     int32_t transform_first[DGI_MAX_LAYERS];
     int32_t gather_width[DGI_MAX_LAYERS];   /* elements per gathered source row */
+    int32_t fused[DGI_MAX_LAYERS];          /* 1: aggregation and transform ran as one kernel (its time is in agg_ms) */
     int64_t oom_retries;                    /* batches redone after halving the thresholds (Sec. 4.1) */
     int64_t workspace_bytes;                /* peak bytes the library allocated for this call */
 } dgi_stats_t;
@@ -128,6 +138,7 @@ typedef struct {
     int64_t num_edges;
     int64_t max_in_degree;
     int64_t num_hub_rows;     /* rows long enough to be split over several workgroups */
+    int64_t num_hub_edges;    /* in-edges of those rows */
     int32_t indptr_type;      /* dgi_itype_t */
     int32_t reserved;
     uint64_t device_bytes;    /* device memory owned by the handle */

@@ -19,7 +19,7 @@ HOST, DEVICE = 0, 1
 F32, BF16 = 0, 1
 AGG = {"sum": 0, "mean": 1, "gcn": 2, "gat": 3}
 ACT = {"none": 0, "relu": 1, "elu": 2, "leaky_relu": 3}
-ORDER = {"auto": 0, "agg_first": 1, "transform_first": 2}
+ORDER = {"auto": 0, "agg_first": 1, "transform_first": 2, "agg_first_fused": 3, "agg_first_split": 4}
 REORDER = {"none": 0, "degree": 1, "bfs_rcm": 2, "random": 3}
 MAX_LAYERS = 16
 
@@ -45,10 +45,12 @@ class StatsStruct(ctypes.Structure):
     _fields_ = [
         ("num_layers", ctypes.c_int32), ("reserved", ctypes.c_int32), ("total_ms", ctypes.c_double),
         ("layer_ms", ctypes.c_double * MAX_LAYERS), ("agg_ms", ctypes.c_double * MAX_LAYERS),
+        ("hub_ms", ctypes.c_double * MAX_LAYERS),
         ("gemm_ms", ctypes.c_double * MAX_LAYERS), ("agg_launches", ctypes.c_int64 * MAX_LAYERS),
         ("gemm_launches", ctypes.c_int64 * MAX_LAYERS), ("batches", ctypes.c_int64 * MAX_LAYERS),
         ("edges", ctypes.c_int64 * MAX_LAYERS), ("transform_first", ctypes.c_int32 * MAX_LAYERS),
-        ("gather_width", ctypes.c_int32 * MAX_LAYERS), ("oom_retries", ctypes.c_int64),
+        ("gather_width", ctypes.c_int32 * MAX_LAYERS), ("fused", ctypes.c_int32 * MAX_LAYERS),
+        ("oom_retries", ctypes.c_int64),
         ("workspace_bytes", ctypes.c_int64),
     ]
 
@@ -64,7 +66,7 @@ class OptsStruct(ctypes.Structure):
 class GraphInfoStruct(ctypes.Structure):
     _fields_ = [
         ("num_nodes", ctypes.c_int64), ("num_edges", ctypes.c_int64), ("max_in_degree", ctypes.c_int64),
-        ("num_hub_rows", ctypes.c_int64), ("indptr_type", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("num_hub_rows", ctypes.c_int64), ("num_hub_edges", ctypes.c_int64), ("indptr_type", ctypes.c_int32), ("reserved", ctypes.c_int32),
         ("device_bytes", ctypes.c_uint64),
     ]
 

@@ -54,6 +54,27 @@ struct AggParams {
     int wpad;
     int64_t n_chunks;    // hub chunks in the range
     int64_t hub_blocks;  // leading workgroups of the launch that work on hub chunks (multiple of 64)
+    int hub_compact;     // hub reduce writes row (h - hub_begin) of `out` instead of row (v - out_row0)
+};
+
+// The fused layer kernel: gather description + the dense transform that consumes the aggregated tile.
+struct FusedParams {
+    AggParams a;           // S = H^{l-1}, width = K; out/self/bias/act unused
+    const void* Wt;        // packed transposed weights [N x ldw]: self block at column 0, neighbour block at K1p
+    int64_t ldw;
+    int K1p;
+    int has_self;
+    int N;
+    const float* bias;
+    int act;
+    float act_slope;
+    void* out;
+    int64_t ld_out;
+    int64_t out_row0;
+    int out_bf16;
+    const float* hub_agg;  // aggregated and scaled hub rows of the range, in hub order, fp32 [n_hubs x hub_ld]
+    int64_t hub_ld;
+    int lds_ld;            // elements per row of the LDS tile
 };
 
 __device__ __forceinline__ float bf16_to_float(uint32_t hi16) { return __uint_as_float(hi16 << 16); }
@@ -178,12 +199,12 @@ __device__ __forceinline__ void combine_groups(float (&acc)[VEC]) {
 
 // scale, self addend, bias, activation, store of one output element
 template <typename T>
-__device__ __forceinline__ void finish_store(const AggParams& p, int64_t v, int c, float sum, float scale) {
+__device__ __forceinline__ void finish_store(const AggParams& p, int64_t v, int64_t out_row, int c, float sum, float scale) {
     float val = sum * scale;
     if (p.self) val += Row<T>::one(static_cast<const T*>(p.self) + v * p.ld_self + c);
     if (p.bias) val += p.bias[c];
     val = activate(val, p.act, p.act_slope);
-    const int64_t o = (v - p.out_row0) * p.ld_out + c;
+    const int64_t o = out_row * p.ld_out + c;
     if (p.out_bf16) static_cast<uint16_t*>(p.out)[o] = float_to_bf16(val);
     else static_cast<float*>(p.out)[o] = val;
 }
@@ -267,7 +288,7 @@ __device__ __forceinline__ void rows_tile(const AggParams& p, int64_t bid) {
                 } else {
 #pragma unroll
                     for (int i = 0; i < VEC; ++i)
-                        if (c + i < p.width) finish_store<T>(p, v, c + i, acc[i], scale);
+                        if (c + i < p.width) finish_store<T>(p, v, v - p.out_row0, c + i, acc[i], scale);
                 }
             }
         }
@@ -318,6 +339,170 @@ __global__ __launch_bounds__(kWaves * 64) void agg_kernel(AggParams p) {
     else rows_tile<T, IdxT, G, MODE>(p, bid - p.hub_blocks);
 }
 
+
+typedef float floatx16_t __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+constexpr int kFusedRows = 32;  // destination rows per workgroup = one MFMA row block
+
+template <typename T>
+__device__ __forceinline__ uint4 pack_row_chunk(const float* f) {  // VEC floats -> 16 bytes of T
+    if (sizeof(T) == 4) return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+    return make_uint4((uint32_t)float_to_bf16(f[0]) | ((uint32_t)float_to_bf16(f[1]) << 16),
+                      (uint32_t)float_to_bf16(f[2]) | ((uint32_t)float_to_bf16(f[3]) << 16),
+                      (uint32_t)float_to_bf16(f[4 % Row<T>::VEC]) | ((uint32_t)float_to_bf16(f[5 % Row<T>::VEC]) << 16),
+                      (uint32_t)float_to_bf16(f[6 % Row<T>::VEC]) | ((uint32_t)float_to_bf16(f[7 % Row<T>::VEC]) << 16));
+}
+
+// Aggregation fused with the layer's dense transform (aggregate-first layers).  A workgroup owns 32
+// destination rows.  Phase 1: its four wavefronts gather and aggregate 8 rows each exactly as the
+// stand-alone kernel does, but deposit the scaled result (and, for GraphSAGE, the row's own features) in an
+// LDS tile laid out like the packed weight's K axis.  Phase 2: the tile is the A operand of MFMA
+// (32 x K), B comes from the packed weight through L2, each wavefront owns every fourth 32-column block;
+// bias, activation and the output conversion happen in registers.  The aggregated matrix never exists
+// in HBM.  Hub rows arrive pre-aggregated (fp32) from the two-stage hub pass that runs before this launch.
+template <typename T, typename IdxT, int G, int MODE>
+__global__ __launch_bounds__(kWaves * 64) void fused_layer_kernel(FusedParams fp) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    T* tile = reinterpret_cast<T*>(lds_raw);
+    const AggParams& p = fp.a;
+    constexpr int VEC = Row<T>::VEC;  // elements per 16 bytes
+    constexpr int UNROLL = (G == 64) ? 8 : 4;
+    constexpr int RPW = kFusedRows / kWaves;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t tile_id = xcd_tile(blockIdx.x);
+    if (tile_id >= p.n_tiles) return;  // whole workgroup leaves together
+    const IdxT* indptr = static_cast<const IdxT*>(p.indptr);
+    const int sub = lane / G, gl = lane % G;
+    const int64_t vt = p.row_begin + tile_id * kFusedRows;
+    const int64_t vw = vt + wave * RPW;
+    const int K = p.width;
+    const int Kp = (K + 2 * VEC - 1) / (2 * VEC) * (2 * VEC);
+    const int chunks = Kp / VEC;
+
+    // ---- phase 1: aggregate 8 rows per wavefront into the tile ----------------------------------------
+    IdxT ipv = 0;
+    if (lane <= RPW) {
+        const int64_t i = vw + lane;
+        ipv = indptr[i < p.row_end ? i : p.row_end];
+    }
+    IdxT bound[RPW + 1];
+#pragma unroll
+    for (int i = 0; i <= RPW; ++i) bound[i] = bcast_lane<IdxT>(ipv, i);
+    int nxt = (int64_t)lane < (int64_t)(bound[1] - bound[0]) ? p.indices[(int64_t)bound[0] + lane] : 0;
+#pragma unroll
+    for (int r = 0; r < RPW; ++r) {
+        const int64_t v = vw + r;
+        T* trow = tile + (wave * RPW + r) * fp.lds_ld;
+        const IdxT eb = bound[r], ee = bound[r + 1];
+        const IdxT deg = ee - eb;
+        const int cur = nxt;
+        if (r + 1 < RPW) nxt = (int64_t)lane < (int64_t)(bound[r + 2 <= RPW ? r + 2 : RPW] - ee) ? p.indices[(int64_t)ee + lane] : 0;
+        if (v >= p.row_end) {  // rows past the range: an all-zero A row
+            for (int ch = lane; ch < (int)(fp.ldw / VEC); ch += 64) *reinterpret_cast<uint4*>(trow + ch * VEC) = make_uint4(0u, 0u, 0u, 0u);
+            continue;
+        }
+        if (fp.has_self) {  // the row's own features: columns [0, Kp) of the tile
+            const T* hrow = static_cast<const T*>(p.S) + v * p.ld_s;
+            for (int ch = lane; ch < chunks; ch += 64)
+                *reinterpret_cast<uint4*>(trow + ch * VEC) =
+                    ch * VEC < K ? *reinterpret_cast<const uint4*>(hrow + ch * VEC) : make_uint4(0u, 0u, 0u, 0u);
+        }
+        T* arow = trow + fp.K1p;
+        if (p.skip_hubs && deg > (IdxT)kHubDegree) {  // pre-aggregated by the hub pass
+            int64_t lo = p.hub_begin, hi = p.hub_end;
+            while (hi - lo > 1) {
+                const int64_t mid = (lo + hi) >> 1;
+                if (p.hub_rows[mid] <= v) lo = mid; else hi = mid;
+            }
+            const float* src = fp.hub_agg + (lo - p.hub_begin) * fp.hub_ld;
+            for (int ch = lane; ch < chunks; ch += 64) {
+                float f[VEC];
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) f[i] = ch * VEC + i < K ? src[ch * VEC + i] : 0.f;
+                *reinterpret_cast<uint4*>(arow + ch * VEC) = pack_row_chunk<T>(f);
+            }
+            continue;
+        }
+        const float scale = row_scale<MODE, IdxT>(p, v, deg);
+        for (int col0 = 0; col0 < Kp; col0 += G * VEC) {
+            float acc[VEC];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+            gather_range<T, G, MODE, UNROLL>(p, (int64_t)eb, (int64_t)ee, lane, col0, acc, true, cur);
+            combine_groups<G, VEC>(acc);
+            const int c = col0 + gl * VEC;
+            if (sub == 0 && c < Kp) {  // columns in [K, Kp) hold zeros (no lane gathered them)
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[i] *= scale;
+                *reinterpret_cast<uint4*>(arow + c) = pack_row_chunk<T>(acc);
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- phase 2: out[32 x N] = act(tile[32 x ldw] . Wt^T + bias) on the matrix cores -----------------
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int nblk = (fp.N + 31) / 32;
+    const T* a_base = tile + lrow * fp.lds_ld + lhalf * VEC;
+    const int ksteps = (int)(fp.ldw / (2 * VEC));
+    for (int cb = wave; cb < nblk; cb += kWaves) {
+        const int n = cb * 32 + lrow;
+        const T* w_base = static_cast<const T*>(fp.Wt) + (int64_t)(n < fp.N ? n : fp.N - 1) * fp.ldw + lhalf * VEC;
+        floatx16_t acc;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+        int ks = 0;
+        for (; ks + 4 <= ksteps; ks += 4) {
+            uint4 b[4], a[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) b[u] = *reinterpret_cast<const uint4*>(w_base + (ks + u) * 2 * VEC);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) a[u] = *reinterpret_cast<const uint4*>(a_base + (ks + u) * 2 * VEC);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (sizeof(T) == 4) {
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[u].x), __uint_as_float(b[u].x), acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[u].y), __uint_as_float(b[u].y), acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[u].z), __uint_as_float(b[u].z), acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[u].w), __uint_as_float(b[u].w), acc, 0, 0, 0);
+                } else {
+                    bf16x8_t av, bv;
+                    __builtin_memcpy(&av, &a[u], 16);
+                    __builtin_memcpy(&bv, &b[u], 16);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc, 0, 0, 0);
+                }
+            }
+        }
+        for (; ks < ksteps; ++ks) {
+            const uint4 b = *reinterpret_cast<const uint4*>(w_base + ks * 2 * VEC);
+            const uint4 a = *reinterpret_cast<const uint4*>(a_base + ks * 2 * VEC);
+            if (sizeof(T) == 4) {
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+            } else {
+                bf16x8_t av, bv;
+                __builtin_memcpy(&av, &a, 16);
+                __builtin_memcpy(&bv, &b, 16);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc, 0, 0, 0);
+            }
+        }
+        if (n < fp.N) {
+            const float bias = fp.bias ? fp.bias[n] : 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t v = vt + 8 * (r / 4) + 4 * lhalf + (r % 4);
+                if (v >= p.row_end) continue;
+                const float val = activate(acc[r] + bias, fp.act, fp.act_slope);
+                const int64_t o = (v - fp.out_row0) * fp.ld_out + n;
+                if (fp.out_bf16) static_cast<uint16_t*>(fp.out)[o] = float_to_bf16(val);
+                else static_cast<float*>(fp.out)[o] = val;
+            }
+        }
+    }
+}
+
 // One wavefront per hub row: add its partial rows in chunk order, then the epilogue.
 template <typename T, typename IdxT, int MODE>
 __global__ __launch_bounds__(kWaves * 64) void agg_hub_reduce_kernel(AggParams p) {
@@ -332,7 +517,7 @@ __global__ __launch_bounds__(kWaves * 64) void agg_hub_reduce_kernel(AggParams p
     for (int c = lane; c < p.width; c += 64) {
         float s = 0.f;
         for (int64_t q = q0; q < q1; ++q) s += p.partials[q * p.wpad + c];
-        finish_store<T>(p, v, c, s, scale);
+        finish_store<T>(p, v, p.hub_compact ? h - p.hub_begin : v - p.out_row0, c, s, scale);
     }
 }
 
@@ -353,7 +538,7 @@ __global__ __launch_bounds__(kWaves * 64) void agg_rows_generic_kernel(AggParams
             const float w = (MODE == MODE_GCN) ? p.rs_out[u] : 1.f;
             s = fmaf(w, Row<T>::one(S + u * p.ld_s + c), s);
         }
-        finish_store<T>(p, v, c, s, scale);
+        finish_store<T>(p, v, v - p.out_row0, c, s, scale);
     }
 }
 
@@ -436,7 +621,119 @@ dgi_status_t dispatch_mode(const AggParams& p, const dgi_graph* g, int mode, boo
     return DGI_ERR_INVALID_ARG;
 }
 
+// ---- fused path: hub pre-pass (chunks + compact reduce into hub_agg), then the fused layer kernel -------
+template <typename T, typename IdxT, int G, int MODE>
+dgi_status_t launch_fused_g(FusedParams fp, const dgi_graph* g, float* partials, float* hub_agg, int stage, hipStream_t stream) {
+    AggParams& p = fp.a;
+    constexpr int64_t kGroup = (int64_t)kXcds * kXcdRun;
+    const auto& hr = g->h_hub_rows;
+    const int64_t hb = std::lower_bound(hr.begin(), hr.end(), p.row_begin) - hr.begin();
+    const int64_t he = std::lower_bound(hr.begin(), hr.end(), p.row_end) - hr.begin();
+    p.hub_begin = hb;
+    p.hub_end = he;
+    p.skip_hubs = he > hb ? 1 : 0;
+    const int Kp = (int)round_up(p.width, 2 * Row<T>::VEC);
+    if (p.skip_hubs) {
+        DGI_REQUIRE(partials && hub_agg, DGI_ERR_INVALID_ARG, "fused: hub rows in range but no hub buffers");
+        AggParams h = p;  // hubs only: no row tiles in this launch
+        h.partials = partials;
+        h.chunk0 = g->h_hub_chunk_ptr[hb];
+        h.n_chunks = g->h_hub_chunk_ptr[he] - h.chunk0;
+        h.hub_blocks = round_up((h.n_chunks + kWaves - 1) / kWaves, kGroup);
+        h.n_tiles = 0;
+        h.out = hub_agg; h.ld_out = Kp; h.out_row0 = 0; h.out_bf16 = 0; h.out_vec_ok = 0; h.hub_compact = 1;
+        h.self = nullptr; h.bias = nullptr; h.act = DGI_ACT_NONE;
+        DGI_REQUIRE(h.hub_blocks * kWaves * 64 < (int64_t)1 << 32, DGI_ERR_INVALID_ARG, "fused: too many hub chunks for one launch");
+        if (stage == 0) {
+            hipLaunchKernelGGL((agg_kernel<T, IdxT, G, MODE>), dim3((unsigned)h.hub_blocks), dim3(kWaves * 64), 0, stream, h);
+            DGI_HIP(hipGetLastError());
+            hipLaunchKernelGGL((agg_hub_reduce_kernel<T, IdxT, MODE>), dim3((unsigned)((he - hb + kWaves - 1) / kWaves)),
+                               dim3(kWaves * 64), 0, stream, h);
+            DGI_HIP(hipGetLastError());
+        }
+        fp.hub_agg = hub_agg;
+        fp.hub_ld = Kp;
+    }
+    if (stage == 0) return DGI_OK;
+    const int64_t rows = p.row_end - p.row_begin;
+    p.n_tiles = (rows + kFusedRows - 1) / kFusedRows;
+    const int64_t grid = round_up(p.n_tiles, kGroup);
+    DGI_REQUIRE(grid * kWaves * 64 < (int64_t)1 << 32, DGI_ERR_INVALID_ARG, "fused: row range too large for one launch");
+    const size_t lds = (size_t)kFusedRows * fp.lds_ld * sizeof(T);
+    auto kernel = fused_layer_kernel<T, IdxT, G, MODE>;
+    if (lds > 48 * 1024)
+        DGI_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kWaves * 64), lds, stream, fp);
+    DGI_HIP(hipGetLastError());
+    return DGI_OK;
+}
+
+template <typename T, typename IdxT, int MODE>
+dgi_status_t launch_fused_mode(const FusedParams& fp, const dgi_graph* g, float* partials, float* hub_agg, int stage, hipStream_t stream) {
+    const int lanes = (fp.a.width + Row<T>::VEC - 1) / Row<T>::VEC;
+    if (lanes <= 16) return launch_fused_g<T, IdxT, 16, MODE>(fp, g, partials, hub_agg, stage, stream);
+    if (lanes <= 32) return launch_fused_g<T, IdxT, 32, MODE>(fp, g, partials, hub_agg, stage, stream);
+    return launch_fused_g<T, IdxT, 64, MODE>(fp, g, partials, hub_agg, stage, stream);
+}
+
+template <typename T, typename IdxT>
+dgi_status_t launch_fused_t(const FusedParams& fp, const dgi_graph* g, int mode, float* partials, float* hub_agg, int stage, hipStream_t stream) {
+    switch (mode) {
+        case MODE_SUM: return launch_fused_mode<T, IdxT, MODE_SUM>(fp, g, partials, hub_agg, stage, stream);
+        case MODE_MEAN: return launch_fused_mode<T, IdxT, MODE_MEAN>(fp, g, partials, hub_agg, stage, stream);
+        case MODE_GCN: return launch_fused_mode<T, IdxT, MODE_GCN>(fp, g, partials, hub_agg, stage, stream);
+    }
+    set_error("unknown aggregation mode %d", mode);
+    return DGI_ERR_INVALID_ARG;
+}
+
 }  // namespace
+
+constexpr size_t kFusedMaxLds = 128 * 1024;
+
+bool fused_supported(const FusedArgs& a) {
+    const int eb = a.dtype == DGI_BF16 ? 2 : 4, E = 16 / eb;
+    if ((uintptr_t)a.H % 16 || (a.ld_h * eb) % 16 || a.K % E || a.K / E <= 8) return false;
+    if ((uintptr_t)a.Wt % 16 || a.ldw % (2 * E) || a.K1p % (2 * E)) return false;
+    if (a.ldw != a.K1p + round_up(a.K, 2 * E)) return false;
+    return (size_t)kFusedRows * (size_t)(a.ldw + E) * eb <= kFusedMaxLds;
+}
+
+uint64_t fused_temp_bytes(const dgi_graph* g, int64_t row_begin, int64_t row_end, int K) {
+    const auto& hr = g->h_hub_rows;
+    const int64_t hb = std::lower_bound(hr.begin(), hr.end(), row_begin) - hr.begin();
+    const int64_t he = std::lower_bound(hr.begin(), hr.end(), row_end) - hr.begin();
+    if (he <= hb) return 0;
+    return (uint64_t)round_up((int64_t)agg_hub_partial_bytes(g, row_begin, row_end, K), 256) +
+           (uint64_t)round_up((he - hb) * round_up(K, 16) * 4, 256);
+}
+
+dgi_status_t launch_fused(const FusedArgs& a, int stage, hipStream_t stream) {
+    if (a.row_end <= a.row_begin) return DGI_OK;
+    const dgi_graph* g = a.g;
+    DGI_REQUIRE(a.row_begin >= 0 && a.row_end <= g->N, DGI_ERR_INVALID_ARG, "fused: row range outside the graph");
+    DGI_REQUIRE(fused_supported(a), DGI_ERR_UNSUPPORTED, "fused: layout not supported");
+    const int eb = a.dtype == DGI_BF16 ? 2 : 4, E = 16 / eb;
+    FusedParams fp{};
+    AggParams& p = fp.a;
+    p.indptr = g->d_indptr; p.indices = g->d_indices; p.rs_out = g->d_rs_out; p.rs_in = g->d_rs_in;
+    p.S = a.H; p.ld_s = a.ld_h; p.width = a.K;
+    p.row_begin = a.row_begin; p.row_end = a.row_end;
+    p.hub_rows = g->d_hub_rows; p.hub_chunk_ptr = g->d_hub_chunk_ptr;
+    p.wpad = (int)round_up(a.K, 8);
+    fp.Wt = a.Wt; fp.ldw = a.ldw; fp.K1p = a.K1p; fp.has_self = a.has_self ? 1 : 0; fp.N = a.N;
+    fp.bias = a.bias; fp.act = a.act; fp.act_slope = a.act_slope;
+    fp.out = a.out; fp.ld_out = a.ld_out; fp.out_row0 = a.out_row0; fp.out_bf16 = a.out_dtype == DGI_BF16;
+    fp.lds_ld = (int)(a.ldw + E);
+    float* partials = static_cast<float*>(a.temp);
+    float* hub_agg = a.temp ? reinterpret_cast<float*>(static_cast<char*>(a.temp) + round_up((int64_t)agg_hub_partial_bytes(g, a.row_begin, a.row_end, a.K), 256)) : nullptr;
+    const bool i64 = g->itype == DGI_I64;
+    if (a.dtype == DGI_BF16)
+        return i64 ? launch_fused_t<uint16_t, int64_t>(fp, g, a.mode, partials, hub_agg, stage, stream)
+                   : launch_fused_t<uint16_t, int32_t>(fp, g, a.mode, partials, hub_agg, stage, stream);
+    return i64 ? launch_fused_t<float, int64_t>(fp, g, a.mode, partials, hub_agg, stage, stream)
+               : launch_fused_t<float, int32_t>(fp, g, a.mode, partials, hub_agg, stage, stream);
+}
 
 uint64_t agg_hub_partial_bytes(const dgi_graph* g, int64_t row_begin, int64_t row_end, int width) {
     const auto& hr = g->h_hub_rows;

@@ -3,6 +3,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdarg>
+#include <cstdlib>
 #include <cstring>
 #include <unordered_set>
 
@@ -44,9 +45,23 @@ struct LayerPlan {
     int64_t z_ld = 0;
     int z_neigh_col = 0;  // first column of the neighbour block in Z
     int z_dtype = DGI_F32;
-    // aggregate-first: AGG tile of the batch
+    // aggregate-first: AGG tile of the batch (unfused path only)
     int64_t agg_ld = 0;
+    bool fused = false;   // aggregate-first with the transform fused into the gather kernel
 };
+
+// Fusing the transform into the gather kernel removes the aggregated matrix's HBM round trip, but every
+// 32-row tile re-reads the packed weight from L2.  It pays when a row's gather (avg_degree * K elements)
+// outweighs its share of that re-read (ldw * N / 32 elements) by a wide margin; measured on MI355X the
+// break-even is a ratio of about 2 (GCN 256->256 at degree 52: ratio 6.5, 15 % faster fused; GraphSAGE
+// bf16 128->128 at degree 14: ratio 1.8, 40 % slower fused).  DGI_TUNE_FUSED = 0 / 2 forces never / always.
+bool want_fused(const dgi_graph* g, int K, int64_t ldw, int N) {
+    static const int mode = [] { const char* e = getenv("DGI_TUNE_FUSED"); return e ? atoi(e) : 1; }();
+    if (mode == 0) return false;
+    if (mode == 2) return true;
+    const double avg_deg = g && g->N > 0 ? (double)g->E / (double)g->N : 0.0;
+    return avg_deg * (double)K >= 3.0 * ((double)ldw * (double)N / 32.0);
+}
 
 dgi_status_t validate_layer(const dgi_layer_t* L) {
     DGI_REQUIRE(L != nullptr, DGI_ERR_INVALID_ARG, "layer is NULL");
@@ -56,17 +71,19 @@ dgi_status_t validate_layer(const dgi_layer_t* L) {
     DGI_REQUIRE(L->W_neigh != nullptr, DGI_ERR_INVALID_ARG, "W_neigh is NULL");
     DGI_REQUIRE((L->feat_dtype == DGI_F32 || L->feat_dtype == DGI_BF16) && (L->out_dtype == DGI_F32 || L->out_dtype == DGI_BF16),
                 DGI_ERR_INVALID_ARG, "unknown dtype");
-    DGI_REQUIRE(L->order >= DGI_ORDER_AUTO && L->order <= DGI_ORDER_TRANSFORM_FIRST, DGI_ERR_INVALID_ARG, "unknown order %d", L->order);
+    DGI_REQUIRE(L->order >= DGI_ORDER_AUTO && L->order <= DGI_ORDER_AGG_FIRST_SPLIT, DGI_ERR_INVALID_ARG, "unknown order %d", L->order);
     if (L->agg == DGI_AGG_GAT) {
         DGI_REQUIRE(L->heads >= 1 && L->out_dim % L->heads == 0, DGI_ERR_INVALID_ARG, "GAT: out_dim must be heads*head_dim");
         DGI_REQUIRE(L->attn_src && L->attn_dst, DGI_ERR_INVALID_ARG, "GAT: attention vectors are NULL");
         DGI_REQUIRE(L->feat_dtype == DGI_F32, DGI_ERR_UNSUPPORTED, "GAT runs on fp32 features only");
-        DGI_REQUIRE(L->order != DGI_ORDER_AGG_FIRST, DGI_ERR_UNSUPPORTED, "GAT is transform-first by definition");
+        DGI_REQUIRE(L->order == DGI_ORDER_AUTO || L->order == DGI_ORDER_TRANSFORM_FIRST, DGI_ERR_UNSUPPORTED,
+                    "GAT is transform-first by definition");
     }
     return DGI_OK;
 }
 
-dgi_status_t plan_layer(const dgi_layer_t* L, LayerPlan* P) {
+// h_in / ld_in: the layer's input as it will be passed (its alignment decides which kernels can run).
+dgi_status_t plan_layer(const dgi_graph* g, const dgi_layer_t* L, const void* h_in, int64_t ld_in, LayerPlan* P) {
     DGI_TRY(validate_layer(L));
     LayerPlan p;
     p.eb = elem_bytes(L->feat_dtype);
@@ -87,10 +104,17 @@ dgi_status_t plan_layer(const dgi_layer_t* L, LayerPlan* P) {
         p.w_rows = p.z_neigh_col + L->out_dim;
         p.z_cols = p.w_rows; p.z_ld = round_up(p.z_cols, p.E); p.z_dtype = L->feat_dtype;
     } else {
-        p.K1p = p.has_self ? in_p : 0;
-        p.ldw = p.K1p + in_p;
+        const int in_p2 = (int)round_up(L->in_dim, 2 * p.E);  // MFMA k-step granularity of the fused kernel
+        p.K1p = p.has_self ? in_p2 : 0;
+        p.ldw = p.K1p + in_p2;
         p.w_rows = L->out_dim;
         p.agg_ld = in_p;
+        FusedArgs fa;
+        fa.H = h_in; fa.ld_h = ld_in; fa.dtype = L->feat_dtype; fa.K = L->in_dim;
+        fa.Wt = nullptr; fa.ldw = p.ldw; fa.K1p = p.K1p;
+        const bool want = L->order == DGI_ORDER_AGG_FIRST_FUSED ||
+                          (L->order != DGI_ORDER_AGG_FIRST_SPLIT && want_fused(g, L->in_dim, p.ldw, L->out_dim));
+        p.fused = want && fused_supported(fa);
     }
     p.wt_bytes = (uint64_t)round_up((int64_t)p.w_rows * p.ldw * p.eb, 256);
     *P = p;
@@ -132,6 +156,7 @@ dgi_status_t run_transform(const dgi_layer_t* L, const LayerPlan& P, const void*
 }
 
 uint64_t batch_temp_bytes(const dgi_graph* g, const dgi_layer_t* L, const LayerPlan& P, int64_t b, int64_t e) {
+    if (P.fused) return fused_temp_bytes(g, b, e, L->in_dim);
     uint64_t bytes = 0;
     if (!P.gat) bytes += round_up((int64_t)agg_hub_partial_bytes(g, b, e, P.transform_first ? L->out_dim : L->in_dim), 256);
     if (!P.transform_first) bytes += (uint64_t)round_up((e - b) * P.agg_ld * P.eb, 256);
@@ -163,7 +188,7 @@ struct KernelTimer {
     }
     dgi_status_t end() { DGI_HIP(hipEventRecord(spans.back().b, stream)); return DGI_OK; }
 };
-enum { SPAN_AGG = 0, SPAN_GEMM = 1, SPAN_LAYER = 2, SPAN_TOTAL = 3 };
+enum { SPAN_AGG = 0, SPAN_GEMM = 1, SPAN_LAYER = 2, SPAN_TOTAL = 3, SPAN_HUB = 4 };
 
 dgi_status_t run_batch(const dgi_graph* g, const dgi_layer_t* L, const LayerPlan& P, const void* h_in, int64_t ld_in,
                        void* h_out, int64_t ld_out, int64_t b, int64_t e, const void* Wt, const void* Z, void* temp,
@@ -195,6 +220,24 @@ dgi_status_t run_batch(const dgi_graph* g, const dgi_layer_t* L, const LayerPlan
         DGI_TRY(launch_aggregate(a, 0, s));
         if (timer) DGI_TRY(timer->end());
         return launch_aggregate(a, 1, s);
+    }
+    if (P.fused) {
+        FusedArgs fa;
+        fa.g = g; fa.mode = P.mode; fa.H = h_in; fa.ld_h = ld_in; fa.dtype = L->feat_dtype; fa.K = L->in_dim;
+        fa.Wt = Wt; fa.ldw = P.ldw; fa.K1p = P.K1p; fa.has_self = P.has_self; fa.N = L->out_dim;
+        fa.bias = L->bias; fa.act = L->act; fa.act_slope = L->act_slope;
+        fa.out = (char*)h_out + b * ld_out * ob; fa.ld_out = ld_out; fa.out_row0 = b; fa.out_dtype = L->out_dtype;
+        fa.row_begin = b; fa.row_end = e;
+        fa.temp = fused_temp_bytes(g, b, e, L->in_dim) ? temp : nullptr;
+        if (fa.temp) {
+            if (timer) DGI_TRY(timer->begin(SPAN_HUB));
+            DGI_TRY(launch_fused(fa, 0, s));
+            if (timer) DGI_TRY(timer->end());
+        }
+        if (timer) DGI_TRY(timer->begin(SPAN_AGG));
+        DGI_TRY(launch_fused(fa, 1, s));
+        if (timer) DGI_TRY(timer->end());
+        return DGI_OK;
     }
     void* agg = (char*)temp + part_bytes;
     a.S = h_in; a.ld_s = ld_in; a.s_dtype = L->feat_dtype; a.width = L->in_dim;
@@ -274,9 +317,11 @@ extern "C" dgi_status_t dgi_layer_workspace_bytes(const dgi_graph_t* g, const dg
                                                   int64_t dst_end, uint64_t* bytes) {
     DGI_REQUIRE(g && bytes, DGI_ERR_INVALID_ARG, "layer_workspace_bytes: NULL argument");
     DGI_REQUIRE(dst_begin >= 0 && dst_end >= dst_begin && dst_end <= g->N, DGI_ERR_INVALID_ARG, "bad destination range");
-    LayerPlan P;
-    DGI_TRY(plan_layer(layer, &P));
-    *bytes = forward_layout(g, layer, P, dst_begin, dst_end).total;
+    // sized for the unfused path as well, so that any input alignment given to dgi_layer_forward fits
+    LayerPlan P, Q;
+    DGI_TRY(plan_layer(g, layer, reinterpret_cast<const void*>(16), 0, &P));
+    DGI_TRY(plan_layer(g, layer, reinterpret_cast<const void*>(1), 1, &Q));
+    *bytes = std::max(forward_layout(g, layer, P, dst_begin, dst_end).total, forward_layout(g, layer, Q, dst_begin, dst_end).total);
     return DGI_OK;
 }
 
@@ -285,7 +330,7 @@ extern "C" dgi_status_t dgi_layer_forward(const dgi_graph_t* g, const dgi_layer_
                                           uint64_t workspace_bytes, void* hip_stream) {
     DGI_REQUIRE(g != nullptr, DGI_ERR_INVALID_ARG, "graph is NULL");
     LayerPlan P;
-    DGI_TRY(plan_layer(layer, &P));
+    DGI_TRY(plan_layer(g, layer, h_in, ld_in, &P));
     DGI_REQUIRE(dst_begin >= 0 && dst_end >= dst_begin && dst_end <= g->N, DGI_ERR_INVALID_ARG,
                 "bad destination range [%lld,%lld) for %lld nodes", (long long)dst_begin, (long long)dst_end, (long long)g->N);
     if (g->N == 0 || dst_end == dst_begin) return DGI_OK;
@@ -308,7 +353,11 @@ extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layer
     DGI_REQUIRE(num_layers >= 1 && num_layers <= DGI_MAX_LAYERS, DGI_ERR_INVALID_ARG, "infer: 1..%d layers supported", DGI_MAX_LAYERS);
     std::vector<LayerPlan> plans((size_t)num_layers);
     for (int l = 0; l < num_layers; ++l) {
-        DGI_TRY(plan_layer(&layers[l], &plans[l]));
+        // layer 0 reads the caller's x; later layers read the library's own 16-byte aligned hidden buffers.  With a
+        // permutation, layer 0 reads the library's permuted copy of x instead.
+        const bool own_input = l > 0 || (opts && opts->perm_new_of_old);
+        const int64_t own_ld = round_up(layers[l].in_dim, 16 / elem_bytes(layers[l].feat_dtype));
+        DGI_TRY(plan_layer(g, &layers[l], own_input ? reinterpret_cast<const void*>(256) : x, own_input ? own_ld : ld_x, &plans[l]));
         if (l > 0) {
             DGI_REQUIRE(layers[l].in_dim == layers[l - 1].out_dim, DGI_ERR_INVALID_ARG, "layer %d: in_dim != previous out_dim", l);
             DGI_REQUIRE(layers[l].feat_dtype == layers[l - 1].out_dtype, DGI_ERR_INVALID_ARG, "layer %d: feat_dtype != previous out_dtype", l);
@@ -441,6 +490,7 @@ extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layer
             o.stats->batches[l] = batches;
             o.stats->edges[l] = g->E;
             o.stats->transform_first[l] = P.transform_first ? 1 : 0;
+            o.stats->fused[l] = P.fused ? 1 : 0;
             o.stats->gather_width[l] = P.gat ? (int)P.z_ld : (P.transform_first ? L.out_dim : L.in_dim);
         }
         cur = dst; ld_cur = ld_dst;  // H^{l-1} is dead from here on: its buffer is the next layer's output
@@ -456,6 +506,7 @@ extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layer
             if (sp.kind == SPAN_TOTAL) o.stats->total_ms = ms;
             else if (sp.kind == SPAN_LAYER) o.stats->layer_ms[sp.layer] = ms;
             else if (sp.kind == SPAN_AGG) { o.stats->agg_ms[sp.layer] += ms; o.stats->agg_launches[sp.layer] += 1; }
+            else if (sp.kind == SPAN_HUB) o.stats->hub_ms[sp.layer] += ms;
             else if (sp.kind == SPAN_GEMM) { o.stats->gemm_ms[sp.layer] += ms; o.stats->gemm_launches[sp.layer] += 1; }
         }
     }

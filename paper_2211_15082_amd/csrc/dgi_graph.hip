@@ -191,7 +191,9 @@ extern "C" dgi_status_t dgi_graph_load(int64_t num_nodes, int64_t num_edges, con
 extern "C" dgi_status_t dgi_graph_info(const dgi_graph_t* g, dgi_graph_info_t* info) {
     DGI_REQUIRE(g && info, DGI_ERR_INVALID_ARG, "graph_info: NULL argument");
     info->num_nodes = g->N; info->num_edges = g->E; info->max_in_degree = g->max_in_degree;
-    info->num_hub_rows = (int64_t)g->h_hub_rows.size(); info->indptr_type = g->itype; info->reserved = 0;
+    info->num_hub_rows = (int64_t)g->h_hub_rows.size();
+    info->num_hub_edges = 0;
+    for (int64_t v : g->h_hub_rows) info->num_hub_edges += g->h_indptr[v + 1] - g->h_indptr[v]; info->indptr_type = g->itype; info->reserved = 0;
     info->device_bytes = g->device_bytes;
     return DGI_OK;
 }

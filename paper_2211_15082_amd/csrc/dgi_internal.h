@@ -103,6 +103,23 @@ uint64_t agg_hub_partial_bytes(const dgi_graph* g, int64_t row_begin, int64_t ro
 // in the range (a no-op when there are none).  Callers run stage 0 then stage 1.
 dgi_status_t launch_aggregate(const AggArgs& a, int stage, hipStream_t stream);
 
+// Aggregate-first layer in one launch: out[v,:] = act([h_v | m_v] Wt^T + bias) for rows [row_begin,row_end),
+// m_v aggregated on the fly and kept in LDS (never written to HBM).
+struct FusedArgs {
+    const dgi_graph* g = nullptr;
+    int mode = MODE_SUM;
+    const void* H = nullptr; int64_t ld_h = 0; int dtype = DGI_F32; int K = 0;
+    const void* Wt = nullptr; int64_t ldw = 0; int K1p = 0; bool has_self = false; int N = 0;
+    const float* bias = nullptr; int act = DGI_ACT_NONE; float act_slope = 0.f;
+    void* out = nullptr; int64_t ld_out = 0; int64_t out_row0 = 0; int out_dtype = DGI_F32;
+    int64_t row_begin = 0, row_end = 0;
+    void* temp = nullptr;  // fused_temp_bytes() of scratch when the range holds hub rows
+};
+bool fused_supported(const FusedArgs& a);
+uint64_t fused_temp_bytes(const dgi_graph* g, int64_t row_begin, int64_t row_end, int K);
+// stage 0: hub pre-pass (no-op without hub rows in the range); stage 1: the fused kernel.  Run 0 then 1.
+dgi_status_t launch_fused(const FusedArgs& a, int stage, hipStream_t stream);
+
 // GAT edge pass over rows [row_begin,row_end).  Zx row u = [ z (heads*F) | el (heads) | er (heads) | pad ].
 struct GatArgs {
     const dgi_graph* g = nullptr;

@@ -46,7 +46,7 @@ WIDTH_CASES = [(16, 16), (47, 47), (48, 64), (64, 16), (100, 256), (128, 172), (
 
 
 @pytest.mark.parametrize("agg", ["sum", "mean", "gcn"])
-@pytest.mark.parametrize("order", ["agg_first", "transform_first"])
+@pytest.mark.parametrize("order", ["agg_first_split", "agg_first_fused", "transform_first"])
 @pytest.mark.parametrize("dims", WIDTH_CASES)
 def test_layer_matches_oracle(agg, order, dims):
     n = 777  # several 16-row workgroup tiles and 128-row GEMM tiles plus a ragged tail
@@ -71,7 +71,7 @@ def test_int64_indptr_and_device_borrowed_csr():
         ip = torch.from_numpy(indptr).to("cuda").to(dt)
         ix = torch.from_numpy(indices).to("cuda")
         g = B().graph_load(ip, ix)
-        for order in ("agg_first", "transform_first"):
+        for order in ("agg_first_split", "agg_first_fused", "transform_first"):
             got = gpu_layer(g, dict(layer, order=order), X)
             assert max_rel_err(got, want) <= TOL_F32
 
@@ -95,7 +95,7 @@ def test_destination_range_writes_only_its_rows():
     layer = dict(agg="mean", act="relu", W_self=rnd((64, 48), 2, 0.2), W_neigh=rnd((64, 48), 3, 0.2), bias=rnd((48,), 4))
     want = oracle.layer_forward(indptr, indices, layer, X)
     g = B().graph_load(indptr, indices)
-    for order in ("agg_first", "transform_first"):
+    for order in ("agg_first_split", "agg_first_fused", "transform_first"):
         for (b, e) in [(0, 1), (13, 14), (17, 211), (399, 400), (0, 400), (5, 5)]:
             got = gpu_layer(g, dict(layer, order=order), X, b, e)
             assert max_rel_err(got[b:e], want[b:e]) <= TOL_F32
@@ -110,16 +110,18 @@ def star_graph(k, extra=40):
     return n, indptr, indices
 
 
+@pytest.mark.parametrize("order", ["agg_first_split", "agg_first_fused"])
 @pytest.mark.parametrize("agg", ["sum", "mean", "gcn"])
-def test_hub_row_of_50000_in_neighbours(agg):
+def test_hub_row_of_50000_in_neighbours(agg, order):
     k = 50_000
     n, indptr, indices = star_graph(k)
-    X = np.zeros((n, 8), dtype=np.float32)
+    d = 8 if order == "agg_first_split" else 64   # the fused kernel takes rows wider than 8 x 16 bytes
+    X = np.zeros((n, d), dtype=np.float32)
     X[1:k + 1, 0] = np.arange(1, k + 1) % 1000
     X[1:k + 1, 1] = 1.0
-    X[:, 2:] = rnd((n, 6), 1)
-    W = np.eye(8, dtype=np.float32)
-    layer = dict(agg=agg, act="none", W_self=None, W_neigh=W, bias=None, order="agg_first")
+    X[:, 2:] = rnd((n, d - 2), 1)
+    W = np.eye(d, dtype=np.float32)
+    layer = dict(agg=agg, act="none", W_self=None, W_neigh=W, bias=None, order=order)
     g = B().graph_load(indptr, indices)
     assert g.info()["num_hub_rows"] == 1 and g.info()["max_in_degree"] == k
     got = gpu_layer(g, layer, X)
@@ -168,7 +170,7 @@ def test_gat_hub_row():
     assert max_rel_err(got, want) <= TOL_F32
 
 
-@pytest.mark.parametrize("order", ["agg_first", "transform_first"])
+@pytest.mark.parametrize("order", ["agg_first_split", "agg_first_fused", "transform_first"])
 def test_bf16_storage_layer(order):
     n = 900
     indptr, indices = random_csr(n, 7.0, seed=12)
@@ -234,10 +236,16 @@ def test_batch_size_invariance_is_bitwise():
 
 
 def test_memory_budget_forces_small_batches_and_oom_is_reported():
+    # a 16-wide input keeps layer 1 on the unfused path, whose aggregated tile is the batch temporary that
+    # the dynamic batch-size control has to fit into the budget
     bd = B()
     cfg = configs.make_config(1)
-    got, stats = run_infer(cfg, batch_size=0, mem_budget_bytes=4_300_000)
+    cfg["x"] = cfg["x"][:, :16].contiguous()
+    cfg["layers"][0]["W_self"] = cfg["layers"][0]["W_self"][:16].contiguous()
+    cfg["layers"][0]["W_neigh"] = cfg["layers"][0]["W_neigh"][:16].contiguous()
+    got, stats = run_infer(cfg, batch_size=0, mem_budget_bytes=4_150_000)
     want = oracle_infer(cfg)
+    assert stats["fused"] == [0, 0]
     assert max_rel_err(got, want) <= TOL_F32 and stats["batches"][0] > 2
     with pytest.raises(bd.DgiError) as ei:
         run_infer(cfg, mem_budget_bytes=100_000)

@@ -31,8 +31,8 @@ def test_struct_sizes_match_header_layout():
     # natural alignment of the C structs in dgi.h
     assert ctypes.sizeof(B.LayerStruct) == 9 * 4 + 4 + 5 * 8 + 4 + 4
     assert ctypes.sizeof(B.OptsStruct) == 6 * 8
-    assert ctypes.sizeof(B.StatsStruct) == 8 + 8 + 16 * (8 * 7 + 4 * 2) + 16
-    assert ctypes.sizeof(B.GraphInfoStruct) == 4 * 8 + 8 + 8
+    assert ctypes.sizeof(B.StatsStruct) == 8 + 8 + 16 * (8 * 8 + 4 * 3) + 16
+    assert ctypes.sizeof(B.GraphInfoStruct) == 5 * 8 + 8 + 8
 
 
 def brute_batch_end(ip, limit, begin, n_t, n_i):
