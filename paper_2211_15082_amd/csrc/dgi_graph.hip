@@ -226,12 +226,23 @@ extern "C" dgi_status_t dgi_graph_reorder(const dgi_graph_t* g, int32_t method, 
     DGI_REQUIRE(perm_where == DGI_HOST || perm_where == DGI_DEVICE, DGI_ERR_INVALID_ARG, "graph_reorder: bad perm location");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int64_t N = g->N, E = g->E;
-    // permutation on the host, from the host copy of the CSR
-    std::vector<int32_t> h_indices((size_t)std::max<int64_t>(E, 1));
-    if (E) DGI_HIP(hipMemcpy(h_indices.data(), g->d_indices, (size_t)E * 4, hipMemcpyDeviceToHost));
     std::vector<int32_t> perm((size_t)std::max<int64_t>(N, 1)), old_of_new((size_t)std::max<int64_t>(N, 1));
-    DGI_TRY(reorder_permutation(N, g->h_indptr.data(), h_indices.data(), method, seed, perm.data()));
-    h_indices.clear(); h_indices.shrink_to_fit();
+    int32_t* d_perm = nullptr;
+    DGI_HIP(hipMalloc((void**)&d_perm, std::max<size_t>(N, 1) * 4));
+    struct FreeOnExit { int32_t*& p; ~FreeOnExit() { (void)hipFree(p); p = nullptr; } } perm_guard{d_perm};
+    // the permutation: on the device for DEGREE / BFS_RCM, on the host otherwise (and beyond the device limits)
+    dgi_status_t pst = DGI_ERR_UNSUPPORTED;
+    if (method == DGI_REORDER_DEGREE || method == DGI_REORDER_BFS_RCM) pst = reorder_permutation_device(g, method, d_perm, stream);
+    if (pst == DGI_OK) {
+        if (N) DGI_HIP(hipMemcpy(perm.data(), d_perm, (size_t)N * 4, hipMemcpyDeviceToHost));
+    } else if (pst == DGI_ERR_UNSUPPORTED) {
+        std::vector<int32_t> h_indices((size_t)std::max<int64_t>(E, 1));
+        if (E) DGI_HIP(hipMemcpy(h_indices.data(), g->d_indices, (size_t)E * 4, hipMemcpyDeviceToHost));
+        DGI_TRY(reorder_permutation(N, g->h_indptr.data(), h_indices.data(), method, seed, perm.data()));
+        if (N) DGI_HIP(hipMemcpy(d_perm, perm.data(), (size_t)N * 4, hipMemcpyHostToDevice));
+    } else {
+        return pst;
+    }
     for (int64_t o = 0; o < N; ++o) old_of_new[perm[o]] = (int32_t)o;
 
     dgi_graph* ng = new dgi_graph();
@@ -242,9 +253,9 @@ extern "C" dgi_status_t dgi_graph_reorder(const dgi_graph_t* g, int32_t method, 
         ng->h_indptr[r + 1] = ng->h_indptr[r] + (g->h_indptr[o + 1] - g->h_indptr[o]);
     }
     dgi_status_t st = DGI_OK;
-    int32_t *d_perm = nullptr, *d_oon = nullptr, *d_unsorted = nullptr;
+    int32_t *d_oon = nullptr, *d_unsorted = nullptr;
     void* d_tmp = nullptr;
-    auto cleanup = [&]() { (void)hipFree(d_perm); (void)hipFree(d_oon); (void)hipFree(d_unsorted); (void)hipFree(d_tmp); };
+    auto cleanup = [&]() { (void)hipFree(d_oon); (void)hipFree(d_unsorted); (void)hipFree(d_tmp); d_oon = d_unsorted = nullptr; d_tmp = nullptr; };
     auto fail = [&](dgi_status_t s) { cleanup(); dgi_graph_free(ng); return s; };
     const size_t isz = g->itype == DGI_I64 ? 8 : 4;
     void* dip = nullptr; int32_t* dix = nullptr;
@@ -256,7 +267,7 @@ extern "C" dgi_status_t dgi_graph_reorder(const dgi_graph_t* g, int32_t method, 
         if (e != hipSuccess) { set_error("graph_reorder: %s failed: %s", what, hipGetErrorString(e)); return false; }
         return true;
     };
-    if (!chk(hipMalloc((void**)&d_perm, std::max<size_t>(N, 1) * 4), "alloc") || !chk(hipMalloc((void**)&d_oon, std::max<size_t>(N, 1) * 4), "alloc") ||
+    if (!chk(hipMalloc((void**)&d_oon, std::max<size_t>(N, 1) * 4), "alloc") ||
         !chk(hipMalloc((void**)&d_unsorted, std::max<size_t>(E, 1) * 4), "alloc"))
         return fail(DGI_ERR_DEVICE);
     if (g->itype == DGI_I64) {
@@ -269,8 +280,7 @@ extern "C" dgi_status_t dgi_graph_reorder(const dgi_graph_t* g, int32_t method, 
             return fail(DGI_ERR_DEVICE);
     }
     if (N) {
-        if (!chk(hipMemcpyAsync(d_perm, perm.data(), N * 4, hipMemcpyHostToDevice, stream), "upload") ||
-            !chk(hipMemcpyAsync(d_oon, old_of_new.data(), N * 4, hipMemcpyHostToDevice, stream), "upload"))
+        if (!chk(hipMemcpyAsync(d_oon, old_of_new.data(), N * 4, hipMemcpyHostToDevice, stream), "upload"))
             return fail(DGI_ERR_DEVICE);
         const int64_t blocks = std::min<int64_t>((N * 64 + 255) / 256, (int64_t)1 << 22);  // < 2^32 threads per launch
         if (g->itype == DGI_I64)

@@ -163,6 +163,14 @@ dgi_status_t launch_fill_zero(void* p, uint64_t bytes, hipStream_t stream);
 dgi_status_t launch_permute_rows(const void* in, int64_t ld_in, void* out, int64_t ld_out, int64_t rows, int width,
                                  int elem_bytes, const int32_t* perm, bool gather, hipStream_t stream);
 
+// BFS reordering enumerates at most this many connected components breadth-first; what is left after that is
+// appended in (degree, id) order (a graph with very many tiny components gains nothing from more).
+constexpr int kMaxBfsComponents = 256;
+
+// permutation computed on the device (dgi_reorder_gpu.hip): DEGREE and BFS_RCM; d_perm is a DEVICE buffer of N ints.
+// Returns DGI_ERR_UNSUPPORTED for graphs beyond its size limits (the caller then uses the host routine).
+dgi_status_t reorder_permutation_device(const dgi_graph* g, int method, int32_t* d_perm, hipStream_t stream);
+
 // host-side permutations (dgi_reorder.cpp)
 dgi_status_t reorder_permutation(int64_t N, const int64_t* indptr, const int32_t* indices, int method, uint64_t seed,
                                  int32_t* perm_new_of_old);

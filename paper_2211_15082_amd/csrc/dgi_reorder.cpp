@@ -6,7 +6,8 @@
 //  BFS_RCM: Cuthill-McKee enumeration on the undirected structure (u ~ v if either direction is stored),
 //           reversed at the end (the paper's RCMK).  The paper leaves the details open; here every
 //           connected component starts at an unvisited node of minimum undirected degree, and the
-//           unvisited neighbours of a dequeued node are appended in ascending (degree, old id) order.
+//           unvisited neighbours of a dequeued node are appended in ascending (degree, old id) order.  After
+//           kMaxBfsComponents components the remaining nodes are appended in (degree, id) order.
 //  RANDOM : seeded Fisher-Yates shuffle.
 #include <algorithm>
 #include <numeric>
@@ -68,9 +69,15 @@ void rcm_order(int64_t N, const int64_t* indptr, const int32_t* indices, int32_t
     std::vector<int32_t> order;
     order.reserve((size_t)N);
     std::vector<int32_t> fresh;
+    int components = 0;
     for (int64_t s = 0; s < N; ++s) {
         const int32_t start = by_degree[s];
         if (seen[start]) continue;
+        if (components++ >= kMaxBfsComponents) {  // leftovers: (degree, id) order, no more searches
+            seen[start] = 1;
+            order.push_back(start);
+            continue;
+        }
         seen[start] = 1;
         size_t head = order.size();
         order.push_back(start);

@@ -297,3 +297,23 @@ def test_graph_vectors_and_validation():
     assert ei.value.status == bd.ERR_BAD_GRAPH
     g0 = bd.graph_load(np.zeros(1, np.int64), np.zeros(0, np.int32))
     assert g0.info()["num_nodes"] == 0
+
+
+@pytest.mark.parametrize("method", ["degree", "bfs_rcm"])
+def test_device_reordering_equals_the_sequential_algorithm(method):
+    # the permutation is computed by kernels in dgi_graph_reorder and by a plain sequential routine in
+    # dgi_reorder_permutation; both follow the same rule, so they agree exactly
+    bd = B()
+    graphs = [random_csr(3000, 3.0, seed=1), random_csr(500, 0.7, seed=2), random_csr(4000, 12.0, seed=3, empty_frac=0.0)]
+    n = 257  # a path (diameter n - 1) plus isolated nodes
+    rows = [[v - 1] if 0 < v < 200 else [] for v in range(n)]
+    ip = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum([len(r) for r in rows], out=ip[1:])
+    graphs.append((ip, np.array([u for r in rows for u in r], dtype=np.int32)))
+    cfg = configs.make_config(5, scale=0.003)
+    graphs.append((cfg["indptr"].numpy().astype(np.int64), cfg["indices"].numpy()))
+    for indptr, indices in graphs:
+        g = bd.graph_load(indptr, indices)
+        g2, perm = bd.graph_reorder(g, method)
+        want = bd.reorder_permutation(indptr, indices, method)
+        assert np.array_equal(perm.cpu().numpy(), want)
