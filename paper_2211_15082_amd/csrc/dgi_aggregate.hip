@@ -42,6 +42,7 @@ struct AggParams {
     const float* bias;
     int act;
     float act_slope;
+    const float* out_scale;
     int64_t row_begin, row_end;
     int64_t n_tiles;
     int skip_hubs;
@@ -68,6 +69,7 @@ struct FusedParams {
     const float* bias;
     int act;
     float act_slope;
+    const float* out_scale;
     void* out;
     int64_t ld_out;
     int64_t out_row0;
@@ -204,6 +206,7 @@ __device__ __forceinline__ void finish_store(const AggParams& p, int64_t v, int6
     if (p.self) val += Row<T>::one(static_cast<const T*>(p.self) + v * p.ld_self + c);
     if (p.bias) val += p.bias[c];
     val = activate(val, p.act, p.act_slope);
+    if (p.out_scale) val *= p.out_scale[v];
     const int64_t o = out_row * p.ld_out + c;
     if (p.out_bf16) static_cast<uint16_t*>(p.out)[o] = float_to_bf16(val);
     else static_cast<float*>(p.out)[o] = val;
@@ -212,7 +215,7 @@ __device__ __forceinline__ void finish_store(const AggParams& p, int64_t v, int6
 template <int MODE, typename IdxT>
 __device__ __forceinline__ float row_scale(const AggParams& p, int64_t v, IdxT deg) {
     if (MODE == MODE_MEAN) return deg > 0 ? 1.0f / (float)deg : 0.f;
-    if (MODE == MODE_GCN) return p.rs_in[v];
+    if (MODE == MODE_GCN || MODE == MODE_GCN_PRE) return p.rs_in[v];
     return 1.f;
 }
 
@@ -268,7 +271,7 @@ __device__ __forceinline__ void rows_tile(const AggParams& p, int64_t bid) {
             combine_groups<G, VEC>(acc);
             const int c = col0 + gl * VEC;
             if (sub == 0 && c < p.width) {
-                const bool plain = !p.self && !p.bias && p.act == DGI_ACT_NONE;
+                const bool plain = !p.self && !p.bias && p.act == DGI_ACT_NONE && !p.out_scale;
                 if (plain && p.out_vec_ok && c + VEC <= p.width) {
                     const int64_t o = (v - p.out_row0) * p.ld_out + c;
                     if (p.out_bf16) {
@@ -494,7 +497,8 @@ __global__ __launch_bounds__(kWaves * 64) void fused_layer_kernel(FusedParams fp
             for (int r = 0; r < 16; ++r) {
                 const int64_t v = vt + 8 * (r / 4) + 4 * lhalf + (r % 4);
                 if (v >= p.row_end) continue;
-                const float val = activate(acc[r] + bias, fp.act, fp.act_slope);
+                float val = activate(acc[r] + bias, fp.act, fp.act_slope);
+                if (fp.out_scale) val *= fp.out_scale[v];
                 const int64_t o = (v - fp.out_row0) * fp.ld_out + n;
                 if (fp.out_bf16) static_cast<uint16_t*>(fp.out)[o] = float_to_bf16(val);
                 else static_cast<float*>(fp.out)[o] = val;
@@ -616,6 +620,7 @@ dgi_status_t dispatch_mode(const AggParams& p, const dgi_graph* g, int mode, boo
         case MODE_SUM: return dispatch_g<T, IdxT, MODE_SUM>(p, g, fast, stage, stream);
         case MODE_MEAN: return dispatch_g<T, IdxT, MODE_MEAN>(p, g, fast, stage, stream);
         case MODE_GCN: return dispatch_g<T, IdxT, MODE_GCN>(p, g, fast, stage, stream);
+        case MODE_GCN_PRE: return dispatch_g<T, IdxT, MODE_GCN_PRE>(p, g, fast, stage, stream);
     }
     set_error("unknown aggregation mode %d", mode);
     return DGI_ERR_INVALID_ARG;
@@ -642,7 +647,7 @@ dgi_status_t launch_fused_g(FusedParams fp, const dgi_graph* g, float* partials,
         h.hub_blocks = round_up((h.n_chunks + kWaves - 1) / kWaves, kGroup);
         h.n_tiles = 0;
         h.out = hub_agg; h.ld_out = Kp; h.out_row0 = 0; h.out_bf16 = 0; h.out_vec_ok = 0; h.hub_compact = 1;
-        h.self = nullptr; h.bias = nullptr; h.act = DGI_ACT_NONE;
+        h.self = nullptr; h.bias = nullptr; h.act = DGI_ACT_NONE; h.out_scale = nullptr;
         DGI_REQUIRE(h.hub_blocks * kWaves * 64 < (int64_t)1 << 32, DGI_ERR_INVALID_ARG, "fused: too many hub chunks for one launch");
         if (stage == 0) {
             hipLaunchKernelGGL((agg_kernel<T, IdxT, G, MODE>), dim3((unsigned)h.hub_blocks), dim3(kWaves * 64), 0, stream, h);
@@ -682,6 +687,7 @@ dgi_status_t launch_fused_t(const FusedParams& fp, const dgi_graph* g, int mode,
         case MODE_SUM: return launch_fused_mode<T, IdxT, MODE_SUM>(fp, g, partials, hub_agg, stage, stream);
         case MODE_MEAN: return launch_fused_mode<T, IdxT, MODE_MEAN>(fp, g, partials, hub_agg, stage, stream);
         case MODE_GCN: return launch_fused_mode<T, IdxT, MODE_GCN>(fp, g, partials, hub_agg, stage, stream);
+        case MODE_GCN_PRE: return launch_fused_mode<T, IdxT, MODE_GCN_PRE>(fp, g, partials, hub_agg, stage, stream);
     }
     set_error("unknown aggregation mode %d", mode);
     return DGI_ERR_INVALID_ARG;
@@ -722,7 +728,7 @@ dgi_status_t launch_fused(const FusedArgs& a, int stage, hipStream_t stream) {
     p.hub_rows = g->d_hub_rows; p.hub_chunk_ptr = g->d_hub_chunk_ptr;
     p.wpad = (int)round_up(a.K, 8);
     fp.Wt = a.Wt; fp.ldw = a.ldw; fp.K1p = a.K1p; fp.has_self = a.has_self ? 1 : 0; fp.N = a.N;
-    fp.bias = a.bias; fp.act = a.act; fp.act_slope = a.act_slope;
+    fp.bias = a.bias; fp.act = a.act; fp.act_slope = a.act_slope; fp.out_scale = a.out_scale;
     fp.out = a.out; fp.ld_out = a.ld_out; fp.out_row0 = a.out_row0; fp.out_bf16 = a.out_dtype == DGI_BF16;
     fp.lds_ld = (int)(a.ldw + E);
     float* partials = static_cast<float*>(a.temp);
@@ -758,7 +764,7 @@ dgi_status_t launch_aggregate(const AggArgs& a, int stage, hipStream_t stream) {
     p.out = a.out; p.ld_out = a.ld_out; p.out_row0 = a.out_row0;
     p.out_bf16 = a.out_dtype == DGI_BF16;
     p.self = a.self; p.ld_self = a.ld_self;
-    p.bias = a.bias; p.act = a.act; p.act_slope = a.act_slope;
+    p.bias = a.bias; p.act = a.act; p.act_slope = a.act_slope; p.out_scale = a.out_scale;
     p.row_begin = a.row_begin; p.row_end = a.row_end;
     p.partials = a.hub_partials;
     p.hub_rows = g->d_hub_rows;

@@ -166,9 +166,11 @@ uint64_t batch_temp_bytes(const dgi_graph* g, const dgi_layer_t* L, const LayerP
 struct KernelTimer;  // defined below
 
 // One batch of destination rows [b,e): the body of the inner loop of Algorithm 2.
+// in_prescaled: the rows of h_in already carry the GCN source factor d_out(u)^-1/2; out_scale: per-node factor
+// to fold into this layer's output rows (the next GCN layer's source factor), or NULL.
 dgi_status_t run_batch(const dgi_graph* g, const dgi_layer_t* L, const LayerPlan& P, const void* h_in, int64_t ld_in,
                        void* h_out, int64_t ld_out, int64_t b, int64_t e, const void* Wt, const void* Z, void* temp,
-                       hipStream_t s, KernelTimer* timer);
+                       hipStream_t s, KernelTimer* timer, bool in_prescaled, const float* out_scale);
 
 // HIP-event timing of kernel classes on the caller's stream.
 struct KernelTimer {
@@ -192,9 +194,10 @@ enum { SPAN_AGG = 0, SPAN_GEMM = 1, SPAN_LAYER = 2, SPAN_TOTAL = 3, SPAN_HUB = 4
 
 dgi_status_t run_batch(const dgi_graph* g, const dgi_layer_t* L, const LayerPlan& P, const void* h_in, int64_t ld_in,
                        void* h_out, int64_t ld_out, int64_t b, int64_t e, const void* Wt, const void* Z, void* temp,
-                       hipStream_t s, KernelTimer* timer) {
+                       hipStream_t s, KernelTimer* timer, bool in_prescaled, const float* out_scale) {
     if (e <= b) return DGI_OK;
     const int ob = elem_bytes(L->out_dtype);
+    const int mode = (P.mode == MODE_GCN && in_prescaled) ? (int)MODE_GCN_PRE : P.mode;
     if (P.gat) {
         GatArgs a;
         a.g = g; a.Zx = (const float*)Z; a.ld_z = P.z_ld; a.heads = L->heads; a.head_dim = L->out_dim / L->heads;
@@ -208,14 +211,14 @@ dgi_status_t run_batch(const dgi_graph* g, const dgi_layer_t* L, const LayerPlan
     }
     const uint64_t part_bytes = round_up((int64_t)agg_hub_partial_bytes(g, b, e, P.transform_first ? L->out_dim : L->in_dim), 256);
     AggArgs a;
-    a.g = g; a.mode = P.mode; a.row_begin = b; a.row_end = e;
+    a.g = g; a.mode = mode; a.row_begin = b; a.row_end = e;
     a.hub_partials = part_bytes ? (float*)temp : nullptr;
     if (P.transform_first) {
         const int zb = elem_bytes(P.z_dtype);
         a.S = (const char*)Z + (int64_t)P.z_neigh_col * zb; a.ld_s = P.z_ld; a.s_dtype = P.z_dtype; a.width = L->out_dim;
         a.self = P.has_self ? Z : nullptr; a.ld_self = P.z_ld;
         a.out = (char*)h_out + b * ld_out * ob; a.ld_out = ld_out; a.out_row0 = b; a.out_dtype = L->out_dtype;
-        a.bias = L->bias; a.act = L->act; a.act_slope = L->act_slope;
+        a.bias = L->bias; a.act = L->act; a.act_slope = L->act_slope; a.out_scale = out_scale;
         if (timer) DGI_TRY(timer->begin(SPAN_AGG));
         DGI_TRY(launch_aggregate(a, 0, s));
         if (timer) DGI_TRY(timer->end());
@@ -223,9 +226,9 @@ dgi_status_t run_batch(const dgi_graph* g, const dgi_layer_t* L, const LayerPlan
     }
     if (P.fused) {
         FusedArgs fa;
-        fa.g = g; fa.mode = P.mode; fa.H = h_in; fa.ld_h = ld_in; fa.dtype = L->feat_dtype; fa.K = L->in_dim;
+        fa.g = g; fa.mode = mode; fa.H = h_in; fa.ld_h = ld_in; fa.dtype = L->feat_dtype; fa.K = L->in_dim;
         fa.Wt = Wt; fa.ldw = P.ldw; fa.K1p = P.K1p; fa.has_self = P.has_self; fa.N = L->out_dim;
-        fa.bias = L->bias; fa.act = L->act; fa.act_slope = L->act_slope;
+        fa.bias = L->bias; fa.act = L->act; fa.act_slope = L->act_slope; fa.out_scale = out_scale;
         fa.out = (char*)h_out + b * ld_out * ob; fa.ld_out = ld_out; fa.out_row0 = b; fa.out_dtype = L->out_dtype;
         fa.row_begin = b; fa.row_end = e;
         fa.temp = fused_temp_bytes(g, b, e, L->in_dim) ? temp : nullptr;
@@ -258,6 +261,7 @@ dgi_status_t run_batch(const dgi_graph* g, const dgi_layer_t* L, const LayerPlan
     ga.bias = L->bias; ga.act = L->act; ga.act_slope = L->act_slope;
     ga.Y = (char*)h_out + b * ld_out * ob; ga.ld_y = ld_out; ga.out_dtype = L->out_dtype;
     ga.M = e - b; ga.Nout = L->out_dim;
+    ga.out_scale = out_scale; ga.row0 = b;
     if (timer) DGI_TRY(timer->begin(SPAN_GEMM));
     DGI_TRY(launch_gemm(ga, s));
     if (timer) DGI_TRY(timer->end());
@@ -344,7 +348,7 @@ extern "C" dgi_status_t dgi_layer_forward(const dgi_graph_t* g, const dgi_layer_
     char* ws = static_cast<char*>(workspace);
     DGI_TRY(prepare_weights(layer, P, ws + f.wt_off, s));
     if (P.transform_first) DGI_TRY(run_transform(layer, P, h_in, ld_in, ws + f.wt_off, ws + f.z_off, 0, g->N, s));
-    return run_batch(g, layer, P, h_in, ld_in, h_out, ld_out, dst_begin, dst_end, ws + f.wt_off, ws + f.z_off, ws + f.temp_off, s, nullptr);
+    return run_batch(g, layer, P, h_in, ld_in, h_out, ld_out, dst_begin, dst_end, ws + f.wt_off, ws + f.z_off, ws + f.temp_off, s, nullptr, false, nullptr);
 }
 
 extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layers, int32_t num_layers, const void* x,
@@ -355,7 +359,7 @@ extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layer
     for (int l = 0; l < num_layers; ++l) {
         // layer 0 reads the caller's x; later layers read the library's own 16-byte aligned hidden buffers.  With a
         // permutation, layer 0 reads the library's permuted copy of x instead.
-        const bool own_input = l > 0 || (opts && opts->perm_new_of_old);
+        const bool own_input = l > 0 || (opts && opts->perm_new_of_old) || layers[0].agg == DGI_AGG_GCN;
         const int64_t own_ld = round_up(layers[l].in_dim, 16 / elem_bytes(layers[l].feat_dtype));
         DGI_TRY(plan_layer(g, &layers[l], own_input ? reinterpret_cast<const void*>(256) : x, own_input ? own_ld : ld_x, &plans[l]));
         if (l > 0) {
@@ -392,7 +396,10 @@ extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layer
     const bool permuted = o.perm_new_of_old != nullptr;
     const int xb = elem_bytes(L0.feat_dtype), yb = elem_bytes(LL.out_dtype);
     const int64_t ld_xp = round_up(L0.in_dim, 16 / xb), ld_yp = round_up(LL.out_dim, 16 / yb);
-    const uint64_t xp_bytes = permuted ? (uint64_t)round_up(N * ld_xp * xb, 256) : 0;
+    // GCN layers gather rows already multiplied by d_out(u)^-1/2: every layer folds the next layer's factor into
+    // its epilogue, and the input of a first GCN layer is scaled once into a library-owned copy.
+    const bool scale_x = L0.agg == DGI_AGG_GCN;
+    const uint64_t xp_bytes = (permuted || scale_x) ? (uint64_t)round_up(N * ld_xp * xb, 256) : 0;
     const uint64_t yp_bytes = permuted ? (uint64_t)round_up(N * ld_yp * yb, 256) : 0;
     uint64_t fixed_max = 0, temp_full_max = 0;
     for (int l = 0; l < num_layers; ++l) {
@@ -422,7 +429,7 @@ extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layer
     auto carve = [&](uint64_t bytes) { char* p = arena + off; off += (uint64_t)round_up((int64_t)bytes, 256); return p; };
     char* hid[2] = {nullptr, nullptr};
     for (int i = 0; i < n_hidden; ++i) hid[i] = carve(hidden_bytes);
-    char* xp = permuted ? carve(xp_bytes) : nullptr;
+    char* xp = (permuted || scale_x) ? carve(xp_bytes) : nullptr;
     char* yp = permuted ? carve(yp_bytes) : nullptr;
     char* fixed = carve(fixed_max);
     char* temp = carve(temp_cap);
@@ -438,6 +445,10 @@ extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layer
         DGI_TRY(launch_permute_rows(x, ld_x, xp, ld_xp, N, L0.in_dim, xb, o.perm_new_of_old, false, s));
         cur = xp; ld_cur = ld_xp;
     }
+    if (scale_x) {  // in place on the permuted copy, or from the caller's x into the copy
+        DGI_TRY(launch_scale_rows(cur, ld_cur, xp, ld_xp, N, L0.in_dim, xb, g->d_rs_out, s));
+        cur = xp; ld_cur = ld_xp;
+    }
     const double avg_deg = N > 0 ? (double)g->E / (double)N : 0.0;
     for (int l = 0; l < num_layers; ++l) {
         const dgi_layer_t& L = layers[l];
@@ -446,6 +457,8 @@ extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layer
         void* dst; int64_t ld_dst;
         if (last) { dst = permuted ? (void*)yp : out; ld_dst = permuted ? ld_yp : ld_out; }
         else { dst = hid[l % 2]; ld_dst = round_up(L.out_dim, 16 / elem_bytes(L.out_dtype)); }
+        const bool in_prescaled = L.agg == DGI_AGG_GCN && (l == 0 || layers[l - 1].agg != DGI_AGG_GAT);
+        const float* out_scale = (!last && layers[l + 1].agg == DGI_AGG_GCN && L.agg != DGI_AGG_GAT) ? g->d_rs_out : nullptr;
         if (tm) { tm->layer = l; DGI_TRY(tm->begin(SPAN_LAYER)); }
         const size_t layer_span = tm ? tm->spans.size() - 1 : 0;
         char* Wt = fixed;
@@ -477,7 +490,7 @@ extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layer
                 n_t = std::min(n_t, std::max<int64_t>((e - b) / 2, 1));
                 continue;
             }
-            DGI_TRY(run_batch(g, &L, P, cur, ld_cur, dst, ld_dst, b, e, Wt, Z, temp, s, tm));
+            DGI_TRY(run_batch(g, &L, P, cur, ld_cur, dst, ld_dst, b, e, Wt, Z, temp, s, tm, in_prescaled, out_scale));
             ++batches;
             if (o.batch_size == 0) {
                 if (need == 0) { n_t = N; n_i = std::max<int64_t>(g->E, 1); }  // nothing to bound

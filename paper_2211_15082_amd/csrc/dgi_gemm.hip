@@ -29,6 +29,7 @@ struct GemmParams {
     void* Y; int64_t ld_y; int out_bf16;
     int64_t M; int Nout;
     int tiles_n;
+    const float* out_scale; int64_t row0;
 };
 
 __device__ __forceinline__ uint16_t f2bf(float f) {
@@ -186,7 +187,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmParams p) {
             for (int r = 0; r < 16; ++r) {
                 const int64_t m = m0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * lhalf + (r % 4);
                 if (m >= p.M) continue;
-                const float v = act_fn(acc[i][j][r] + b, p.act, p.act_slope);
+                float v = act_fn(acc[i][j][r] + b, p.act, p.act_slope);
+                if (p.out_scale) v *= p.out_scale[p.row0 + m];
                 if (p.out_bf16) static_cast<uint16_t*>(p.Y)[m * p.ld_y + n] = f2bf(v);
                 else static_cast<float*>(p.Y)[m * p.ld_y + n] = v;
             }
@@ -231,6 +233,22 @@ __global__ void permute_rows_kernel(const T* in, int64_t ld_in, T* out, int64_t 
     }
 }
 
+// out[r, c] = in[r, c] * scale[r]
+template <typename T>
+__global__ void scale_rows_kernel(const T* in, int64_t ld_in, T* out, int64_t ld_out, int64_t rows, int width, const float* scale) {
+    const int64_t total = rows * width;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t r = i / width;
+        const int c = (int)(i % width);
+        if (sizeof(T) == 4) {
+            reinterpret_cast<float*>(out)[r * ld_out + c] = reinterpret_cast<const float*>(in)[r * ld_in + c] * scale[r];
+        } else {
+            const float f = __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(in)[r * ld_in + c] << 16) * scale[r];
+            reinterpret_cast<uint16_t*>(out)[r * ld_out + c] = f2bf(f);
+        }
+    }
+}
+
 template <typename T, int WGM, int WGN, int TM, int TN>
 dgi_status_t launch_cfg(GemmParams p, hipStream_t stream) {
     constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
@@ -259,6 +277,7 @@ dgi_status_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
     p.bias = a.bias; p.act = a.act; p.act_slope = a.act_slope;
     p.Y = a.Y; p.ld_y = a.ld_y; p.out_bf16 = a.out_dtype == DGI_BF16;
     p.M = a.M; p.Nout = a.Nout;
+    p.out_scale = a.out_scale; p.row0 = a.row0;
     // 128-wide column tiles: a 256-wide tile would read A once but leaves one wavefront per SIMD and measured slower
     if (a.dtype == DGI_BF16) {
         if (a.Nout <= 64) return launch_cfg<uint16_t, 4, 1, 1, 2>(p, stream);
@@ -297,6 +316,21 @@ dgi_status_t launch_fill_zero(void* ptr, uint64_t bytes, hipStream_t stream) {
     uint64_t grid = (words + 255) / 256;
     if (grid > 65536) grid = 65536;
     hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)grid), dim3(256), 0, stream, (uint32_t*)ptr, words);
+    DGI_HIP(hipGetLastError());
+    return DGI_OK;
+}
+
+dgi_status_t launch_scale_rows(const void* in, int64_t ld_in, void* out, int64_t ld_out, int64_t rows, int width,
+                               int elem_bytes, const float* scale, hipStream_t stream) {
+    const int64_t n = rows * width;
+    if (n == 0) return DGI_OK;
+    const int64_t grid = std::min<int64_t>((n + 255) / 256, (int64_t)1 << 22);
+    if (elem_bytes == 2)
+        hipLaunchKernelGGL(scale_rows_kernel<uint16_t>, dim3((unsigned)grid), dim3(256), 0, stream, (const uint16_t*)in, ld_in,
+                           (uint16_t*)out, ld_out, rows, width, scale);
+    else
+        hipLaunchKernelGGL(scale_rows_kernel<float>, dim3((unsigned)grid), dim3(256), 0, stream, (const float*)in, ld_in,
+                           (float*)out, ld_out, rows, width, scale);
     DGI_HIP(hipGetLastError());
     return DGI_OK;
 }

@@ -74,7 +74,9 @@ struct dgi_graph {
 namespace dgi {
 
 // ---- kernel launch descriptors ------------------------------------------------------------------
-enum : int { MODE_SUM = 0, MODE_MEAN = 1, MODE_GCN = 2 };
+// MODE_GCN_PRE: GCN whose source rows were already multiplied by d_out(u)^-1/2 by the kernel that produced
+// them, so the gather needs no per-edge coefficient (only the destination scale d_in(v)^-1/2).
+enum : int { MODE_SUM = 0, MODE_MEAN = 1, MODE_GCN = 2, MODE_GCN_PRE = 3 };
 
 // Gather/aggregate of destination rows [row_begin,row_end):
 //   out[v - out_row0, c] = act( scale_v * sum_{u in N(v)} coef_u * S[u, c] + self[v, c] + bias[c] )
@@ -95,6 +97,7 @@ struct AggArgs {
     const float* bias = nullptr;
     int act = DGI_ACT_NONE;
     float act_slope = 0.f;
+    const float* out_scale = nullptr;  // optional per-row factor applied after the activation (indexed by node id)
     int64_t row_begin = 0, row_end = 0;
     float* hub_partials = nullptr;  // fp32 [chunks in range x width_padded], needed when the range holds hub rows
 };
@@ -111,6 +114,7 @@ struct FusedArgs {
     const void* H = nullptr; int64_t ld_h = 0; int dtype = DGI_F32; int K = 0;
     const void* Wt = nullptr; int64_t ldw = 0; int K1p = 0; bool has_self = false; int N = 0;
     const float* bias = nullptr; int act = DGI_ACT_NONE; float act_slope = 0.f;
+    const float* out_scale = nullptr;  // optional per-row factor applied after the activation (indexed by node id)
     void* out = nullptr; int64_t ld_out = 0; int64_t out_row0 = 0; int out_dtype = DGI_F32;
     int64_t row_begin = 0, row_end = 0;
     void* temp = nullptr;  // fused_temp_bytes() of scratch when the range holds hub rows
@@ -149,6 +153,7 @@ struct GemmArgs {
     int act = DGI_ACT_NONE; float act_slope = 0.f;
     void* Y = nullptr; int64_t ld_y = 0; int out_dtype = DGI_F32;
     int64_t M = 0; int Nout = 0;
+    const float* out_scale = nullptr; int64_t row0 = 0;  // optional: Y[r,:] *= out_scale[row0 + r] after the activation
 };
 dgi_status_t launch_gemm(const GemmArgs& a, hipStream_t stream);
 
@@ -159,6 +164,9 @@ dgi_status_t launch_pack_weight(const void* W, int dtype, int K, int Nout, void*
 dgi_status_t launch_pack_gat_attn(const float* W, int K, int heads, int F, const float* a_src, const float* a_dst,
                                   float* Wt, int64_t ldw, hipStream_t stream);
 dgi_status_t launch_fill_zero(void* p, uint64_t bytes, hipStream_t stream);
+// out[r, c] = in[r, c] * scale[r]  (rows x width, dtype fp32 or bf16)
+dgi_status_t launch_scale_rows(const void* in, int64_t ld_in, void* out, int64_t ld_out, int64_t rows, int width,
+                               int elem_bytes, const float* scale, hipStream_t stream);
 // out[perm ? perm[r] : r] rows <- in rows (gather_inverse=false: out[perm[r]] = in[r]; true: out[r] = in[perm[r]])
 dgi_status_t launch_permute_rows(const void* in, int64_t ld_in, void* out, int64_t ld_out, int64_t rows, int width,
                                  int elem_bytes, const int32_t* perm, bool gather, hipStream_t stream);

@@ -317,3 +317,28 @@ def test_device_reordering_equals_the_sequential_algorithm(method):
         g2, perm = bd.graph_reorder(g, method)
         want = bd.reorder_permutation(indptr, indices, method)
         assert np.array_equal(perm.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("order", ["auto", "agg_first_split", "agg_first_fused", "transform_first"])
+def test_mixed_stack_with_gcn_source_scaling_folded_into_producers(order):
+    # GCN layers read rows pre-multiplied by d_out^-1/2 when the producing layer can fold the factor into its
+    # epilogue (first layer: scaled copy of x; SAGE/GCN producers: epilogue), and fall back to the per-edge
+    # coefficient after a GAT layer.  All variants must agree with the oracle.
+    bd = B()
+    n = 1500
+    indptr, indices = random_csr(n, 9.0, seed=77)
+    X = rnd((n, 64), 1)
+    def gcn(i, o, seed, act="relu"):
+        return dict(agg="gcn", act=act, W_neigh=rnd((i, o), seed, 0.2), bias=rnd((o,), seed + 1), order=order)
+    layers = [gcn(64, 96, 10),
+              dict(agg="mean", act="relu", W_self=rnd((96, 64), 20, 0.2), W_neigh=rnd((96, 64), 21, 0.2), bias=rnd((64,), 22), order=order),
+              gcn(64, 48, 30),
+              dict(agg="gat", act="elu", W_neigh=rnd((48, 32), 40, 0.3), heads=2, attn_src=rnd((2, 16), 41, 0.5),
+                   attn_dst=rnd((2, 16), 42, 0.5), bias=rnd((32,), 43)),
+              gcn(32, 16, 50, act="none")]
+    want = oracle.infer(indptr, indices, layers, X)
+    g = bd.graph_load(indptr, indices)
+    structs, keep = zip(*[bd.make_layer(L) for L in layers])
+    out = torch.empty(n, 16, dtype=torch.float32, device="cuda")
+    bd.infer(g, list(structs), torch.from_numpy(X).cuda(), out, batch_size=400)
+    assert max_rel_err(out.cpu().numpy(), want) <= TOL_F32
