@@ -204,6 +204,24 @@ dgi_status_t dgi_layer_workspace_bytes(const dgi_graph_t* g, const dgi_layer_t* 
 dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layers, int32_t num_layers, const void* x,
                        int64_t ld_x, void* out, int64_t ld_out, const dgi_infer_opts_t* opts, void* hip_stream);
 
+/* Partial inference (Sections 2 and 3.3): output embeddings of `num_targets` target nodes only.
+ *   targets : DEVICE, int32 node ids (duplicates allowed);  out: DEVICE [num_targets x out_dim], row i = target i.
+ * The per-layer target sets V^L = targets, V^{l-1} = V^l + in-neighbours(V^l) are marked on the device; when
+ * |V^l| * average degree >= num_nodes the annotation stops and all nodes are used from that layer down (the
+ * paper's shortcut), which here means: run dgi_infer on the whole graph and pick the target rows.  Otherwise
+ * V^1 with its complete in-neighbour lists and the inputs V^0 are extracted into a relabelled sub-problem on
+ * which the ordinary layer-wise schedule runs (degrees in the GCN normaliser remain those of the full graph).
+ * opts->perm_new_of_old must be NULL.  Waits for completion.  pstats (HOST, may be NULL) reports the set sizes. */
+typedef struct {
+    int32_t num_layers;
+    int32_t all_nodes_from_layer;            /* l: layers <= l ran on all nodes (shortcut); -1: never triggered */
+    int64_t set_size[DGI_MAX_LAYERS + 1];    /* |V^l| for the annotated layers, index l in [0, num_layers] */
+    int64_t sub_nodes, sub_edges;            /* size of the problem that was actually run */
+} dgi_partial_stats_t;
+dgi_status_t dgi_infer_partial(const dgi_graph_t* g, const dgi_layer_t* layers, int32_t num_layers, const void* x,
+                               int64_t ld_x, const int32_t* targets, int64_t num_targets, void* out, int64_t ld_out,
+                               const dgi_infer_opts_t* opts, dgi_partial_stats_t* pstats, void* hip_stream);
+
 /* ------------------------------------------------------------------------------------------------
  * Host-side planning helpers (no device access; usable without a GPU).
  *

@@ -63,6 +63,13 @@ class OptsStruct(ctypes.Structure):
     ]
 
 
+class PartialStatsStruct(ctypes.Structure):
+    _fields_ = [
+        ("num_layers", ctypes.c_int32), ("all_nodes_from_layer", ctypes.c_int32),
+        ("set_size", ctypes.c_int64 * (MAX_LAYERS + 1)), ("sub_nodes", ctypes.c_int64), ("sub_edges", ctypes.c_int64),
+    ]
+
+
 class GraphInfoStruct(ctypes.Structure):
     _fields_ = [
         ("num_nodes", ctypes.c_int64), ("num_edges", ctypes.c_int64), ("max_in_degree", ctypes.c_int64),
@@ -73,7 +80,7 @@ class GraphInfoStruct(ctypes.Structure):
 
 EXPORTS = [
     "dgi_graph_load", "dgi_graph_free", "dgi_graph_release_workspace", "dgi_graph_info", "dgi_graph_vector", "dgi_graph_csr", "dgi_graph_reorder",
-    "dgi_layer_forward", "dgi_layer_workspace_bytes", "dgi_infer", "dgi_plan_batch_end", "dgi_threshold_update",
+    "dgi_layer_forward", "dgi_layer_workspace_bytes", "dgi_infer", "dgi_infer_partial", "dgi_plan_batch_end", "dgi_threshold_update",
     "dgi_threshold_halve", "dgi_batch_input_set_size", "dgi_reorder_permutation", "dgi_status_string",
     "dgi_last_error", "dgi_version",
 ]
@@ -272,6 +279,21 @@ def infer(graph, layer_structs, x, out, batch_size=0, perm_new_of_old=None, mem_
     d = {k: (list(getattr(stats, k))[:n] if hasattr(getattr(stats, k), "__len__") else getattr(stats, k))
          for k, _ in StatsStruct._fields_ if k != "reserved"}
     return d
+
+
+def infer_partial(graph, layer_structs, x, targets, out, batch_size=0, mem_budget_bytes=0):
+    """targets: torch int32 CUDA tensor; out: [len(targets), out_dim] CUDA tensor.  Returns the annotation stats."""
+    arr = (LayerStruct * len(layer_structs))(*layer_structs)
+    opts = OptsStruct()
+    opts.batch_size = int(batch_size)
+    opts.mem_budget_bytes = int(mem_budget_bytes)
+    ps = PartialStatsStruct()
+    _check(_lib.dgi_infer_partial(graph.handle, arr, ctypes.c_int32(len(layer_structs)), _dptr(x), ctypes.c_int64(x.stride(0)),
+                                  _dptr(targets), ctypes.c_int64(targets.numel()), _dptr(out), ctypes.c_int64(out.stride(0)),
+                                  ctypes.byref(opts), ctypes.byref(ps), _stream()))
+    n = ps.num_layers
+    return {"set_size": list(ps.set_size)[:n + 1], "all_nodes_from_layer": ps.all_nodes_from_layer,
+            "sub_nodes": ps.sub_nodes, "sub_edges": ps.sub_edges}
 
 
 # ---- host-side planning helpers (no device access) ------------------------------------------------------

@@ -124,6 +124,13 @@ def test_config5_full_size_sampled_rows_and_reordering():
     want = nodewise_oracle(cfg["indptr"], cfg["indices"], cfg["x"], layers, targets, 2)
     tt = torch.tensor(targets, device="cuda")
     assert max_rel_err(out[tt].cpu().numpy(), want) <= 1e-4
+    # partial inference of the same targets (Section 3.3): a small sub-problem, the same rows
+    tgt = tt.to(torch.int32)
+    pout = torch.empty(len(targets), 64, dtype=torch.float32, device="cuda")
+    pst = bd.infer_partial(g, structs, cfg["x"].contiguous(), tgt, pout)
+    print("cfg5 partial: sets %s, sub-problem %d nodes / %d edges" % (pst["set_size"], pst["sub_nodes"], pst["sub_edges"]), flush=True)
+    assert pst["all_nodes_from_layer"] == -1 and pst["sub_nodes"] < cfg["num_nodes"] // 100
+    assert max_rel_err(pout.cpu().numpy(), want) <= 1e-4
     # batch sizes of the ablation: bitwise the same output
     for bs in (64 * 1024, 1 << 20):
         out2 = torch.empty_like(out)

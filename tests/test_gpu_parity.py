@@ -342,3 +342,46 @@ def test_mixed_stack_with_gcn_source_scaling_folded_into_producers(order):
     out = torch.empty(n, 16, dtype=torch.float32, device="cuda")
     bd.infer(g, list(structs), torch.from_numpy(X).cuda(), out, batch_size=400)
     assert max_rel_err(out.cpu().numpy(), want) <= TOL_F32
+
+
+@pytest.mark.parametrize("kind", ["sage", "gcn", "gat"])
+def test_partial_inference_matches_the_oracle_rows(kind):
+    # Sections 2 / 3.3: output rows of a target subset only; V^l annotated backwards from the targets
+    bd = B()
+    n = 6000
+    indptr, indices = random_csr(n, 2.5, seed=91)
+    X = rnd((n, 32), 1)
+    if kind == "sage":
+        layers = [dict(agg="mean", act="relu", W_self=rnd((32, 48), 2, 0.2), W_neigh=rnd((32, 48), 3, 0.2), bias=rnd((48,), 4)),
+                  dict(agg="mean", act="none", W_self=rnd((48, 16), 5, 0.2), W_neigh=rnd((48, 16), 6, 0.2), bias=None)]
+    elif kind == "gcn":   # the normaliser needs the full graph's out-degrees, not the extracted sub-graph's
+        layers = [dict(agg="gcn", act="relu", W_neigh=rnd((32, 48), 2, 0.2), bias=rnd((48,), 4)),
+                  dict(agg="gcn", act="relu", W_neigh=rnd((48, 24), 5, 0.2), bias=rnd((24,), 7)),
+                  dict(agg="gcn", act="none", W_neigh=rnd((24, 16), 8, 0.2), bias=None)]
+    else:
+        layers = [dict(agg="gat", act="elu", W_neigh=rnd((32, 32), 2, 0.3), heads=2, attn_src=rnd((2, 16), 3, 0.5),
+                       attn_dst=rnd((2, 16), 4, 0.5), bias=rnd((32,), 5)),
+                  dict(agg="gat", act="none", W_neigh=rnd((32, 16), 6, 0.3), heads=1, attn_src=rnd((1, 16), 7, 0.5),
+                       attn_dst=rnd((1, 16), 8, 0.5), bias=None)]
+    want = oracle.infer(indptr, indices, layers, X)
+    g = bd.graph_load(indptr, indices)
+    structs, keep = zip(*[bd.make_layer(L) for L in layers])
+    x = torch.from_numpy(X).cuda()
+    rng = np.random.default_rng(3)
+    for count in (1, 17, 400, 5000):
+        t = rng.integers(0, n, count).astype(np.int32)
+        t[-1] = t[0]                                    # a duplicate target
+        targets = torch.from_numpy(t).cuda()
+        out = torch.full((count, 16), 777.0, dtype=torch.float32, device="cuda")
+        st = bd.infer_partial(g, list(structs), x, targets, out)
+        assert max_rel_err(out.cpu().numpy(), want[t]) <= TOL_F32, (kind, count)
+        L = len(layers)
+        assert st["set_size"][L] == np.unique(t).size
+        if count <= 17:
+            assert st["all_nodes_from_layer"] == -1 and st["sub_nodes"] < n     # a small sub-problem was extracted
+            sizes = st["set_size"]
+            assert all(sizes[l - 1] >= sizes[l] for l in range(1, L + 1))
+        if count == 5000:
+            assert st["all_nodes_from_layer"] == L - 1 and st["sub_nodes"] == n  # |V^L| d_avg >= n: shortcut
+    with pytest.raises(bd.DgiError):
+        bd.infer_partial(g, list(structs), x, torch.tensor([n], dtype=torch.int32, device="cuda"), out)
