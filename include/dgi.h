@@ -131,6 +131,11 @@ typedef struct {
     dgi_stats_t* stats;            /* HOST, or NULL.  Setting it makes dgi_infer wait for completion. */
     int64_t init_node_threshold;   /* initial n_t of Eq. 2 for batch_size==0; 0 = 65536 */
     int64_t init_edge_threshold;   /* initial n_i of Eq. 2; 0 = init_node_threshold * average degree */
+    int32_t jk_concat;             /* 1: jumping-knowledge stack (the paper's JKNet): layers 0..L-2 form a chain and the
+                                      last layer reads the concatenation of all their outputs, so layers[L-1].in_dim must
+                                      be the sum of the earlier out_dims; every hidden layer is kept until the last
+                                      layer has run */
+    int32_t reserved;
 } dgi_infer_opts_t;
 
 typedef struct {

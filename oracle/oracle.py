@@ -138,3 +138,14 @@ def infer(indptr, indices, layers, x):
     if rc != 0:
         raise RuntimeError("oracle_infer failed")
     return out
+
+
+def infer_jk(indptr, indices, layers, x):
+    """Jumping-knowledge stack (the JKNet example of the paper's appendix): layers[:-1] form a chain, each output
+    is kept, and the last layer is applied to their concatenation.  Plain composition of layer_forward."""
+    hs = []
+    h = _f32(x)
+    for layer in layers[:-1]:
+        h = layer_forward(indptr, indices, layer, h)
+        hs.append(h)
+    return layer_forward(indptr, indices, layers[-1], np.concatenate(hs, axis=1))

@@ -59,7 +59,7 @@ class OptsStruct(ctypes.Structure):
     _fields_ = [
         ("batch_size", ctypes.c_int64), ("perm_new_of_old", ctypes.c_void_p), ("mem_budget_bytes", ctypes.c_uint64),
         ("stats", ctypes.POINTER(StatsStruct)), ("init_node_threshold", ctypes.c_int64),
-        ("init_edge_threshold", ctypes.c_int64),
+        ("init_edge_threshold", ctypes.c_int64), ("jk_concat", ctypes.c_int32), ("reserved", ctypes.c_int32),
     ]
 
 
@@ -260,7 +260,7 @@ def layer_forward(graph, layer_struct, h_in, h_out, dst_begin, dst_end, workspac
 
 
 def infer(graph, layer_structs, x, out, batch_size=0, perm_new_of_old=None, mem_budget_bytes=0, want_stats=False,
-          init_node_threshold=0, init_edge_threshold=0):
+          init_node_threshold=0, init_edge_threshold=0, jk_concat=False):
     arr = (LayerStruct * len(layer_structs))(*layer_structs)
     opts = OptsStruct()
     opts.batch_size = int(batch_size)
@@ -268,6 +268,7 @@ def infer(graph, layer_structs, x, out, batch_size=0, perm_new_of_old=None, mem_
     opts.mem_budget_bytes = int(mem_budget_bytes)
     opts.init_node_threshold = int(init_node_threshold)
     opts.init_edge_threshold = int(init_edge_threshold)
+    opts.jk_concat = 1 if jk_concat else 0
     stats = StatsStruct() if want_stats else None
     if stats is not None:
         opts.stats = ctypes.pointer(stats)

@@ -355,20 +355,40 @@ extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layer
                                   int64_t ld_x, void* out, int64_t ld_out, const dgi_infer_opts_t* opts, void* hip_stream) {
     DGI_REQUIRE(g != nullptr && layers != nullptr, DGI_ERR_INVALID_ARG, "infer: NULL argument");
     DGI_REQUIRE(num_layers >= 1 && num_layers <= DGI_MAX_LAYERS, DGI_ERR_INVALID_ARG, "infer: 1..%d layers supported", DGI_MAX_LAYERS);
+    dgi_infer_opts_t o{};
+    if (opts) o = *opts;
+    // Jumping-knowledge stack (the paper's JKNet example): the last layer reads the concatenation of all earlier
+    // layer outputs.  The hidden layers then live side by side in one [N x sum(out_dim)] matrix: layer l writes
+    // its column block, layer l+1 reads that block, the last layer reads all of it (leading dimensions do the rest),
+    // and no hidden layer is released before the last layer has run.
+    const bool jk = o.jk_concat != 0;
+    int64_t ld_cat = 0;
+    std::vector<int64_t> cat_off((size_t)num_layers, 0);
+    if (jk) {
+        DGI_REQUIRE(num_layers >= 2, DGI_ERR_INVALID_ARG, "infer: a jumping-knowledge stack needs at least 2 layers");
+        const int hd = layers[0].out_dtype, E = 16 / elem_bytes(hd);
+        for (int l = 0; l + 1 < num_layers; ++l) {
+            DGI_REQUIRE(layers[l].out_dtype == hd, DGI_ERR_INVALID_ARG, "infer: jumping-knowledge layers must share one hidden dtype");
+            DGI_REQUIRE(layers[l].out_dim % E == 0, DGI_ERR_UNSUPPORTED, "infer: jumping-knowledge hidden widths must be multiples of 16 bytes");
+            cat_off[l] = ld_cat;
+            ld_cat += layers[l].out_dim;
+        }
+        DGI_REQUIRE(layers[num_layers - 1].in_dim == ld_cat && layers[num_layers - 1].feat_dtype == hd, DGI_ERR_INVALID_ARG,
+                    "infer: the last jumping-knowledge layer must read the concatenation of all earlier outputs");
+    }
     std::vector<LayerPlan> plans((size_t)num_layers);
     for (int l = 0; l < num_layers; ++l) {
         // layer 0 reads the caller's x; later layers read the library's own 16-byte aligned hidden buffers.  With a
         // permutation, layer 0 reads the library's permuted copy of x instead.
-        const bool own_input = l > 0 || (opts && opts->perm_new_of_old) || layers[0].agg == DGI_AGG_GCN;
-        const int64_t own_ld = round_up(layers[l].in_dim, 16 / elem_bytes(layers[l].feat_dtype));
+        const bool scaled_x = layers[0].agg == DGI_AGG_GCN && !jk;
+        const bool own_input = l > 0 || o.perm_new_of_old || scaled_x;
+        const int64_t own_ld = (jk && l > 0) ? ld_cat : round_up(layers[l].in_dim, 16 / elem_bytes(layers[l].feat_dtype));
         DGI_TRY(plan_layer(g, &layers[l], own_input ? reinterpret_cast<const void*>(256) : x, own_input ? own_ld : ld_x, &plans[l]));
-        if (l > 0) {
+        if (l > 0 && !(jk && l == num_layers - 1)) {
             DGI_REQUIRE(layers[l].in_dim == layers[l - 1].out_dim, DGI_ERR_INVALID_ARG, "layer %d: in_dim != previous out_dim", l);
             DGI_REQUIRE(layers[l].feat_dtype == layers[l - 1].out_dtype, DGI_ERR_INVALID_ARG, "layer %d: feat_dtype != previous out_dtype", l);
         }
     }
-    dgi_infer_opts_t o{};
-    if (opts) o = *opts;
     DGI_REQUIRE(o.batch_size >= 0, DGI_ERR_INVALID_ARG, "infer: negative batch_size");
     if (o.stats) { std::memset(o.stats, 0, sizeof(dgi_stats_t)); o.stats->num_layers = num_layers; }
     const int64_t N = g->N;
@@ -392,13 +412,17 @@ extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layer
         const int eb = elem_bytes(layers[l].out_dtype);
         hidden_bytes = std::max<uint64_t>(hidden_bytes, (uint64_t)round_up(N * round_up(layers[l].out_dim, 16 / eb) * eb, 256));
     }
-    const int n_hidden = num_layers >= 3 ? 2 : (num_layers == 2 ? 1 : 0);
+    int n_hidden = num_layers >= 3 ? 2 : (num_layers == 2 ? 1 : 0);
+    if (jk) {  // one concatenated matrix instead of ping-pong buffers
+        hidden_bytes = (uint64_t)round_up(N * ld_cat * elem_bytes(layers[0].out_dtype), 256);
+        n_hidden = 1;
+    }
     const bool permuted = o.perm_new_of_old != nullptr;
     const int xb = elem_bytes(L0.feat_dtype), yb = elem_bytes(LL.out_dtype);
     const int64_t ld_xp = round_up(L0.in_dim, 16 / xb), ld_yp = round_up(LL.out_dim, 16 / yb);
     // GCN layers gather rows already multiplied by d_out(u)^-1/2: every layer folds the next layer's factor into
     // its epilogue, and the input of a first GCN layer is scaled once into a library-owned copy.
-    const bool scale_x = L0.agg == DGI_AGG_GCN;
+    const bool scale_x = L0.agg == DGI_AGG_GCN && !jk;  // (a jumping-knowledge output has several consumers: no folding)
     const uint64_t xp_bytes = (permuted || scale_x) ? (uint64_t)round_up(N * ld_xp * xb, 256) : 0;
     const uint64_t yp_bytes = permuted ? (uint64_t)round_up(N * ld_yp * yb, 256) : 0;
     uint64_t fixed_max = 0, temp_full_max = 0;
@@ -456,9 +480,11 @@ extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layer
         const bool last = l == num_layers - 1;
         void* dst; int64_t ld_dst;
         if (last) { dst = permuted ? (void*)yp : out; ld_dst = permuted ? ld_yp : ld_out; }
+        else if (jk) { dst = hid[0] + cat_off[l] * elem_bytes(L.out_dtype); ld_dst = ld_cat; }
         else { dst = hid[l % 2]; ld_dst = round_up(L.out_dim, 16 / elem_bytes(L.out_dtype)); }
-        const bool in_prescaled = L.agg == DGI_AGG_GCN && (l == 0 || layers[l - 1].agg != DGI_AGG_GAT);
-        const float* out_scale = (!last && layers[l + 1].agg == DGI_AGG_GCN && L.agg != DGI_AGG_GAT) ? g->d_rs_out : nullptr;
+        if (jk && last) { cur = hid[0]; ld_cur = ld_cat; }  // the whole concatenation
+        const bool in_prescaled = !jk && L.agg == DGI_AGG_GCN && (l == 0 || layers[l - 1].agg != DGI_AGG_GAT);
+        const float* out_scale = (!jk && !last && layers[l + 1].agg == DGI_AGG_GCN && L.agg != DGI_AGG_GAT) ? g->d_rs_out : nullptr;
         if (tm) { tm->layer = l; DGI_TRY(tm->begin(SPAN_LAYER)); }
         const size_t layer_span = tm ? tm->spans.size() - 1 : 0;
         char* Wt = fixed;

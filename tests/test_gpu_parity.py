@@ -385,3 +385,30 @@ def test_partial_inference_matches_the_oracle_rows(kind):
             assert st["all_nodes_from_layer"] == L - 1 and st["sub_nodes"] == n  # |V^L| d_avg >= n: shortcut
     with pytest.raises(bd.DgiError):
         bd.infer_partial(g, list(structs), x, torch.tensor([n], dtype=torch.int32, device="cuda"), out)
+
+
+@pytest.mark.parametrize("last", ["gcn", "mean"])
+def test_jumping_knowledge_stack(last):
+    # the last layer reads the concatenation of all earlier layer outputs (the paper's JKNet example)
+    bd = B()
+    n = 3000
+    indptr, indices = random_csr(n, 8.0, seed=55)
+    X = rnd((n, 48), 1)
+    dims = [48, 64, 32, 64]
+    layers = []
+    for l in range(3):
+        layers.append(dict(agg="mean", act="relu", W_self=rnd((dims[l], dims[l + 1]), 10 + l, 0.2),
+                           W_neigh=rnd((dims[l], dims[l + 1]), 20 + l, 0.2), bias=rnd((dims[l + 1],), 30 + l)))
+    cat = sum(dims[1:])
+    layers.append(dict(agg=last, act="none", W_self=None if last == "gcn" else rnd((cat, 24), 40, 0.1),
+                       W_neigh=rnd((cat, 24), 41, 0.1), bias=rnd((24,), 42)))
+    want = oracle.infer_jk(indptr, indices, layers, X)
+    g = bd.graph_load(indptr, indices)
+    structs, keep = zip(*[bd.make_layer(L) for L in layers])
+    out = torch.empty(n, 24, dtype=torch.float32, device="cuda")
+    for bs in (0, 700):
+        st = bd.infer(g, list(structs), torch.from_numpy(X).cuda(), out, jk_concat=True, batch_size=bs, want_stats=True)
+        assert max_rel_err(out.cpu().numpy(), want) <= TOL_F32
+    assert st["gather_width"][-1] in (cat, 24)
+    with pytest.raises(bd.DgiError):   # the last layer must read the whole concatenation
+        bd.infer(g, list(structs[:3]), torch.from_numpy(X).cuda(), torch.empty(n, 64, device="cuda"), jk_concat=True)

@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_sizes_match_header_layout():
     # natural alignment of the C structs in dgi.h
     assert ctypes.sizeof(B.LayerStruct) == 9 * 4 + 4 + 5 * 8 + 4 + 4
-    assert ctypes.sizeof(B.OptsStruct) == 6 * 8
+    assert ctypes.sizeof(B.OptsStruct) == 7 * 8
     assert ctypes.sizeof(B.StatsStruct) == 8 + 8 + 16 * (8 * 8 + 4 * 3) + 16
     assert ctypes.sizeof(B.GraphInfoStruct) == 5 * 8 + 8 + 8
 

@@ -339,3 +339,18 @@ def test_empty_graph_and_empty_rows():
     layer = dict(agg="mean", act="relu", W_self=rnd((3, 2), 1), W_neigh=rnd((3, 2), 2), bias=None)
     out = oracle.layer_forward(np.zeros(1, np.int64), np.zeros(0, np.int32), layer, np.zeros((0, 3), np.float32))
     assert out.shape == (0, 2)
+
+
+def test_jumping_knowledge_stack_matches_dense_algebra():
+    # JKNet (the paper's appendix example): the last layer reads the concatenation of all earlier layer outputs
+    indptr, indices = random_csr(40, 3.0, seed=31)
+    A = dense_adjacency(indptr, indices)
+    X = rnd((40, 6), 1)
+    l1 = dict(agg="mean", act="relu", W_self=rnd((6, 8), 2), W_neigh=rnd((6, 8), 3), bias=rnd((8,), 4))
+    l2 = dict(agg="mean", act="relu", W_self=rnd((8, 4), 5), W_neigh=rnd((8, 4), 6), bias=rnd((4,), 7))
+    l3 = dict(agg="gcn", act="none", W_neigh=rnd((12, 5), 8), bias=rnd((5,), 9))
+    h1 = sage_dense(A, X, l1["W_self"], l1["W_neigh"], l1["bias"], "relu", "mean")
+    h2 = sage_dense(A, h1.astype(np.float32), l2["W_self"], l2["W_neigh"], l2["bias"], "relu", "mean")
+    want = gcn_dense(A, np.concatenate([h1, h2], axis=1).astype(np.float32), l3["W_neigh"], l3["bias"], "none")
+    got = oracle.infer_jk(indptr, indices, [l1, l2, l3], X)
+    np.testing.assert_allclose(got, want, rtol=1e-5, atol=1e-5)
