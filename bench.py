@@ -201,6 +201,11 @@ def main():
         del a, b
     n_layers = len(structs)
     agg_edges = n_layers * e
+    step_ms = sorted(s_["total_ms"] for s_ in stats)  # per-call HIP-event time, first enqueue to last completion
+    deg = torch.diff(cfg["indptr"].to(torch.int64)).double()
+    q = torch.quantile(deg[torch.randperm(n, device=dev)[:min(n, 4_000_000)]], torch.tensor([0.5, 0.9, 0.99, 0.999], dtype=torch.float64, device=dev))
+    degree_stats = {"mean": round(float(deg.mean()), 2), "max": int(deg.max()), "zero_rows": int((deg == 0).sum()),
+                    "p50": int(q[0]), "p90": int(q[1]), "p99": int(q[2]), "p99.9": int(q[3])}
 
     # dominant kernel: the aggregation launch with the largest total time
     agg_ms = [sum(s["agg_ms"][l] for s in stats) for l in range(n_layers)]
@@ -233,13 +238,14 @@ def main():
         "warmup": args.warmup,
         "ms_per_step": sec * 1e3,
         "inference_seconds": sec,
+        "ms_per_step_median": step_ms[len(step_ms) // 2], "ms_per_step_min": step_ms[0],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16" if storage == "bf16" else "f32",
         "data": "synthetic",
         "config": {"workload": cfg["name"], "num_nodes": n, "num_edges": e, "max_in_degree": info["max_in_degree"],
-                   "hub_rows": info["num_hub_rows"], "hub_edges": info["num_hub_edges"], "scale": args.scale, "batch_size": args.batch_size or "dynamic",
+                   "in_degree": degree_stats, "hub_rows": info["num_hub_rows"], "hub_edges": info["num_hub_edges"], "scale": args.scale, "batch_size": args.batch_size or "dynamic",
                    "batches_per_layer": stats[-1]["batches"], "transform_first": stats[-1]["transform_first"], "fused": stats[-1]["fused"],
                    "generate_seconds": round(t_gen, 2)},
         "per_layer_ms": {"layer": [round(sum(s["layer_ms"][l] for s in stats) / args.steps, 3) for l in range(n_layers)],

@@ -14,6 +14,7 @@
 // of a row in chunk order and applies the epilogue.  No floating-point atomics anywhere.
 #include <algorithm>
 
+#include "dgi_device.h"
 #include "dgi_internal.h"
 
 namespace dgi {
@@ -78,22 +79,6 @@ struct FusedParams {
     int64_t hub_ld;
     int lds_ld;            // elements per row of the LDS tile
 };
-
-__device__ __forceinline__ float bf16_to_float(uint32_t hi16) { return __uint_as_float(hi16 << 16); }
-__device__ __forceinline__ uint16_t float_to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // NaN stays NaN
-    u += 0x7fffu + ((u >> 16) & 1u);  // round to nearest even
-    return (uint16_t)(u >> 16);
-}
-__device__ __forceinline__ float activate(float x, int act, float slope) {
-    switch (act) {
-        case DGI_ACT_RELU: return x > 0.f ? x : 0.f;
-        case DGI_ACT_ELU: return x > 0.f ? x : slope * expm1f(x);
-        case DGI_ACT_LEAKY_RELU: return x > 0.f ? x : slope * x;
-        default: return x;
-    }
-}
 
 template <typename T> struct Row;
 template <> struct Row<float> {

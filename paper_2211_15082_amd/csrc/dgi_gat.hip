@@ -7,6 +7,7 @@
 // single sweep: every lane group keeps a running maximum m, a running denominator l and the weighted
 // sum rescaled by exp(m_old - m_new) per block of UNROLL neighbours; the lane groups are merged at the
 // end with the same rule.  Scores are shifted by the running maximum before exp, so nothing overflows.
+#include "dgi_device.h"
 #include "dgi_internal.h"
 
 namespace dgi {
@@ -33,25 +34,11 @@ struct GatParams {
     int64_t row_begin, row_end;
 };
 
-__device__ __forceinline__ uint16_t f2bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
-__device__ __forceinline__ float act_gat(float x, int act, float slope) {
-    switch (act) {
-        case DGI_ACT_RELU: return x > 0.f ? x : 0.f;
-        case DGI_ACT_ELU: return x > 0.f ? x : slope * expm1f(x);
-        case DGI_ACT_LEAKY_RELU: return x > 0.f ? x : slope * x;
-        default: return x;
-    }
-}
 __device__ __forceinline__ void store_out(const GatParams& p, int64_t v, int c, float val) {
     if (p.bias) val += p.bias[c];
-    val = act_gat(val, p.act, p.act_slope);
+    val = activate(val, p.act, p.act_slope);
     const int64_t o = (v - p.out_row0) * p.ld_out + c;
-    if (p.out_bf16) static_cast<uint16_t*>(p.out)[o] = f2bf16(val);
+    if (p.out_bf16) static_cast<uint16_t*>(p.out)[o] = float_to_bf16(val);
     else static_cast<float*>(p.out)[o] = val;
 }
 

@@ -12,6 +12,7 @@
 // fragment reads of 8 consecutive lanes cover all banks.
 #include <algorithm>
 
+#include "dgi_device.h"
 #include "dgi_internal.h"
 
 namespace dgi {
@@ -31,21 +32,6 @@ struct GemmParams {
     int tiles_n;
     const float* out_scale; int64_t row0;
 };
-
-__device__ __forceinline__ uint16_t f2bf(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
-__device__ __forceinline__ float act_fn(float x, int act, float slope) {
-    switch (act) {
-        case DGI_ACT_RELU: return x > 0.f ? x : 0.f;
-        case DGI_ACT_ELU: return x > 0.f ? x : slope * expm1f(x);
-        case DGI_ACT_LEAKY_RELU: return x > 0.f ? x : slope * x;
-        default: return x;
-    }
-}
 
 // 16 bytes of row `row` starting at element k of a [rows x K] matrix; zero outside [0,rows) x [0,K).
 template <typename T>
@@ -187,9 +173,9 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmParams p) {
             for (int r = 0; r < 16; ++r) {
                 const int64_t m = m0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * lhalf + (r % 4);
                 if (m >= p.M) continue;
-                float v = act_fn(acc[i][j][r] + b, p.act, p.act_slope);
+                float v = activate(acc[i][j][r] + b, p.act, p.act_slope);
                 if (p.out_scale) v *= p.out_scale[p.row0 + m];
-                if (p.out_bf16) static_cast<uint16_t*>(p.Y)[m * p.ld_y + n] = f2bf(v);
+                if (p.out_bf16) static_cast<uint16_t*>(p.Y)[m * p.ld_y + n] = float_to_bf16(v);
                 else static_cast<float*>(p.Y)[m * p.ld_y + n] = v;
             }
         }
@@ -244,7 +230,7 @@ __global__ void scale_rows_kernel(const T* in, int64_t ld_in, T* out, int64_t ld
             reinterpret_cast<float*>(out)[r * ld_out + c] = reinterpret_cast<const float*>(in)[r * ld_in + c] * scale[r];
         } else {
             const float f = __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(in)[r * ld_in + c] << 16) * scale[r];
-            reinterpret_cast<uint16_t*>(out)[r * ld_out + c] = f2bf(f);
+            reinterpret_cast<uint16_t*>(out)[r * ld_out + c] = float_to_bf16(f);
         }
     }
 }

@@ -172,3 +172,23 @@ def test_rcm_on_a_path_is_the_path():
     perm = B.reorder_permutation(indptr, indices, "bfs_rcm")
     pos = perm[order]
     assert (np.abs(np.diff(pos)) == 1).all()
+
+
+def test_argument_validation_fails_before_any_device_work():
+    # these calls must be rejected by host-side checks alone (this test runs without a GPU)
+    lib = ctypes.CDLL(B.LIB_PATH)
+    h = ctypes.c_void_p()
+    ip = np.zeros(3, dtype=np.int64)
+    args = lambda n, e, p: (ctypes.c_int64(n), ctypes.c_int64(e), p, ctypes.c_int32(B.I64), None, ctypes.c_int32(B.HOST), None, ctypes.byref(h))
+    assert lib.dgi_graph_load(*args(-1, 0, ip.ctypes.data_as(ctypes.c_void_p))) == B.ERR_INVALID_ARG
+    assert lib.dgi_graph_load(*args(2, 0, None)) == B.ERR_INVALID_ARG
+    assert lib.dgi_graph_load(*args(2, 5, ip.ctypes.data_as(ctypes.c_void_p))) == B.ERR_INVALID_ARG   # indices NULL with edges
+    assert "indices" in B.last_error()
+    assert lib.dgi_graph_free(None) == B.OK
+    assert lib.dgi_infer(None, None, 1, None, 0, None, 0, None, None) == B.ERR_INVALID_ARG
+    assert lib.dgi_layer_forward(None, None, None, 0, None, 0, 0, 0, None, 0, None) == B.ERR_INVALID_ARG
+    assert lib.dgi_infer_partial(None, None, 1, None, 0, None, 0, None, 0, None, None, None) == B.ERR_INVALID_ARG
+    with pytest.raises(B.DgiError) as ei:
+        B.plan_batch_end(np.zeros(4, np.int64), 3, 5, 1, 1)
+    assert ei.value.status == B.ERR_INVALID_ARG and "begin" in str(ei.value)
+    assert lib.dgi_reorder_permutation(ctypes.c_int64(2), None, None, 1, ctypes.c_uint64(0), None) == B.ERR_INVALID_ARG
