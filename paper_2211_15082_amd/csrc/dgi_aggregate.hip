@@ -343,9 +343,9 @@ __device__ __forceinline__ uint4 pack_row_chunk(const float* f) {  // VEC floats
 
 // Aggregation fused with the layer's dense transform (aggregate-first layers).  A workgroup owns 32
 // destination rows.  Phase 1: its four wavefronts gather and aggregate 8 rows each exactly as the
-// stand-alone kernel does, but deposit the scaled result (and, for GraphSAGE, the row's own features) in an
-// LDS tile laid out like the packed weight's K axis.  Phase 2: the tile is the A operand of MFMA
-// (32 x K), B comes from the packed weight through L2, each wavefront owns every fourth 32-column block;
+// stand-alone kernel does, but deposit the scaled result in an LDS tile (32 x K).  Phase 2: the tile is the
+// A operand of MFMA, the rows' own features (GraphSAGE) are a second A block read straight from global
+// memory, B comes from the packed weight through L2, each wavefront owns every fourth 32-column block;
 // bias, activation and the output conversion happen in registers.  The aggregated matrix never exists
 // in HBM.  Hub rows arrive pre-aggregated (fp32) from the two-stage hub pass that runs before this launch.
 template <typename T, typename IdxT, int G, int MODE>
@@ -386,16 +386,10 @@ __global__ __launch_bounds__(kWaves * 64) void fused_layer_kernel(FusedParams fp
         const int cur = nxt;
         if (r + 1 < RPW) nxt = (int64_t)lane < (int64_t)(bound[r + 2 <= RPW ? r + 2 : RPW] - ee) ? p.indices[(int64_t)ee + lane] : 0;
         if (v >= p.row_end) {  // rows past the range: an all-zero A row
-            for (int ch = lane; ch < (int)(fp.ldw / VEC); ch += 64) *reinterpret_cast<uint4*>(trow + ch * VEC) = make_uint4(0u, 0u, 0u, 0u);
+            for (int ch = lane; ch < chunks; ch += 64) *reinterpret_cast<uint4*>(trow + ch * VEC) = make_uint4(0u, 0u, 0u, 0u);
             continue;
         }
-        if (fp.has_self) {  // the row's own features: columns [0, Kp) of the tile
-            const T* hrow = static_cast<const T*>(p.S) + v * p.ld_s;
-            for (int ch = lane; ch < chunks; ch += 64)
-                *reinterpret_cast<uint4*>(trow + ch * VEC) =
-                    ch * VEC < K ? *reinterpret_cast<const uint4*>(hrow + ch * VEC) : make_uint4(0u, 0u, 0u, 0u);
-        }
-        T* arow = trow + fp.K1p;
+        T* arow = trow;
         if (p.skip_hubs && deg > (IdxT)kHubDegree) {  // pre-aggregated by the hub pass
             int64_t lo = p.hub_begin, hi = p.hub_end;
             while (hi - lo > 1) {
@@ -428,53 +422,63 @@ __global__ __launch_bounds__(kWaves * 64) void fused_layer_kernel(FusedParams fp
     }
     __syncthreads();
 
-    // ---- phase 2: out[32 x N] = act(tile[32 x ldw] . Wt^T + bias) on the matrix cores -----------------
+    // ---- phase 2: out[32 x N] = act([h_v | tile] . Wt^T + bias) on the matrix cores ------------------------
+    // A operand: the aggregated block comes from the LDS tile; the rows' own features (GraphSAGE) are read from
+    // global memory straight into MFMA fragment layout (lane = row, 16 bytes of K), which keeps the tile small.
+    // B operand: the packed weight through L2.  A wavefront owns column blocks wave, wave+4, ... one at a time
+    // (two per sweep would halve the A reads but costs registers, i.e. gather occupancy: measured slower).
     const int lrow = lane & 31, lhalf = lane >> 5;
     const int nblk = (fp.N + 31) / 32;
-    const T* a_base = tile + lrow * fp.lds_ld + lhalf * VEC;
-    const int ksteps = (int)(fp.ldw / (2 * VEC));
+    const int ksteps = Kp / (2 * VEC);
+    const int64_t vrow = vt + lrow;
+    const T* a_lds = tile + lrow * fp.lds_ld + lhalf * VEC;
+    const T* a_self = static_cast<const T*>(p.S) + (vrow < p.row_end ? vrow : p.row_begin) * p.ld_s + lhalf * VEC;
+    const bool self_row = fp.has_self && vrow < p.row_end;
+    auto mma = [&](floatx16_t& acc, const uint4& a, const uint4& b) {
+        if (sizeof(T) == 4) {
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+        } else {
+            bf16x8_t av, bv;
+            __builtin_memcpy(&av, &a, 16);
+            __builtin_memcpy(&bv, &b, 16);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc, 0, 0, 0);
+        }
+    };
     for (int cb = wave; cb < nblk; cb += kWaves) {
         const int n = cb * 32 + lrow;
-        const T* w_base = static_cast<const T*>(fp.Wt) + (int64_t)(n < fp.N ? n : fp.N - 1) * fp.ldw + lhalf * VEC;
+        const T* w = static_cast<const T*>(fp.Wt) + (int64_t)(n < fp.N ? n : fp.N - 1) * fp.ldw + lhalf * VEC;
         floatx16_t acc;
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-        int ks = 0;
-        for (; ks + 4 <= ksteps; ks += 4) {
-            uint4 b[4], a[4];
+        constexpr int U = 4;
+        if (fp.has_self) {  // K block of the rows' own features: columns [0, Kp) of the packed weight
+            for (int ks = 0; ks < ksteps; ks += U) {
+                uint4 a[U], b[U];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) b[u] = *reinterpret_cast<const uint4*>(w_base + (ks + u) * 2 * VEC);
-#pragma unroll
-            for (int u = 0; u < 4; ++u) a[u] = *reinterpret_cast<const uint4*>(a_base + (ks + u) * 2 * VEC);
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                if (sizeof(T) == 4) {
-                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[u].x), __uint_as_float(b[u].x), acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[u].y), __uint_as_float(b[u].y), acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[u].z), __uint_as_float(b[u].z), acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[u].w), __uint_as_float(b[u].w), acc, 0, 0, 0);
-                } else {
-                    bf16x8_t av, bv;
-                    __builtin_memcpy(&av, &a[u], 16);
-                    __builtin_memcpy(&bv, &b[u], 16);
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc, 0, 0, 0);
+                for (int u = 0; u < U; ++u) {
+                    const int k = (ks + u) * 2 * VEC;  // + lhalf * VEC is inside the base pointers
+                    const bool in = ks + u < ksteps;
+                    a[u] = (in && self_row && k + lhalf * VEC < K) ? *reinterpret_cast<const uint4*>(a_self + k) : make_uint4(0u, 0u, 0u, 0u);
+                    b[u] = in ? *reinterpret_cast<const uint4*>(w + k) : make_uint4(0u, 0u, 0u, 0u);
                 }
+#pragma unroll
+                for (int u = 0; u < U; ++u) mma(acc, a[u], b[u]);
             }
         }
-        for (; ks < ksteps; ++ks) {
-            const uint4 b = *reinterpret_cast<const uint4*>(w_base + ks * 2 * VEC);
-            const uint4 a = *reinterpret_cast<const uint4*>(a_base + ks * 2 * VEC);
-            if (sizeof(T) == 4) {
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
-            } else {
-                bf16x8_t av, bv;
-                __builtin_memcpy(&av, &a, 16);
-                __builtin_memcpy(&bv, &b, 16);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc, 0, 0, 0);
+        for (int ks = 0; ks < ksteps; ks += U) {  // K block of the aggregated neighbourhood: columns [K1p, K1p + Kp)
+            uint4 a[U], b[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int k = (ks + u) * 2 * VEC;
+                const bool in = ks + u < ksteps;
+                b[u] = in ? *reinterpret_cast<const uint4*>(w + fp.K1p + k) : make_uint4(0u, 0u, 0u, 0u);
+                a[u] = in ? *reinterpret_cast<const uint4*>(a_lds + k) : make_uint4(0u, 0u, 0u, 0u);
             }
+#pragma unroll
+            for (int u = 0; u < U; ++u) mma(acc, a[u], b[u]);
         }
         if (n < fp.N) {
             const float bias = fp.bias ? fp.bias[n] : 0.f;
@@ -484,9 +488,7 @@ __global__ __launch_bounds__(kWaves * 64) void fused_layer_kernel(FusedParams fp
                 if (v >= p.row_end) continue;
                 float val = activate(acc[r] + bias, fp.act, fp.act_slope);
                 if (fp.out_scale) val *= fp.out_scale[v];
-                const int64_t o = (v - fp.out_row0) * fp.ld_out + n;
-                if (fp.out_bf16) static_cast<uint16_t*>(fp.out)[o] = float_to_bf16(val);
-                else static_cast<float*>(fp.out)[o] = val;
+                store_element(fp.out, (v - fp.out_row0) * fp.ld_out + n, val, fp.out_bf16);
             }
         }
     }
@@ -687,7 +689,7 @@ bool fused_supported(const FusedArgs& a) {
     if ((uintptr_t)a.H % 16 || (a.ld_h * eb) % 16 || a.K % E || a.K / E <= 8) return false;
     if ((uintptr_t)a.Wt % 16 || a.ldw % (2 * E) || a.K1p % (2 * E)) return false;
     if (a.ldw != a.K1p + round_up(a.K, 2 * E)) return false;
-    return (size_t)kFusedRows * (size_t)(a.ldw + E) * eb <= kFusedMaxLds;
+    return (size_t)kFusedRows * (size_t)(round_up(a.K, 2 * E) + E) * eb <= kFusedMaxLds;
 }
 
 uint64_t fused_temp_bytes(const dgi_graph* g, int64_t row_begin, int64_t row_end, int K) {
@@ -715,7 +717,7 @@ dgi_status_t launch_fused(const FusedArgs& a, int stage, hipStream_t stream) {
     fp.Wt = a.Wt; fp.ldw = a.ldw; fp.K1p = a.K1p; fp.has_self = a.has_self ? 1 : 0; fp.N = a.N;
     fp.bias = a.bias; fp.act = a.act; fp.act_slope = a.act_slope; fp.out_scale = a.out_scale;
     fp.out = a.out; fp.ld_out = a.ld_out; fp.out_row0 = a.out_row0; fp.out_bf16 = a.out_dtype == DGI_BF16;
-    fp.lds_ld = (int)(a.ldw + E);
+    fp.lds_ld = (int)(round_up(a.K, 2 * E) + E);
     float* partials = static_cast<float*>(a.temp);
     float* hub_agg = a.temp ? reinterpret_cast<float*>(static_cast<char*>(a.temp) + round_up((int64_t)agg_hub_partial_bytes(g, a.row_begin, a.row_end, a.K), 256)) : nullptr;
     const bool i64 = g->itype == DGI_I64;

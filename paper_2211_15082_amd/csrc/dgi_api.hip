@@ -50,17 +50,21 @@ struct LayerPlan {
     bool fused = false;   // aggregate-first with the transform fused into the gather kernel
 };
 
-// Fusing the transform into the gather kernel removes the aggregated matrix's HBM round trip, but every
-// 32-row tile re-reads the packed weight from L2.  It pays when a row's gather (avg_degree * K elements)
-// outweighs its share of that re-read (ldw * N / 32 elements) by a wide margin; measured on MI355X the
-// break-even is a ratio of about 2 (GCN 256->256 at degree 52: ratio 6.5, 15 % faster fused; GraphSAGE
-// bf16 128->128 at degree 14: ratio 1.8, 40 % slower fused).  DGI_TUNE_FUSED = 0 / 2 forces never / always.
-bool want_fused(const dgi_graph* g, int K, int64_t ldw, int N) {
+// Fusing the transform into the gather kernel removes the aggregated matrix's HBM round trip and hides the MFMA
+// work under other workgroups' gathers, but every 32-row tile re-reads the packed weight from L2 in a
+// latency-bound sweep.  It pays when a row's gather (avg_degree * K elements) outweighs its share of that
+// sweep (ldw * N / 32 elements).  Measured on MI355X (fused vs split, whole layer):
+//   GCN fp32 256->256, degree 52 (ratio 6.5): 18.8 vs 22.0 ms;  GraphSAGE fp32 256->256, degree 20 (ratio 1.25):
+//   125 vs 133 ms;  GraphSAGE bf16 128->128, degree 14 (ratio 1.8): 155 vs 118 ms.
+// The split path's fp32 GEMM is MFMA-bound and expensive, its bf16 GEMM is cheap, hence the two thresholds.
+// DGI_TUNE_FUSED = 0 / 2 forces never / always (tuning aid).
+bool want_fused(const dgi_graph* g, int dtype, int K, int64_t ldw, int N) {
     static const int mode = [] { const char* e = getenv("DGI_TUNE_FUSED"); return e ? atoi(e) : 1; }();
     if (mode == 0) return false;
     if (mode == 2) return true;
     const double avg_deg = g && g->N > 0 ? (double)g->E / (double)g->N : 0.0;
-    return avg_deg * (double)K >= 3.0 * ((double)ldw * (double)N / 32.0);
+    const double ratio = avg_deg * (double)K / ((double)ldw * (double)N / 32.0);
+    return ratio >= (dtype == DGI_BF16 ? 3.0 : 1.0);
 }
 
 dgi_status_t validate_layer(const dgi_layer_t* L) {
@@ -113,7 +117,7 @@ dgi_status_t plan_layer(const dgi_graph* g, const dgi_layer_t* L, const void* h_
         fa.H = h_in; fa.ld_h = ld_in; fa.dtype = L->feat_dtype; fa.K = L->in_dim;
         fa.Wt = nullptr; fa.ldw = p.ldw; fa.K1p = p.K1p;
         const bool want = L->order == DGI_ORDER_AGG_FIRST_FUSED ||
-                          (L->order != DGI_ORDER_AGG_FIRST_SPLIT && want_fused(g, L->in_dim, p.ldw, L->out_dim));
+                          (L->order != DGI_ORDER_AGG_FIRST_SPLIT && want_fused(g, L->feat_dtype, L->in_dim, p.ldw, L->out_dim));
         p.fused = want && fused_supported(fa);
     }
     p.wt_bytes = (uint64_t)round_up((int64_t)p.w_rows * p.ldw * p.eb, 256);
