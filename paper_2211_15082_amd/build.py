@@ -24,7 +24,19 @@ def _compile(src):
     return obj, err
 
 
-def build_library(verbose=False):
+def build_library(verbose=False, extra_flags=(), lib_path=None):
+    """extra_flags / lib_path: build a variant next to the product library (tuning experiments)."""
+    global FLAGS, LIB
+    saved = (FLAGS, LIB)
+    FLAGS = [*FLAGS, *extra_flags]
+    LIB = lib_path or LIB
+    try:
+        return _build(verbose)
+    finally:
+        FLAGS, LIB = saved
+
+
+def _build(verbose):
     os.makedirs(OBJ_DIR, exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(6, os.cpu_count() or 1)) as ex:
         results = list(ex.map(_compile, SOURCES))

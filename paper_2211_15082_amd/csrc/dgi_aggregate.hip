@@ -20,8 +20,16 @@
 namespace dgi {
 namespace {
 
+#ifndef DGI_UNROLL_WIDE
+#define DGI_UNROLL_WIDE 8        // row loads in flight per lane when a whole wavefront covers one source row
+#endif
 constexpr int kWaves = 4;        // wavefronts per workgroup
-constexpr int kRowsPerWg = 16;   // destination rows per workgroup
+constexpr int kRowsPerWg = 16;   // destination rows per workgroup (wide rows)
+// Narrow rows (G <= 16 lanes per source row): every lane group owns its own destination row, so a wavefront
+// works on 64/G rows at once and a workgroup on 4 times that.
+template <int G> constexpr int rows_per_wave() { return (64 / G) > 4 ? (64 / G) : 4; }
+template <int G> constexpr int rows_per_wg() { return kWaves * rows_per_wave<G>(); }
+constexpr int kGroupRowMaxDegree = 64;  // longer rows are gathered by the whole wavefront instead
 constexpr int kXcds = 8;         // XCDs of MI355X; workgroup i is dispatched to XCD i % 8
 constexpr int kXcdRun = 8;       // consecutive tiles handed to one XCD, so that neighbouring rows share an L2
 
@@ -87,7 +95,15 @@ template <> struct Row<float> {
     static __device__ __forceinline__ Raw zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
     static __device__ __forceinline__ void unpack(const Raw& r, float* f) { f[0] = r.x; f[1] = r.y; f[2] = r.z; f[3] = r.w; }
     static __device__ __forceinline__ float one(const float* p) { return *p; }
+    // acc += row chunk if ok.  A masked-out chunk was loaded from another neighbour of the same destination row,
+    // so weighting it with 0 cannot bring in a NaN the true sum does not already have.
+    static __device__ __forceinline__ void add_masked(const Raw& r, bool ok, float* acc) {
+        const float w = ok ? 1.f : 0.f;
+        acc[0] = fmaf(w, r.x, acc[0]); acc[1] = fmaf(w, r.y, acc[1]);
+        acc[2] = fmaf(w, r.z, acc[2]); acc[3] = fmaf(w, r.w, acc[3]);
+    }
 };
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 template <> struct Row<uint16_t> {
     static constexpr int VEC = 8;
     using Raw = uint4;
@@ -99,6 +115,26 @@ template <> struct Row<uint16_t> {
         f[6] = __uint_as_float(r.w << 16); f[7] = __uint_as_float(r.w & 0xffff0000u);
     }
     static __device__ __forceinline__ float one(const uint16_t* p) { return bf16_to_float(*p); }
+    // acc += row chunk if ok, two fp32 accumulators per 32-bit word with v_dot2_f32_bf16 against (1,0) / (0,1):
+    // no unpacking, and the mask costs two selects per chunk instead of one per element.
+    // The selectors are kept in registers (the empty asm hides their value from the optimiser): folded into an
+    // inline constant, the (1,0) pair did not select the low half on gfx950.
+    static __device__ __forceinline__ void add_masked(const Raw& r, bool ok, float* acc) {
+        uint32_t one_lo = 0x00003f80u, one_hi = 0x3f800000u;
+        asm volatile("" : "+v"(one_lo), "+v"(one_hi));
+        const uint32_t sel_lo = ok ? one_lo : 0u, sel_hi = ok ? one_hi : 0u;
+        bf16x2_t lo, hi;
+        __builtin_memcpy(&lo, &sel_lo, 4);
+        __builtin_memcpy(&hi, &sel_hi, 4);
+        const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            bf16x2_t v;
+            __builtin_memcpy(&v, &w[i], 4);
+            acc[2 * i] = __builtin_amdgcn_fdot2_f32_bf16(v, lo, acc[2 * i], false);
+            acc[2 * i + 1] = __builtin_amdgcn_fdot2_f32_bf16(v, hi, acc[2 * i + 1], false);
+        }
+    }
 };
 
 // Tile handled by workgroup `bid`: runs of kXcdRun consecutive tiles go to the same XCD.
@@ -161,14 +197,14 @@ __device__ __forceinline__ void gather_range(const AggParams& p, int64_t eb, int
             }
 #pragma unroll
             for (int t = 0; t < UNROLL; ++t) {
-                float f[VEC];
-                Row<T>::unpack(raw[t], f);
                 if (MODE == MODE_GCN) {
+                    float f[VEC];
+                    Row<T>::unpack(raw[t], f);
+                    const float w = ok[t] ? c[t] : 0.f;
 #pragma unroll
-                    for (int i = 0; i < VEC; ++i) acc[i] = ok[t] ? fmaf(c[t], f[i], acc[i]) : acc[i];
+                    for (int i = 0; i < VEC; ++i) acc[i] = fmaf(w, f[i], acc[i]);
                 } else {
-#pragma unroll
-                    for (int i = 0; i < VEC; ++i) acc[i] += ok[t] ? f[i] : 0.f;
+                    Row<T>::add_masked(raw[t], ok[t], acc);
                 }
             }
         }
@@ -214,13 +250,130 @@ __device__ __forceinline__ IdxT bcast_lane(IdxT x, int src) {
     return (IdxT)__shfl((int)x, src, 64);
 }
 
+// Narrow rows: one lane group per destination row.  The 64/G groups of a wavefront walk their own neighbour
+// lists side by side (a group whose list is exhausted idles with its loads masked off), each lane keeps the
+// whole sum of its column slice, and no cross-group reduction or per-row bookkeeping by all 64 lanes is
+// needed: for low-degree graphs this kernel is bound by instruction issue, not by memory, and this mapping
+// issues about a quarter of the vector instructions per row.  Rows longer than kGroupRowMaxDegree are left to
+// the cooperative path below (whole wavefront per row), so one long list does not stall three short ones.
+template <typename T, typename IdxT, int G, int MODE>
+__device__ __forceinline__ void rows_tile_grouped(const AggParams& p, int64_t bid) {
+    constexpr int VEC = Row<T>::VEC;
+    constexpr int NSUB = 64 / G;
+    constexpr int RPW = rows_per_wave<G>();
+    constexpr int UNROLL = 4;
+    static_assert(RPW == NSUB, "one row per lane group");
+    using Raw = typename Row<T>::Raw;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t tile = xcd_tile(bid);
+    if (tile >= p.n_tiles) return;
+    const IdxT* indptr = static_cast<const IdxT*>(p.indptr);
+    const int sub = lane / G, gl = lane % G;
+    const int64_t vw = p.row_begin + tile * rows_per_wg<G>() + wave * RPW;
+    if (vw >= p.row_end) return;
+    IdxT ipv = 0;
+    if (lane <= RPW) {
+        const int64_t i = vw + lane;
+        ipv = indptr[i < p.row_end ? i : p.row_end];
+    }
+    // ---- phase A: every group gathers its own (short) row ----------------------------------------------------
+    const int64_t eb = (int64_t)bcast_lane<IdxT>(ipv, sub), ee = (int64_t)bcast_lane<IdxT>(ipv, sub + 1);
+    const int64_t v = vw + sub;
+    const int64_t deg = ee - eb;  // 0 for rows past the range
+    const bool mine = v < p.row_end && deg <= kGroupRowMaxDegree;
+    const int dg = mine ? (int)deg : 0;
+    const int col = gl * VEC;
+    const bool col_ok = col < p.width;
+    const T* sbase = static_cast<const T*>(p.S) + col;
+    float acc[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+    for (int base = 0; __any(base < dg); base += G) {
+        const int left = dg - base;  // edges of this group's row still to do (may be <= 0)
+        const int my = gl < left ? p.indices[eb + base + gl] : 0;
+        float myc = 1.f;
+        if (MODE == MODE_GCN) myc = gl < left ? p.rs_out[my] : 0.f;
+        for (int j = 0; j < G && __any(j < left); j += UNROLL) {
+            Raw raw[UNROLL];
+            float c[UNROLL];
+#pragma unroll
+            for (int t = 0; t < UNROLL; ++t) {
+                const int k = j + t;
+                const bool ok = k < left && col_ok;
+                const int u = __shfl(my, k, G);
+                if (MODE == MODE_GCN) c[t] = __shfl(myc, k, G);
+                raw[t] = ok ? *reinterpret_cast<const Raw*>(sbase + (int64_t)u * p.ld_s) : Row<T>::zero();
+            }
+#pragma unroll
+            for (int t = 0; t < UNROLL; ++t) {
+                if (MODE == MODE_GCN) {
+                    float f[VEC];
+                    Row<T>::unpack(raw[t], f);
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) acc[i] = fmaf(c[t], f[i], acc[i]);
+                } else {
+                    Row<T>::add_masked(raw[t], true, acc);  // masked-off chunks are zero already
+                }
+            }
+        }
+    }
+    if (mine && col_ok) {
+        const float scale = row_scale<MODE, int64_t>(p, v, deg);
+        const bool plain = !p.self && !p.bias && p.act == DGI_ACT_NONE && !p.out_scale;
+        if (plain && p.out_vec_ok && col + VEC <= p.width) {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] *= scale;
+            const int64_t o = (v - p.out_row0) * p.ld_out + col;
+            if (p.out_bf16) {
+                uint32_t w[VEC / 2];
+#pragma unroll
+                for (int i = 0; i < VEC / 2; ++i) w[i] = (uint32_t)float_to_bf16(acc[2 * i]) | ((uint32_t)float_to_bf16(acc[2 * i + 1]) << 16);
+#pragma unroll
+                for (int i = 0; i < VEC / 2; i += 2) *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + o + 2 * i) = make_uint2(w[i], w[i + 1]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < VEC; i += 4)
+                    *reinterpret_cast<float4*>(static_cast<float*>(p.out) + o + i) = make_float4(acc[i], acc[i + 1], acc[i + 2], acc[i + 3]);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i)
+                if (col + i < p.width) finish_store<T>(p, v, v - p.out_row0, col + i, acc[i], scale);
+        }
+    }
+    // ---- phase B: the wavefront's long rows, all lane groups on one row at a time ------------------------------
+    IdxT bound[RPW + 1];
+#pragma unroll
+    for (int i = 0; i <= RPW; ++i) bound[i] = bcast_lane<IdxT>(ipv, i);
+#pragma unroll
+    for (int r = 0; r < RPW; ++r) {
+        const int64_t vr = vw + r;
+        if (vr >= p.row_end) break;
+        const IdxT rb = bound[r], re = bound[r + 1];
+        const IdxT rdeg = re - rb;
+        if (rdeg <= (IdxT)kGroupRowMaxDegree) continue;
+        if (p.skip_hubs && rdeg > (IdxT)kHubDegree) continue;
+        const float scale = row_scale<MODE, IdxT>(p, vr, rdeg);
+        float a2[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) a2[i] = 0.f;
+        gather_range<T, G, MODE, UNROLL>(p, (int64_t)rb, (int64_t)re, lane, 0, a2);
+        combine_groups<G, VEC>(a2);
+        if (sub == 0 && col_ok) {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i)
+                if (col + i < p.width) finish_store<T>(p, vr, vr - p.out_row0, col + i, a2[i], scale);
+        }
+    }
+}
+
 // Workgroup `bid` of the row part: kRowsPerWg destination rows; each wavefront owns kRowsPerWg / kWaves
 // consecutive rows, reads their indptr entries with one load, and fetches the first 64 neighbour ids of the
 // next row while it gathers the current one (a row costs one dependent memory latency instead of three).
 template <typename T, typename IdxT, int G, int MODE>
 __device__ __forceinline__ void rows_tile(const AggParams& p, int64_t bid) {
     constexpr int VEC = Row<T>::VEC;
-    constexpr int UNROLL = (G == 64) ? 8 : 4;
+    constexpr int UNROLL = (G == 64) ? DGI_UNROLL_WIDE : 4;
     constexpr int RPW = kRowsPerWg / kWaves;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t tile = xcd_tile(bid);
@@ -287,7 +440,7 @@ __device__ __forceinline__ void rows_tile(const AggParams& p, int64_t bid) {
 template <typename T, typename IdxT, int G, int MODE>
 __device__ __forceinline__ void hub_chunk(const AggParams& p, int64_t block) {
     constexpr int VEC = Row<T>::VEC;
-    constexpr int UNROLL = (G == 64) ? 8 : 4;
+    constexpr int UNROLL = (G == 64) ? DGI_UNROLL_WIDE : 4;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t qi = block * kWaves + wave;
     if (qi >= p.n_chunks) return;
@@ -324,6 +477,7 @@ template <typename T, typename IdxT, int G, int MODE>
 __global__ __launch_bounds__(kWaves * 64) void agg_kernel(AggParams p) {
     const int64_t bid = blockIdx.x;
     if (bid < p.hub_blocks) hub_chunk<T, IdxT, G, MODE>(p, bid);
+    else if (G <= 16) rows_tile_grouped<T, IdxT, (G <= 16 ? G : 16), MODE>(p, bid - p.hub_blocks);
     else rows_tile<T, IdxT, G, MODE>(p, bid - p.hub_blocks);
 }
 
@@ -354,7 +508,7 @@ __global__ __launch_bounds__(kWaves * 64) void fused_layer_kernel(FusedParams fp
     T* tile = reinterpret_cast<T*>(lds_raw);
     const AggParams& p = fp.a;
     constexpr int VEC = Row<T>::VEC;  // elements per 16 bytes
-    constexpr int UNROLL = (G == 64) ? 8 : 4;
+    constexpr int UNROLL = (G == 64) ? DGI_UNROLL_WIDE : 4;
     constexpr int RPW = kFusedRows / kWaves;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t tile_id = xcd_tile(blockIdx.x);
@@ -537,7 +691,8 @@ template <typename T, typename IdxT, int G, int MODE>
 dgi_status_t launch_fast(const AggParams& p0, const dgi_graph* g, hipStream_t stream) {
     AggParams p = p0;
     const int64_t rows = p.row_end - p.row_begin;
-    p.n_tiles = (rows + kRowsPerWg - 1) / kRowsPerWg;
+    constexpr int kTileRows = G <= 16 ? rows_per_wg<(G <= 16 ? G : 16)>() : kRowsPerWg;
+    p.n_tiles = (rows + kTileRows - 1) / kTileRows;
     constexpr int64_t kGroup = (int64_t)kXcds * kXcdRun;
     // hub rows inside the range
     const auto& hr = g->h_hub_rows;

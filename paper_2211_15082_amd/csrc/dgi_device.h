@@ -11,12 +11,12 @@ namespace dgi {
 
 __device__ __forceinline__ float bf16_to_float(uint32_t hi16) { return __uint_as_float(hi16 << 16); }
 
-// round to nearest even; NaN stays NaN
+// round to nearest even (v_cvt_pk_bf16_f32 on gfx950); NaN stays NaN
 __device__ __forceinline__ uint16_t float_to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    const __bf16 h = static_cast<__bf16>(f);
+    uint16_t u;
+    __builtin_memcpy(&u, &h, 2);
+    return u;
 }
 
 __device__ __forceinline__ float activate(float x, int act, float slope) {
