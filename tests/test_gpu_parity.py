@@ -412,3 +412,21 @@ def test_jumping_knowledge_stack(last):
     assert st["gather_width"][-1] in (cat, 24)
     with pytest.raises(bd.DgiError):   # the last layer must read the whole concatenation
         bd.infer(g, list(structs[:3]), torch.from_numpy(X).cuda(), torch.empty(n, 64, device="cuda"), jk_concat=True)
+
+
+@pytest.mark.parametrize("storage,dims", [("f32", (64, 96)), ("f32", (128, 47)), ("bf16", (128, 128)), ("bf16", (128, 172)), ("bf16", (64, 16))])
+def test_split_and_transform_first_paths_with_many_rows(storage, dims):
+    # several hundred GEMM tiles and aggregation workgroups per launch; both orders
+    n = 9000
+    d_in, d_out = dims
+    indptr, indices = random_csr(n, 4.0, seed=d_in * 7 + d_out)
+    X = rnd((n, d_in), 1)
+    Ws, Wn = rnd((d_in, d_out), 2, 0.15), rnd((d_in, d_out), 3, 0.15)
+    if storage == "bf16":
+        X, Ws, Wn = [torch.from_numpy(a).to(torch.bfloat16).float().numpy() for a in (X, Ws, Wn)]
+    g = B().graph_load(indptr, indices)
+    for order in ("agg_first_split", "transform_first"):
+        layer = dict(agg="mean", act="relu", W_self=Ws, W_neigh=Wn, bias=rnd((d_out,), 4), order=order)
+        got = gpu_layer(g, layer, X, storage=storage)
+        want = oracle.layer_forward(indptr, indices, layer, X)
+        assert max_rel_err(got, want) <= (TOL_BF16 if storage == "bf16" else TOL_F32), (order,)
