@@ -11,6 +11,7 @@
 // in flight while the current one is multiplied).  LDS rows are padded by 16 bytes so that the 16-byte
 // fragment reads of 8 consecutive lanes cover all banks.
 #include <algorithm>
+#include <cstdlib>
 
 #include "dgi_device.h"
 #include "dgi_internal.h"
@@ -27,7 +28,7 @@ struct GemmParams {
     const void* Wt; int64_t ldw; int K1p;
     const float* bias;
     int act; float act_slope;
-    void* Y; int64_t ld_y; int out_bf16;
+    void* Y; int64_t ld_y; int out_bf16; int y_vec;
     int64_t M; int Nout;
     int tiles_n;
     const float* out_scale; int64_t row0;
@@ -47,16 +48,24 @@ __device__ __forceinline__ uint4 load_chunk(const T* base, int64_t ld, int64_t r
     return *reinterpret_cast<uint4*>(tmp);
 }
 
+// The register budget is pinned to the occupancy the accumulators allow (16 registers per 32x32 block):
+// the kernel hides memory latency with resident workgroups, and measured slower whenever one was lost.
 template <typename T, int WGM, int WGN, int TM, int TN>
-__global__ __launch_bounds__(256) void gemm_kernel(GemmParams p) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(TM * TN >= 6 ? 2 : TM * TN >= 4 ? 3 : 4)))
+void gemm_kernel(GemmParams p) {
     constexpr int E = 16 / sizeof(T);      // elements per 16-byte chunk
     constexpr int BK = 8 * E;              // 128 bytes of K per step
     constexpr int LDS_LD = BK + E;         // padded row, in elements
     constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
     constexpr int A_CHUNKS = BM * 8 / 256, B_CHUNKS = BN * 8 / 256;
     static_assert(WGM * WGN == 4, "4 wavefronts per workgroup");
-    __shared__ __attribute__((aligned(16))) T As[BM * LDS_LD];
-    __shared__ __attribute__((aligned(16))) T Bs[BN * LDS_LD];
+    // the epilogue stages each wavefront's 32-row strip (TN*32 columns, up to 4 bytes each, rows padded by
+    // 16 bytes) in the same memory once the last slab has been multiplied
+    constexpr int MAIN_BYTES = (BM + BN) * LDS_LD * (int)sizeof(T);
+    constexpr int EPI_BYTES = 4 * 32 * (TN * 32 * 4 + 16);
+    __shared__ __attribute__((aligned(16))) unsigned char smem[MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES];
+    T* As = reinterpret_cast<T*>(smem);
+    T* Bs = As + BM * LDS_LD;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
@@ -162,6 +171,60 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmParams p) {
     }
 
     // epilogue: lane holds column (lane % 32) of rows 8*(r/4) + 4*(lane/32) + r%4 of each 32x32 block
+    auto value = [&](int i, int j, int r, int64_t m, float b) {
+        float v = activate(acc[i][j][r] + b, p.act, p.act_slope);
+        if (p.out_scale && m < p.M) v *= p.out_scale[p.row0 + m];
+        return v;
+    };
+    if (p.y_vec) {
+        // transpose through LDS so that every lane stores 16 contiguous bytes of an output row: one store
+        // instruction per 1 KB instead of one per 128 (bf16) or 256 (fp32) bytes
+        auto staged = [&](auto tag) {
+            using O = decltype(tag);
+            constexpr int OB = (int)sizeof(O), EPC = 16 / OB;
+            constexpr int RS = TN * 32 * OB + 16;   // staged row stride in bytes
+            constexpr int CPR = TN * 32 * OB / 16;  // 16-byte chunks per staged row
+            unsigned char* stage = smem + wave * 32 * RS;
+            unsigned char* Yb = static_cast<unsigned char*>(p.Y);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int64_t mb = m0 + (wm * TM + i) * 32;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const int n = n0 + (wn * TN + j) * 32 + lrow;
+                    const float b = (p.bias && n < p.Nout) ? p.bias[n] : 0.f;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int row = 8 * (r / 4) + 4 * lhalf + (r % 4);
+                        const float v = value(i, j, r, mb + row, b);
+                        O* dst = reinterpret_cast<O*>(stage + row * RS) + j * 32 + lrow;
+                        if constexpr (OB == 2) *dst = float_to_bf16(v);
+                        else *dst = v;
+                    }
+                }
+                __syncthreads();
+#pragma unroll 2
+                for (int c = lane; c < 32 * CPR; c += 64) {
+                    const int row = c / CPR, cc = c % CPR;
+                    const int64_t m = mb + row;
+                    const int n = n0 + wn * TN * 32 + cc * EPC;
+                    if (m < p.M && n < p.Nout) {
+                        const unsigned char* src = stage + row * RS + cc * 16;
+                        unsigned char* y = Yb + (m * p.ld_y + n) * OB;
+                        if (n + EPC <= p.Nout) {
+                            *reinterpret_cast<uint4*>(y) = *reinterpret_cast<const uint4*>(src);
+                        } else {
+                            for (int t = 0; t < p.Nout - n; ++t) reinterpret_cast<O*>(y)[t] = reinterpret_cast<const O*>(src)[t];
+                        }
+                    }
+                }
+                if (i + 1 < TM) __syncthreads();
+            }
+        };
+        if (p.out_bf16) staged(uint16_t{});
+        else staged(float{});
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -173,8 +236,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmParams p) {
             for (int r = 0; r < 16; ++r) {
                 const int64_t m = m0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * lhalf + (r % 4);
                 if (m >= p.M) continue;
-                float v = activate(acc[i][j][r] + b, p.act, p.act_slope);
-                if (p.out_scale) v *= p.out_scale[p.row0 + m];
+                const float v = value(i, j, r, m, b);
                 if (p.out_bf16) static_cast<uint16_t*>(p.Y)[m * p.ld_y + n] = float_to_bf16(v);
                 else static_cast<float*>(p.Y)[m * p.ld_y + n] = v;
             }
@@ -263,6 +325,11 @@ dgi_status_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
     p.bias = a.bias; p.act = a.act; p.act_slope = a.act_slope;
     p.Y = a.Y; p.ld_y = a.ld_y; p.out_bf16 = a.out_dtype == DGI_BF16;
     p.M = a.M; p.Nout = a.Nout;
+    {
+        const int ob = p.out_bf16 ? 2 : 4;
+        static const bool scalar_only = [] { const char* e = getenv("DGI_TUNE_GEMM_EPI"); return e && atoi(e) == 0; }();
+        p.y_vec = !scalar_only && ((uintptr_t)a.Y % 16 == 0) && ((a.ld_y * ob) % 16 == 0);
+    }
     p.out_scale = a.out_scale; p.row0 = a.row0;
     // 128-wide column tiles: a 256-wide tile would read A once but leaves one wavefront per SIMD and measured slower
     if (a.dtype == DGI_BF16) {
