@@ -13,6 +13,7 @@
 // chunks, one wavefront each (hub kernel), writing fp32 partial rows; a reduce kernel adds the partials
 // of a row in chunk order and applies the epilogue.  No floating-point atomics anywhere.
 #include <algorithm>
+#include <cstdlib>
 
 #include "dgi_device.h"
 #include "dgi_internal.h"
@@ -86,6 +87,7 @@ struct FusedParams {
     const float* hub_agg;  // aggregated and scaled hub rows of the range, in hub order, fp32 [n_hubs x hub_ld]
     int64_t hub_ld;
     int lds_ld;            // elements per row of the LDS tile
+    int self_lds;          // 0: self rows from global memory; 1: in the tile, 4 wavefronts; 2: in the tile, 8 wavefronts
 };
 
 template <typename T> struct Row;
@@ -495,21 +497,24 @@ __device__ __forceinline__ uint4 pack_row_chunk(const float* f) {  // VEC floats
                       (uint32_t)float_to_bf16(f[6 % Row<T>::VEC]) | ((uint32_t)float_to_bf16(f[7 % Row<T>::VEC]) << 16));
 }
 
-// Aggregation fused with the layer's dense transform (aggregate-first layers).  A workgroup owns 32
-// destination rows.  Phase 1: its four wavefronts gather and aggregate 8 rows each exactly as the
+// Aggregation fused with the layer's dense transform (aggregate-first layers).  A workgroup of W wavefronts
+// owns 32 destination rows.  Phase 1: the wavefronts gather and aggregate 32/W rows each exactly as the
 // stand-alone kernel does, but deposit the scaled result in an LDS tile (32 x K).  Phase 2: the tile is the
-// A operand of MFMA, the rows' own features (GraphSAGE) are a second A block read straight from global
-// memory, B comes from the packed weight through L2, each wavefront owns every fourth 32-column block;
-// bias, activation and the output conversion happen in registers.  The aggregated matrix never exists
-// in HBM.  Hub rows arrive pre-aggregated (fp32) from the two-stage hub pass that runs before this launch.
-template <typename T, typename IdxT, int G, int MODE>
-__global__ __launch_bounds__(kWaves * 64) void fused_layer_kernel(FusedParams fp) {
+// A operand of MFMA, B comes from the packed weight through L2, each wavefront owns every W-th 32-column
+// block; bias, activation and the output conversion happen in registers.  The aggregated matrix never
+// exists in HBM.  Hub rows arrive pre-aggregated (fp32) from the two-stage hub pass that runs before this
+// launch.  The rows' own features (GraphSAGE) are a second A block: with SL they are copied into the tile
+// (LDS row = [h_v | m_v]) by coalesced loads before the gather starts, so phase 2 reads both blocks from
+// LDS; without SL they are read from global memory straight into fragment layout (smaller tile, but every
+// column block re-reads them with 32 cache lines per load instruction).
+template <typename T, typename IdxT, int G, int MODE, int W, bool SL>
+__global__ __launch_bounds__(W * 64) void fused_layer_kernel(FusedParams fp) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     T* tile = reinterpret_cast<T*>(lds_raw);
     const AggParams& p = fp.a;
     constexpr int VEC = Row<T>::VEC;  // elements per 16 bytes
     constexpr int UNROLL = (G == 64) ? DGI_UNROLL_WIDE : 4;
-    constexpr int RPW = kFusedRows / kWaves;
+    constexpr int RPW = kFusedRows / W;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t tile_id = xcd_tile(blockIdx.x);
     if (tile_id >= p.n_tiles) return;  // whole workgroup leaves together
@@ -520,8 +525,21 @@ __global__ __launch_bounds__(kWaves * 64) void fused_layer_kernel(FusedParams fp
     const int K = p.width;
     const int Kp = (K + 2 * VEC - 1) / (2 * VEC) * (2 * VEC);
     const int chunks = Kp / VEC;
+    const int acol = SL ? Kp : 0;  // column of the aggregated block inside an LDS row
 
-    // ---- phase 1: aggregate 8 rows per wavefront into the tile ----------------------------------------
+    if (SL) {  // the rows' own features: [0, Kp) of every LDS row, zero past K and past the row range
+#pragma unroll
+        for (int r = 0; r < RPW; ++r) {
+            const int64_t v = vw + r;
+            T* trow = tile + (wave * RPW + r) * fp.lds_ld;
+            const T* srow = static_cast<const T*>(p.S) + (v < p.row_end ? v : p.row_begin) * p.ld_s;
+            for (int ch = lane; ch < chunks; ch += 64)
+                *reinterpret_cast<uint4*>(trow + ch * VEC) =
+                    (v < p.row_end && ch * VEC < K) ? *reinterpret_cast<const uint4*>(srow + ch * VEC) : make_uint4(0u, 0u, 0u, 0u);
+        }
+    }
+
+    // ---- phase 1: aggregate 32/W rows per wavefront into the tile -------------------------------------
     IdxT ipv = 0;
     if (lane <= RPW) {
         const int64_t i = vw + lane;
@@ -534,7 +552,7 @@ __global__ __launch_bounds__(kWaves * 64) void fused_layer_kernel(FusedParams fp
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
         const int64_t v = vw + r;
-        T* trow = tile + (wave * RPW + r) * fp.lds_ld;
+        T* trow = tile + (wave * RPW + r) * fp.lds_ld + acol;
         const IdxT eb = bound[r], ee = bound[r + 1];
         const IdxT deg = ee - eb;
         const int cur = nxt;
@@ -577,10 +595,10 @@ __global__ __launch_bounds__(kWaves * 64) void fused_layer_kernel(FusedParams fp
     __syncthreads();
 
     // ---- phase 2: out[32 x N] = act([h_v | tile] . Wt^T + bias) on the matrix cores ------------------------
-    // A operand: the aggregated block comes from the LDS tile; the rows' own features (GraphSAGE) are read from
-    // global memory straight into MFMA fragment layout (lane = row, 16 bytes of K), which keeps the tile small.
-    // B operand: the packed weight through L2.  A wavefront owns column blocks wave, wave+4, ... one at a time
-    // (two per sweep would halve the A reads but costs registers, i.e. gather occupancy: measured slower).
+    // A operand in MFMA fragment layout (lane = row, 16 bytes of K) from the LDS tile (and from global memory
+    // for the rows' own features without SL).  B operand: the packed weight through L2.  A wavefront owns
+    // column blocks wave, wave+W, ... one at a time (two per sweep would halve the A reads but costs
+    // registers, i.e. gather occupancy: measured slower).
     const int lrow = lane & 31, lhalf = lane >> 5;
     const int nblk = (fp.N + 31) / 32;
     const int ksteps = Kp / (2 * VEC);
@@ -601,14 +619,14 @@ __global__ __launch_bounds__(kWaves * 64) void fused_layer_kernel(FusedParams fp
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc, 0, 0, 0);
         }
     };
-    for (int cb = wave; cb < nblk; cb += kWaves) {
+    for (int cb = wave; cb < nblk; cb += W) {
         const int n = cb * 32 + lrow;
         const T* w = static_cast<const T*>(fp.Wt) + (int64_t)(n < fp.N ? n : fp.N - 1) * fp.ldw + lhalf * VEC;
         floatx16_t acc;
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[i] = 0.f;
         constexpr int U = 4;
-        if (fp.has_self) {  // K block of the rows' own features: columns [0, Kp) of the packed weight
+        if (!SL && fp.has_self) {  // K block of the rows' own features: columns [0, Kp) of the packed weight
             for (int ks = 0; ks < ksteps; ks += U) {
                 uint4 a[U], b[U];
 #pragma unroll
@@ -622,13 +640,17 @@ __global__ __launch_bounds__(kWaves * 64) void fused_layer_kernel(FusedParams fp
                 for (int u = 0; u < U; ++u) mma(acc, a[u], b[u]);
             }
         }
-        for (int ks = 0; ks < ksteps; ks += U) {  // K block of the aggregated neighbourhood: columns [K1p, K1p + Kp)
+        // K block of the aggregated neighbourhood: columns [K1p, K1p + Kp) of the packed weight; with SL one
+        // loop over the whole LDS row [h_v | m_v] against columns [0, 2 Kp) (the host checks K1p == Kp)
+        const int lsteps = SL ? 2 * ksteps : ksteps;
+        const int wcol = SL ? 0 : fp.K1p;
+        for (int ks = 0; ks < lsteps; ks += U) {
             uint4 a[U], b[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int k = (ks + u) * 2 * VEC;
-                const bool in = ks + u < ksteps;
-                b[u] = in ? *reinterpret_cast<const uint4*>(w + fp.K1p + k) : make_uint4(0u, 0u, 0u, 0u);
+                const bool in = ks + u < lsteps;
+                b[u] = in ? *reinterpret_cast<const uint4*>(w + wcol + k) : make_uint4(0u, 0u, 0u, 0u);
                 a[u] = in ? *reinterpret_cast<const uint4*>(a_lds + k) : make_uint4(0u, 0u, 0u, 0u);
             }
 #pragma unroll
@@ -769,7 +791,7 @@ dgi_status_t dispatch_mode(const AggParams& p, const dgi_graph* g, int mode, boo
 }
 
 // ---- fused path: hub pre-pass (chunks + compact reduce into hub_agg), then the fused layer kernel -------
-template <typename T, typename IdxT, int G, int MODE>
+template <typename T, typename IdxT, int G, int MODE, int W, bool SL>
 dgi_status_t launch_fused_g(FusedParams fp, const dgi_graph* g, float* partials, float* hub_agg, int stage, hipStream_t stream) {
     AggParams& p = fp.a;
     constexpr int64_t kGroup = (int64_t)kXcds * kXcdRun;
@@ -805,12 +827,12 @@ dgi_status_t launch_fused_g(FusedParams fp, const dgi_graph* g, float* partials,
     const int64_t rows = p.row_end - p.row_begin;
     p.n_tiles = (rows + kFusedRows - 1) / kFusedRows;
     const int64_t grid = round_up(p.n_tiles, kGroup);
-    DGI_REQUIRE(grid * kWaves * 64 < (int64_t)1 << 32, DGI_ERR_INVALID_ARG, "fused: row range too large for one launch");
+    DGI_REQUIRE(grid * W * 64 < (int64_t)1 << 32, DGI_ERR_INVALID_ARG, "fused: row range too large for one launch");
     const size_t lds = (size_t)kFusedRows * fp.lds_ld * sizeof(T);
-    auto kernel = fused_layer_kernel<T, IdxT, G, MODE>;
+    auto kernel = fused_layer_kernel<T, IdxT, G, MODE, W, SL>;
     if (lds > 48 * 1024)
         DGI_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kWaves * 64), lds, stream, fp);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(W * 64), lds, stream, fp);
     DGI_HIP(hipGetLastError());
     return DGI_OK;
 }
@@ -818,9 +840,22 @@ dgi_status_t launch_fused_g(FusedParams fp, const dgi_graph* g, float* partials,
 template <typename T, typename IdxT, int MODE>
 dgi_status_t launch_fused_mode(const FusedParams& fp, const dgi_graph* g, float* partials, float* hub_agg, int stage, hipStream_t stream) {
     const int lanes = (fp.a.width + Row<T>::VEC - 1) / Row<T>::VEC;
-    if (lanes <= 16) return launch_fused_g<T, IdxT, 16, MODE>(fp, g, partials, hub_agg, stage, stream);
-    if (lanes <= 32) return launch_fused_g<T, IdxT, 32, MODE>(fp, g, partials, hub_agg, stage, stream);
-    return launch_fused_g<T, IdxT, 64, MODE>(fp, g, partials, hub_agg, stage, stream);
+    // self rows exist only with the GraphSAGE aggregations
+    if constexpr (MODE == MODE_SUM || MODE == MODE_MEAN) {
+        if (fp.self_lds == 2) {
+            if (lanes <= 16) return launch_fused_g<T, IdxT, 16, MODE, 8, true>(fp, g, partials, hub_agg, stage, stream);
+            if (lanes <= 32) return launch_fused_g<T, IdxT, 32, MODE, 8, true>(fp, g, partials, hub_agg, stage, stream);
+            return launch_fused_g<T, IdxT, 64, MODE, 8, true>(fp, g, partials, hub_agg, stage, stream);
+        }
+        if (fp.self_lds == 1) {
+            if (lanes <= 16) return launch_fused_g<T, IdxT, 16, MODE, 4, true>(fp, g, partials, hub_agg, stage, stream);
+            if (lanes <= 32) return launch_fused_g<T, IdxT, 32, MODE, 4, true>(fp, g, partials, hub_agg, stage, stream);
+            return launch_fused_g<T, IdxT, 64, MODE, 4, true>(fp, g, partials, hub_agg, stage, stream);
+        }
+    }
+    if (lanes <= 16) return launch_fused_g<T, IdxT, 16, MODE, 4, false>(fp, g, partials, hub_agg, stage, stream);
+    if (lanes <= 32) return launch_fused_g<T, IdxT, 32, MODE, 4, false>(fp, g, partials, hub_agg, stage, stream);
+    return launch_fused_g<T, IdxT, 64, MODE, 4, false>(fp, g, partials, hub_agg, stage, stream);
 }
 
 template <typename T, typename IdxT>
@@ -873,6 +908,20 @@ dgi_status_t launch_fused(const FusedArgs& a, int stage, hipStream_t stream) {
     fp.bias = a.bias; fp.act = a.act; fp.act_slope = a.act_slope; fp.out_scale = a.out_scale;
     fp.out = a.out; fp.ld_out = a.ld_out; fp.out_row0 = a.out_row0; fp.out_bf16 = a.out_dtype == DGI_BF16;
     fp.lds_ld = (int)(round_up(a.K, 2 * E) + E);
+    {
+        // Variant 2 (self rows in the tile, 8 wavefronts) when every wavefront gets a column block: phase 2 then
+        // reads nothing but the weight from outside the workgroup and takes half as long per tile (measured on
+        // 256 -> 256 fp32 GraphSAGE: 125 -> 112 ms per layer).  With 4 wavefronts the larger tile costs as much
+        // gather occupancy as the LDS reads save, and narrow outputs would leave wavefronts idle in phase 2.
+        const int Kp = (int)round_up(a.K, 2 * E);
+        static const int forced = [] { const char* e = getenv("DGI_TUNE_FUSED_SELF"); return e ? atoi(e) : -1; }();
+        const bool can = a.has_self && a.K1p == Kp && (a.mode == MODE_SUM || a.mode == MODE_MEAN) &&
+                         (size_t)kFusedRows * (size_t)(2 * Kp + E) * eb <= 80 * 1024;
+        int variant = 0;
+        if (can) variant = forced >= 0 ? forced : ((a.N + 31) / 32 >= 8 ? 2 : 0);
+        fp.self_lds = variant;
+        if (variant) fp.lds_ld = 2 * Kp + E;
+    }
     float* partials = static_cast<float*>(a.temp);
     float* hub_agg = a.temp ? reinterpret_cast<float*>(static_cast<char*>(a.temp) + round_up((int64_t)agg_hub_partial_bytes(g, a.row_begin, a.row_end, a.K), 256)) : nullptr;
     const bool i64 = g->itype == DGI_I64;

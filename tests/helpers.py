@@ -2,10 +2,13 @@
 import numpy as np
 
 
-def random_csr(n, avg_deg, seed, empty_frac=0.2, duplicates=True):
+def random_csr(n, avg_deg, seed, empty_frac=0.2, duplicates=True, hub=None):
+    """Poisson in-degrees, uniform sources; hub=(row, degree) plants one high-degree destination."""
     rng = np.random.default_rng(seed)
     deg = rng.poisson(avg_deg, n)
     deg[rng.random(n) < empty_frac] = 0
+    if hub is not None:
+        deg[hub[0]] = hub[1]
     indptr = np.zeros(n + 1, dtype=np.int64)
     np.cumsum(deg, out=indptr[1:])
     indices = rng.integers(0, n, indptr[-1]).astype(np.int32)

@@ -430,3 +430,25 @@ def test_split_and_transform_first_paths_with_many_rows(storage, dims):
         got = gpu_layer(g, layer, X, storage=storage)
         want = oracle.layer_forward(indptr, indices, layer, X)
         assert max_rel_err(got, want) <= (TOL_BF16 if storage == "bf16" else TOL_F32), (order,)
+
+
+@pytest.mark.parametrize("storage,dims", [("f32", (256, 256)), ("f32", (72, 300)), ("bf16", (256, 320)), ("bf16", (128, 256))])
+@pytest.mark.parametrize("agg", ["sum", "mean"])
+def test_fused_layer_with_eight_or_more_column_blocks(storage, dims, agg):
+    # 256 or more output columns: the fused kernel runs its 8-wavefront form with the rows' own features in the
+    # LDS tile; a 3000-edge hub row goes through the pre-pass, the last tile is ragged
+    n = 1500
+    d_in, d_out = dims
+    # (no hub under bf16 + sum: the aggregated vector is rounded to bf16 before the transform, and a sum of 3000
+    # unit-variance rows rounds by more than the RMS-floored tolerance allows on outputs that nearly cancel)
+    hub = None if (storage == "bf16" and agg == "sum") else (11, 3000)
+    indptr, indices = random_csr(n, 6.0, seed=d_in + 3 * d_out, hub=hub)
+    X = rnd((n, d_in), 1)
+    Ws, Wn = rnd((d_in, d_out), 2, 0.1), rnd((d_in, d_out), 3, 0.1)
+    if storage == "bf16":
+        X, Ws, Wn = [torch.from_numpy(a).to(torch.bfloat16).float().numpy() for a in (X, Ws, Wn)]
+    layer = dict(agg=agg, act="relu", W_self=Ws, W_neigh=Wn, bias=rnd((d_out,), 4), order="agg_first_fused")
+    g = B().graph_load(indptr, indices)
+    got = gpu_layer(g, layer, X, storage=storage)
+    want = oracle.layer_forward(indptr, indices, layer, X)
+    assert max_rel_err(got, want) <= (TOL_BF16 if storage == "bf16" else TOL_F32)
