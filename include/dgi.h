@@ -227,6 +227,41 @@ dgi_status_t dgi_infer_partial(const dgi_graph_t* g, const dgi_layer_t* layers, 
                                int64_t ld_x, const int32_t* targets, int64_t num_targets, void* out, int64_t ld_out,
                                const dgi_infer_opts_t* opts, dgi_partial_stats_t* pstats, void* hip_stream);
 
+/* Layer-wise inference with the embeddings outside the GPU (Algorithm 2 as Sections 2 and 4.1 describe it:
+ * the graph structure is on the device, the feature matrices H^0 .. H^L live in host memory, and every batch
+ * loads its input set, computes one layer for its destination rows and dumps them back).
+ *   x_host   : HOST, page-locked (hipHostMalloc / a pinned tensor), [N x layers[0].in_dim], leading dimension ld_x.
+ *   out_host : HOST, page-locked, [N x layers[L-1].out_dim], leading dimension ld_out.
+ * Hidden layers H^1 .. H^{L-1} are kept in page-locked host buffers owned by the call (two, used alternately:
+ * H^{l-1} is released when layer l is done).  Per batch [b, e) of destination rows the device (i) marks and
+ * compacts the input set I = [b, e) + the sources of the batch's edges, (ii) reads the rows H^{l-1}[I] straight
+ * from host memory into a compact device matrix, (iii) relabels the batch's neighbour lists to positions in I
+ * and runs the layer (dgi_layer_forward's kernels) on that sub-problem, (iv) copies the rows H^l[b:e] to host.
+ * Batch sizes follow Section 4.1 with real memory at stake: the batch's device memory M_k (input rows,
+ * relabelled lists, output rows, layer workspace) is measured, the thresholds are rescaled by r = M / M_k
+ * (Eq. 2), and a batch that does not fit the budget M = opts->mem_budget_bytes (0 = 90 % of free device
+ * memory) halves the thresholds and is planned again.  opts->batch_size > 0 fixes the rows per batch instead;
+ * opts->perm_new_of_old and opts->jk_concat are not supported here, opts->stats is ignored.
+ * Waits for completion.  hstats (HOST, may be NULL) reports what was moved. */
+typedef struct {
+    int32_t num_layers;
+    int32_t reserved;
+    double  total_ms;                        /* wall-clock of the call */
+    double  load_ms[DGI_MAX_LAYERS];         /* input-set construction + rows read from host memory */
+    double  compute_ms[DGI_MAX_LAYERS];      /* the layer's kernels */
+    double  store_ms[DGI_MAX_LAYERS];        /* rows copied back to host memory */
+    int64_t batches[DGI_MAX_LAYERS];
+    int64_t input_rows[DGI_MAX_LAYERS];      /* sum over batches of |I| (what node reordering shrinks, Section 4.2) */
+    int64_t input_bytes[DGI_MAX_LAYERS];     /* bytes read from host memory */
+    int64_t output_bytes[DGI_MAX_LAYERS];    /* bytes written to host memory */
+    int64_t oom_retries;                     /* batches planned again after halving the thresholds */
+    int64_t peak_batch_bytes;                /* largest M_k */
+    int64_t budget_bytes;                    /* M */
+} dgi_host_stats_t;
+dgi_status_t dgi_infer_host(const dgi_graph_t* g, const dgi_layer_t* layers, int32_t num_layers, const void* x_host,
+                            int64_t ld_x, void* out_host, int64_t ld_out, const dgi_infer_opts_t* opts,
+                            dgi_host_stats_t* hstats, void* hip_stream);
+
 /* ------------------------------------------------------------------------------------------------
  * Host-side planning helpers (no device access; usable without a GPU).
  *

@@ -70,6 +70,16 @@ class PartialStatsStruct(ctypes.Structure):
     ]
 
 
+class HostStatsStruct(ctypes.Structure):
+    _fields_ = [
+        ("num_layers", ctypes.c_int32), ("reserved", ctypes.c_int32), ("total_ms", ctypes.c_double),
+        ("load_ms", ctypes.c_double * MAX_LAYERS), ("compute_ms", ctypes.c_double * MAX_LAYERS), ("store_ms", ctypes.c_double * MAX_LAYERS),
+        ("batches", ctypes.c_int64 * MAX_LAYERS), ("input_rows", ctypes.c_int64 * MAX_LAYERS), ("input_bytes", ctypes.c_int64 * MAX_LAYERS),
+        ("output_bytes", ctypes.c_int64 * MAX_LAYERS), ("oom_retries", ctypes.c_int64), ("peak_batch_bytes", ctypes.c_int64),
+        ("budget_bytes", ctypes.c_int64),
+    ]
+
+
 class GraphInfoStruct(ctypes.Structure):
     _fields_ = [
         ("num_nodes", ctypes.c_int64), ("num_edges", ctypes.c_int64), ("max_in_degree", ctypes.c_int64),
@@ -80,7 +90,7 @@ class GraphInfoStruct(ctypes.Structure):
 
 EXPORTS = [
     "dgi_graph_load", "dgi_graph_free", "dgi_graph_release_workspace", "dgi_graph_info", "dgi_graph_vector", "dgi_graph_csr", "dgi_graph_reorder",
-    "dgi_layer_forward", "dgi_layer_workspace_bytes", "dgi_infer", "dgi_infer_partial", "dgi_plan_batch_end", "dgi_threshold_update",
+    "dgi_layer_forward", "dgi_layer_workspace_bytes", "dgi_infer", "dgi_infer_partial", "dgi_infer_host", "dgi_plan_batch_end", "dgi_threshold_update",
     "dgi_threshold_halve", "dgi_batch_input_set_size", "dgi_reorder_permutation", "dgi_status_string",
     "dgi_last_error", "dgi_version",
 ]
@@ -295,6 +305,24 @@ def infer_partial(graph, layer_structs, x, targets, out, batch_size=0, mem_budge
     n = ps.num_layers
     return {"set_size": list(ps.set_size)[:n + 1], "all_nodes_from_layer": ps.all_nodes_from_layer,
             "sub_nodes": ps.sub_nodes, "sub_edges": ps.sub_edges}
+
+
+def infer_host(graph, layer_structs, x_host, out_host, batch_size=0, mem_budget_bytes=0, init_node_threshold=0,
+               init_edge_threshold=0):
+    """x_host / out_host: pinned CPU tensors (torch `pin_memory=True`; the library refuses anything else).
+    Returns the transfer statistics."""
+    arr = (LayerStruct * len(layer_structs))(*layer_structs)
+    opts = OptsStruct()
+    opts.batch_size = int(batch_size)
+    opts.mem_budget_bytes = int(mem_budget_bytes)
+    opts.init_node_threshold = int(init_node_threshold)
+    opts.init_edge_threshold = int(init_edge_threshold)
+    hs = HostStatsStruct()
+    _check(_lib.dgi_infer_host(graph.handle, arr, ctypes.c_int32(len(layer_structs)), _dptr(x_host), ctypes.c_int64(x_host.stride(0)),
+                               _dptr(out_host), ctypes.c_int64(out_host.stride(0)), ctypes.byref(opts), ctypes.byref(hs), _stream()))
+    n = hs.num_layers
+    return {k: (list(getattr(hs, k))[:n] if hasattr(getattr(hs, k), "__len__") else getattr(hs, k))
+            for k, _ in HostStatsStruct._fields_ if k != "reserved"}
 
 
 # ---- host-side planning helpers (no device access) ------------------------------------------------------

@@ -7,23 +7,16 @@
 // lists) and the inputs V^0 are extracted into a compact sub-problem, relabelled, and the ordinary
 // layer-wise schedule (dgi_infer) runs on it: rows outside V^l at layer l are computed too, but they have
 // empty lists below V^1 and nobody reads them.  Degrees in the GCN normaliser stay those of the full graph.
-#include <hipcub/hipcub.hpp>
-
 #include <algorithm>
 #include <climits>
 #include <cstring>
 
-#include "dgi_internal.h"
+#include "dgi_subproblem.h"
 
 namespace dgi {
 namespace {
 
-constexpr int kBlock = 256;
-inline unsigned grid_for(int64_t n) { return (unsigned)std::max<int64_t>(1, std::min<int64_t>((n + kBlock - 1) / kBlock, (int64_t)1 << 22)); }
-
-__global__ void fill_depth_kernel(int32_t* depth, int64_t N, int32_t value) {
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N; i += (int64_t)gridDim.x * blockDim.x) depth[i] = value;
-}
+using namespace subp;
 
 __global__ void mark_targets_kernel(const int32_t* targets, int64_t n, int64_t N, int32_t L, int32_t* depth, int* bad) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
@@ -45,55 +38,9 @@ __global__ void expand_depth_kernel(const IdxT* indptr, const int32_t* indices, 
     }
 }
 
-__global__ void level_flags_kernel(const int32_t* depth, int64_t N, int32_t l, int32_t* flag) {
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N; i += (int64_t)gridDim.x * blockDim.x)
-        flag[i] = depth[i] >= l ? 1 : 0;
-}
-
-// per kept node (local id i, global id U[i]): kept in-degree (complete list for depth >= 1, empty otherwise),
-// and the full graph's normalisers
-template <typename IdxT>
-__global__ void sub_rows_kernel(const int32_t* U, int64_t n_sub, const IdxT* indptr, const int32_t* depth, int64_t* sub_deg) {
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_sub; i += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t v = U[i];
-        sub_deg[i] = depth[v] >= 1 ? (int64_t)(indptr[v + 1] - indptr[v]) : 0;
-    }
-}
-
-template <typename IdxT>
-__global__ void sub_indices_kernel(const int32_t* U, int64_t n_sub, const IdxT* indptr, const int32_t* indices,
-                                   const int64_t* sub_indptr, const int32_t* loc, int32_t* sub_indices) {
-    const int lane = threadIdx.x & 63;
-    const int64_t waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
-    for (int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; i < n_sub; i += waves) {
-        const int64_t a = sub_indptr[i], d = sub_indptr[i + 1] - a;
-        const int64_t src = (int64_t)indptr[U[i]];
-        for (int64_t j = lane; j < d; j += 64) sub_indices[a + j] = loc[indices[src + j]];
-    }
-}
-
-__global__ void gather_f32_kernel(const float* in, const int32_t* idx, int64_t n, float* out) {
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) out[i] = in[idx[i]];
-}
-
 __global__ void local_targets_kernel(const int32_t* targets, int64_t n, const int32_t* loc, int32_t* out) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) out[i] = loc[targets[i]];
 }
-
-struct Buf {
-    void* p = nullptr;
-    ~Buf() { (void)hipFree(p); }
-    dgi_status_t alloc(size_t bytes) { DGI_HIP(hipMalloc(&p, std::max<size_t>(bytes, 16))); return DGI_OK; }
-    template <typename T> T* as() { return static_cast<T*>(p); }
-};
-
-#define DGI_CUB(call)                                                                                              \
-    do {                                                                                                           \
-        hipError_t _e = (call);                                                                                    \
-        if (_e != hipSuccess) { set_error("%s failed: %s", #call, hipGetErrorString(_e)); return DGI_ERR_DEVICE; } \
-    } while (0)
-
-struct GraphGuard { dgi_graph_t* g = nullptr; ~GraphGuard() { dgi_graph_free(g); } };
 
 template <typename IdxT>
 dgi_status_t infer_partial(const dgi_graph* g, const dgi_layer_t* layers, int32_t L, const void* x, int64_t ld_x,
@@ -104,32 +51,17 @@ dgi_status_t infer_partial(const dgi_graph* g, const dgi_layer_t* layers, int32_
     const int xb = layers[0].feat_dtype == DGI_BF16 ? 2 : 4, yb = layers[L - 1].out_dtype == DGI_BF16 ? 2 : 4;
     const int in_dim = layers[0].in_dim, out_dim = layers[L - 1].out_dim;
     const double d_avg = N > 0 ? (double)g->E / (double)N : 0.0;
-    Buf depth, flag, loc, tmp, cnt, bad;
-    DGI_TRY(depth.alloc(N * 4)); DGI_TRY(flag.alloc(N * 4)); DGI_TRY(loc.alloc((N + 1) * 4)); DGI_TRY(cnt.alloc(8)); DGI_TRY(bad.alloc(4));
-    size_t tb = 0, t2 = 0;
-    DGI_CUB(hipcub::DeviceReduce::Sum(nullptr, tb, flag.as<int32_t>(), cnt.as<int32_t>(), (int)N, s));
-    DGI_CUB(hipcub::DeviceScan::ExclusiveSum(nullptr, t2, flag.as<int32_t>(), loc.as<int32_t>(), (int)N, s));
-    tb = std::max(tb, t2);
-    DGI_CUB(hipcub::DeviceSelect::Flagged(nullptr, t2, hipcub::CountingInputIterator<int32_t>(0), flag.as<int32_t>(), (int32_t*)nullptr, cnt.as<int32_t>(), (int)N, s));
-    tb = std::max(tb, t2);
-    DGI_CUB(hipcub::DeviceScan::InclusiveSum(nullptr, t2, (int64_t*)nullptr, (int64_t*)nullptr, (int)N, s));
-    tb = std::max(tb, t2);
-    DGI_TRY(tmp.alloc(tb));
+    Buf depth, bad;
+    Scratch sc;
+    DGI_TRY(depth.alloc(N * 4)); DGI_TRY(bad.alloc(4));
+    DGI_TRY(sc.alloc(N, s));
 
     DGI_TRY(launch_fill_zero(bad.p, 4, s));
-    hipLaunchKernelGGL(fill_depth_kernel, dim3(grid_for(N)), dim3(kBlock), 0, s, depth.as<int32_t>(), N, -1);
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(grid_for(N)), dim3(kBlock), 0, s, depth.as<int32_t>(), N, -1);
     hipLaunchKernelGGL(mark_targets_kernel, dim3(grid_for(nt)), dim3(kBlock), 0, s, targets, nt, N, L, depth.as<int32_t>(), bad.as<int>());
     int h_bad = 0;
     DGI_HIP(hipMemcpyAsync(&h_bad, bad.p, 4, hipMemcpyDeviceToHost, s));
-    auto count_level = [&](int32_t l, int64_t* n_out) -> dgi_status_t {
-        hipLaunchKernelGGL(level_flags_kernel, dim3(grid_for(N)), dim3(kBlock), 0, s, depth.as<int32_t>(), N, l, flag.as<int32_t>());
-        DGI_CUB(hipcub::DeviceReduce::Sum(tmp.p, tb, flag.as<int32_t>(), cnt.as<int32_t>(), (int)N, s));
-        int32_t c = 0;
-        DGI_HIP(hipMemcpyAsync(&c, cnt.p, 4, hipMemcpyDeviceToHost, s));
-        DGI_HIP(hipStreamSynchronize(s));
-        *n_out = c;
-        return DGI_OK;
-    };
+    auto count_level = [&](int32_t l, int64_t* n_out) { return sc.count_level(depth.as<int32_t>(), N, l, n_out, s); };
     int64_t n_l = 0;
     DGI_TRY(count_level(L, &n_l));
     DGI_REQUIRE(h_bad == 0, DGI_ERR_INVALID_ARG, "infer_partial: a target id is outside [0, num_nodes)");
@@ -162,29 +94,17 @@ dgi_status_t infer_partial(const dgi_graph* g, const dgi_layer_t* layers, int32_
     const int64_t n_sub = n_l;  // |V^0|
     Buf U, sub_deg, sub_indptr, sub_indices, x_sub, out_sub, tloc;
     DGI_TRY(U.alloc(n_sub * 4)); DGI_TRY(sub_deg.alloc((n_sub + 1) * 8)); DGI_TRY(sub_indptr.alloc((n_sub + 1) * 8));
-    // flag still holds (depth >= 0) from the last count_level call
-    DGI_CUB(hipcub::DeviceScan::ExclusiveSum(tmp.p, tb, flag.as<int32_t>(), loc.as<int32_t>(), (int)N, s));
-    DGI_CUB(hipcub::DeviceSelect::Flagged(tmp.p, tb, hipcub::CountingInputIterator<int32_t>(0), flag.as<int32_t>(), U.as<int32_t>(), cnt.as<int32_t>(), (int)N, s));
-    hipLaunchKernelGGL(sub_rows_kernel<IdxT>, dim3(grid_for(n_sub)), dim3(kBlock), 0, s, U.as<int32_t>(), n_sub, indptr, depth.as<int32_t>(), sub_deg.as<int64_t>());
-    DGI_TRY(launch_fill_zero(sub_indptr.p, 8, s));
-    DGI_CUB(hipcub::DeviceScan::InclusiveSum(tmp.p, tb, sub_deg.as<int64_t>(), sub_indptr.as<int64_t>() + 1, (int)n_sub, s));
+    // sc.flag still holds (depth >= 0) from the last count_level call
     int64_t e_sub = 0;
-    DGI_HIP(hipMemcpyAsync(&e_sub, sub_indptr.as<int64_t>() + n_sub, 8, hipMemcpyDeviceToHost, s));
-    DGI_HIP(hipStreamSynchronize(s));
+    DGI_TRY(sub_rows<IdxT>(g, depth.as<int32_t>(), sc, n_sub, U.as<int32_t>(), sub_deg.as<int64_t>(), sub_indptr.as<int64_t>(), &e_sub, s));
     DGI_TRY(sub_indices.alloc(e_sub * 4));
-    hipLaunchKernelGGL(sub_indices_kernel<IdxT>, dim3(grid_for(n_sub * 64)), dim3(kBlock), 0, s, U.as<int32_t>(), n_sub, indptr, g->d_indices,
-                       sub_indptr.as<int64_t>(), loc.as<int32_t>(), sub_indices.as<int32_t>());
-    DGI_HIP(hipGetLastError());
     GraphGuard sub;
-    DGI_TRY(dgi_graph_load(n_sub, e_sub, sub_indptr.p, DGI_I64, sub_indices.as<int32_t>(), DGI_DEVICE, s, &sub.g));
-    // the GCN normalisers are those of the full graph
-    hipLaunchKernelGGL(gather_f32_kernel, dim3(grid_for(n_sub)), dim3(kBlock), 0, s, g->d_rs_out, U.as<int32_t>(), n_sub, sub.g->d_rs_out);
-    hipLaunchKernelGGL(gather_f32_kernel, dim3(grid_for(n_sub)), dim3(kBlock), 0, s, g->d_rs_in, U.as<int32_t>(), n_sub, sub.g->d_rs_in);
+    DGI_TRY(sub_graph<IdxT>(g, sc, n_sub, e_sub, U.as<int32_t>(), sub_indptr.as<int64_t>(), sub_indices.as<int32_t>(), &sub, s));
     const int64_t ld_xs = round_up(in_dim, 16 / xb), ld_os = round_up(out_dim, 16 / yb);
     DGI_TRY(x_sub.alloc((size_t)n_sub * ld_xs * xb)); DGI_TRY(out_sub.alloc((size_t)n_sub * ld_os * yb)); DGI_TRY(tloc.alloc(nt * 4));
     DGI_TRY(launch_permute_rows(x, ld_x, x_sub.p, ld_xs, n_sub, in_dim, xb, U.as<int32_t>(), true, s));
     DGI_TRY(dgi_infer(sub.g, layers, L, x_sub.p, ld_xs, out_sub.p, ld_os, &o, s));
-    hipLaunchKernelGGL(local_targets_kernel, dim3(grid_for(nt)), dim3(kBlock), 0, s, targets, nt, loc.as<int32_t>(), tloc.as<int32_t>());
+    hipLaunchKernelGGL(local_targets_kernel, dim3(grid_for(nt)), dim3(kBlock), 0, s, targets, nt, sc.loc.as<int32_t>(), tloc.as<int32_t>());
     DGI_TRY(launch_permute_rows(out_sub.p, ld_os, out, ld_out, nt, out_dim, yb, tloc.as<int32_t>(), true, s));
     DGI_HIP(hipStreamSynchronize(s));
     if (ps) { ps->sub_nodes = n_sub; ps->sub_edges = e_sub; }

@@ -33,6 +33,7 @@ def test_struct_sizes_match_header_layout():
     assert ctypes.sizeof(B.OptsStruct) == 7 * 8
     assert ctypes.sizeof(B.StatsStruct) == 8 + 8 + 16 * (8 * 8 + 4 * 3) + 16
     assert ctypes.sizeof(B.GraphInfoStruct) == 5 * 8 + 8 + 8
+    assert ctypes.sizeof(B.HostStatsStruct) == 8 + 8 + 16 * 8 * 7 + 3 * 8
 
 
 def brute_batch_end(ip, limit, begin, n_t, n_i):
@@ -188,6 +189,7 @@ def test_argument_validation_fails_before_any_device_work():
     assert lib.dgi_infer(None, None, 1, None, 0, None, 0, None, None) == B.ERR_INVALID_ARG
     assert lib.dgi_layer_forward(None, None, None, 0, None, 0, 0, 0, None, 0, None) == B.ERR_INVALID_ARG
     assert lib.dgi_infer_partial(None, None, 1, None, 0, None, 0, None, 0, None, None, None) == B.ERR_INVALID_ARG
+    assert lib.dgi_infer_host(None, None, 1, None, 0, None, 0, None, None, None) == B.ERR_INVALID_ARG
     with pytest.raises(B.DgiError) as ei:
         B.plan_batch_end(np.zeros(4, np.int64), 3, 5, 1, 1)
     assert ei.value.status == B.ERR_INVALID_ARG and "begin" in str(ei.value)
