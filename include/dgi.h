@@ -135,7 +135,8 @@ typedef struct {
                                       last layer reads the concatenation of all their outputs, so layers[L-1].in_dim must
                                       be the sum of the earlier out_dims; every hidden layer is kept until the last
                                       layer has run */
-    int32_t reserved;
+    int32_t host_stream_always;    /* dgi_infer_host only.  1: keep the hidden layers in host memory and stream every
+                                      batch (the paper's regime) even when everything would fit the budget */
 } dgi_infer_opts_t;
 
 typedef struct {
@@ -161,7 +162,7 @@ typedef struct {
 dgi_status_t dgi_graph_load(int64_t num_nodes, int64_t num_edges, const void* indptr, int32_t indptr_type,
                             const int32_t* indices, int32_t where, void* hip_stream, dgi_graph_t** out);
 dgi_status_t dgi_graph_free(dgi_graph_t* g);            /* NULL is a no-op; also frees the cached workspace */
-/* Frees the workspace dgi_infer keeps in the handle between calls (waits for the device first). */
+/* Frees the buffers dgi_infer and dgi_infer_host keep in the handle between calls (waits for the device first). */
 dgi_status_t dgi_graph_release_workspace(dgi_graph_t* g);
 dgi_status_t dgi_graph_info(const dgi_graph_t* g, dgi_graph_info_t* info /*HOST*/);
 
@@ -232,20 +233,26 @@ dgi_status_t dgi_infer_partial(const dgi_graph_t* g, const dgi_layer_t* layers, 
  * loads its input set, computes one layer for its destination rows and dumps them back).
  *   x_host   : HOST, page-locked (hipHostMalloc / a pinned tensor), [N x layers[0].in_dim], leading dimension ld_x.
  *   out_host : HOST, page-locked, [N x layers[L-1].out_dim], leading dimension ld_out.
- * Hidden layers H^1 .. H^{L-1} are kept in page-locked host buffers owned by the call (two, used alternately:
- * H^{l-1} is released when layer l is done).  Per batch [b, e) of destination rows the device (i) marks and
- * compacts the input set I = [b, e) + the sources of the batch's edges, (ii) reads the rows H^{l-1}[I] straight
+ * Hidden layers H^1 .. H^{L-1} are kept in two page-locked host buffers used alternately (H^{l-1}'s buffer is
+ * reused when layer l is done); they and the device memory of the batches stay in the graph handle between
+ * calls (dgi_graph_release_workspace or dgi_graph_free returns them), and calls on one handle are serialised.
+ * Per batch [b, e) of destination rows the device (i) marks and compacts the input set I = [b, e) + the sources of the batch's edges, (ii) reads the rows H^{l-1}[I] straight
  * from host memory into a compact device matrix, (iii) relabels the batch's neighbour lists to positions in I
  * and runs the layer (dgi_layer_forward's kernels) on that sub-problem, (iv) copies the rows H^l[b:e] to host.
- * Batch sizes follow Section 4.1 with real memory at stake: the batch's device memory M_k (input rows,
- * relabelled lists, output rows, layer workspace) is measured, the thresholds are rescaled by r = M / M_k
- * (Eq. 2), and a batch that does not fit the budget M = opts->mem_budget_bytes (0 = 90 % of free device
- * memory) halves the thresholds and is planned again.  opts->batch_size > 0 fixes the rows per batch instead;
+ * Two batches are in flight: while one computes and dumps on a second stream, the next one is built and loaded
+ * (the host link carries both directions at once), so a batch may use M = half of opts->mem_budget_bytes
+ * (0 = 90 % of free device memory).  Batch sizes follow Section 4.1 with real memory at stake: the batch's
+ * device memory M_k (input rows, relabelled lists, output rows, layer workspace) is measured, the thresholds are
+ * rescaled by r = M / M_k (Eq. 2), and a batch that does not fit M halves the thresholds and is planned again.
+ * When the whole graph fits M, every layer is one batch; when x, the output and dgi_infer's own buffers all fit
+ * the budget, the call is one copy in, dgi_infer, one copy out (hstats->device_resident = 1) and the hidden
+ * layers never leave the device (opts->host_stream_always = 1 switches that off).  opts->batch_size > 0 fixes
+ * the rows per batch instead;
  * opts->perm_new_of_old and opts->jk_concat are not supported here, opts->stats is ignored.
  * Waits for completion.  hstats (HOST, may be NULL) reports what was moved. */
 typedef struct {
     int32_t num_layers;
-    int32_t reserved;
+    int32_t device_resident;                 /* 1: everything fitted the budget, the hidden layers never left the device */
     double  total_ms;                        /* wall-clock of the call */
     double  load_ms[DGI_MAX_LAYERS];         /* input-set construction + rows read from host memory */
     double  compute_ms[DGI_MAX_LAYERS];      /* the layer's kernels */
@@ -256,7 +263,7 @@ typedef struct {
     int64_t output_bytes[DGI_MAX_LAYERS];    /* bytes written to host memory */
     int64_t oom_retries;                     /* batches planned again after halving the thresholds */
     int64_t peak_batch_bytes;                /* largest M_k */
-    int64_t budget_bytes;                    /* M */
+    int64_t budget_bytes;                    /* M, the memory one batch may use */
 } dgi_host_stats_t;
 dgi_status_t dgi_infer_host(const dgi_graph_t* g, const dgi_layer_t* layers, int32_t num_layers, const void* x_host,
                             int64_t ld_x, void* out_host, int64_t ld_out, const dgi_infer_opts_t* opts,

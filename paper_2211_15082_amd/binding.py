@@ -59,7 +59,7 @@ class OptsStruct(ctypes.Structure):
     _fields_ = [
         ("batch_size", ctypes.c_int64), ("perm_new_of_old", ctypes.c_void_p), ("mem_budget_bytes", ctypes.c_uint64),
         ("stats", ctypes.POINTER(StatsStruct)), ("init_node_threshold", ctypes.c_int64),
-        ("init_edge_threshold", ctypes.c_int64), ("jk_concat", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("init_edge_threshold", ctypes.c_int64), ("jk_concat", ctypes.c_int32), ("host_stream_always", ctypes.c_int32),
     ]
 
 
@@ -72,7 +72,7 @@ class PartialStatsStruct(ctypes.Structure):
 
 class HostStatsStruct(ctypes.Structure):
     _fields_ = [
-        ("num_layers", ctypes.c_int32), ("reserved", ctypes.c_int32), ("total_ms", ctypes.c_double),
+        ("num_layers", ctypes.c_int32), ("device_resident", ctypes.c_int32), ("total_ms", ctypes.c_double),
         ("load_ms", ctypes.c_double * MAX_LAYERS), ("compute_ms", ctypes.c_double * MAX_LAYERS), ("store_ms", ctypes.c_double * MAX_LAYERS),
         ("batches", ctypes.c_int64 * MAX_LAYERS), ("input_rows", ctypes.c_int64 * MAX_LAYERS), ("input_bytes", ctypes.c_int64 * MAX_LAYERS),
         ("output_bytes", ctypes.c_int64 * MAX_LAYERS), ("oom_retries", ctypes.c_int64), ("peak_batch_bytes", ctypes.c_int64),
@@ -308,7 +308,7 @@ def infer_partial(graph, layer_structs, x, targets, out, batch_size=0, mem_budge
 
 
 def infer_host(graph, layer_structs, x_host, out_host, batch_size=0, mem_budget_bytes=0, init_node_threshold=0,
-               init_edge_threshold=0):
+               init_edge_threshold=0, stream_always=False):
     """x_host / out_host: pinned CPU tensors (torch `pin_memory=True`; the library refuses anything else).
     Returns the transfer statistics."""
     arr = (LayerStruct * len(layer_structs))(*layer_structs)
@@ -317,6 +317,7 @@ def infer_host(graph, layer_structs, x_host, out_host, batch_size=0, mem_budget_
     opts.mem_budget_bytes = int(mem_budget_bytes)
     opts.init_node_threshold = int(init_node_threshold)
     opts.init_edge_threshold = int(init_edge_threshold)
+    opts.host_stream_always = 1 if stream_always else 0
     hs = HostStatsStruct()
     _check(_lib.dgi_infer_host(graph.handle, arr, ctypes.c_int32(len(layer_structs)), _dptr(x_host), ctypes.c_int64(x_host.stride(0)),
                                _dptr(out_host), ctypes.c_int64(out_host.stride(0)), ctypes.byref(opts), ctypes.byref(hs), _stream()))

@@ -309,14 +309,28 @@ extern "C" const char* dgi_status_string(dgi_status_t s) {
     return "unknown status";
 }
 
-extern "C" dgi_status_t dgi_graph_release_workspace(dgi_graph_t* g) {
-    if (!g) return DGI_OK;
+dgi_status_t dgi::release_infer_arena(const dgi_graph* g) {
     std::lock_guard<std::mutex> ws_lock(g->ws_mutex);
     if (g->ws_ptr) {
         DGI_HIP(hipDeviceSynchronize());
         (void)hipFree(g->ws_ptr);
         g->ws_ptr = nullptr;
         g->ws_bytes = 0;
+    }
+    return DGI_OK;
+}
+
+extern "C" dgi_status_t dgi_graph_release_workspace(dgi_graph_t* g) {
+    if (!g) return DGI_OK;
+    DGI_TRY(release_infer_arena(g));
+    std::lock_guard<std::mutex> hs_lock(g->hs_mutex);
+    if (g->hs_arena || g->hs_hid[0] || g->hs_hid[1]) {
+        DGI_HIP(hipDeviceSynchronize());
+        (void)hipFree(g->hs_arena);
+        (void)hipHostFree(g->hs_hid[0]);
+        (void)hipHostFree(g->hs_hid[1]);
+        g->hs_arena = nullptr; g->hs_arena_bytes = 0;
+        g->hs_hid[0] = g->hs_hid[1] = nullptr; g->hs_hid_bytes = 0;
     }
     return DGI_OK;
 }

@@ -136,6 +136,9 @@ extern "C" dgi_status_t dgi_graph_free(dgi_graph_t* g) {
     (void)hipFree(g->d_hub_rows);
     (void)hipFree(g->d_hub_chunk_ptr);
     (void)hipFree(g->ws_ptr);
+    (void)hipFree(g->hs_arena);
+    (void)hipHostFree(g->hs_hid[0]);
+    (void)hipHostFree(g->hs_hid[1]);
     delete g;
     return DGI_OK;
 }

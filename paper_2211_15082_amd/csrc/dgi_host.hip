@@ -25,16 +25,49 @@ __global__ void mark_sources_kernel(const int32_t* indices, int64_t e0, int64_t 
         atomicMax(&depth[indices[i]], 0);
 }
 
-struct HostBuf {  // page-locked host memory, visible to the device
-    void* p = nullptr;
-    ~HostBuf() { (void)hipHostFree(p); }
-    dgi_status_t alloc(size_t bytes) { DGI_HIP(hipHostMalloc(&p, std::max<size_t>(bytes, 16), hipHostMallocDefault)); return DGI_OK; }
+// One of two pipeline slots: the device memory of a batch, its sub-problem and the events around its three
+// stages.  While one slot computes and dumps its batch on the second stream, the other builds and loads the
+// next batch on the first.
+struct Slot {
+    char* mem = nullptr;
+    GraphGuard sub;
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};  // load begin, loaded, computed, stored
+    bool pending = false;
+    int layer = 0;
+    int64_t n_sub = 0, rows = 0, in_bytes = 0, out_bytes = 0;
+    uint64_t M_k = 0;
+    ~Slot() { for (auto e : ev) if (e) (void)hipEventDestroy(e); }
+    dgi_status_t create() { for (auto& e : ev) DGI_HIP(hipEventCreate(&e)); return DGI_OK; }
+    // wait until the slot's batch has been stored, account for it, release its sub-problem
+    dgi_status_t retire(dgi_host_stats_t* hs) {
+        if (!pending) return DGI_OK;
+        DGI_HIP(hipEventSynchronize(ev[3]));
+        if (hs) {
+            float t01 = 0.f, t12 = 0.f, t23 = 0.f;
+            DGI_HIP(hipEventElapsedTime(&t01, ev[0], ev[1]));
+            DGI_HIP(hipEventElapsedTime(&t12, ev[1], ev[2]));
+            DGI_HIP(hipEventElapsedTime(&t23, ev[2], ev[3]));
+            hs->load_ms[layer] += t01; hs->compute_ms[layer] += t12; hs->store_ms[layer] += t23;
+            hs->batches[layer] += 1;
+            hs->input_rows[layer] += n_sub;
+            hs->input_bytes[layer] += in_bytes;
+            hs->output_bytes[layer] += out_bytes;
+            hs->peak_batch_bytes = std::max<int64_t>(hs->peak_batch_bytes, (int64_t)M_k);
+        }
+        sub.reset();
+        pending = false;
+        return DGI_OK;
+    }
 };
 
-struct Events {
-    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
-    ~Events() { for (auto e : ev) if (e) (void)hipEventDestroy(e); }
-    dgi_status_t create() { for (auto& e : ev) DGI_HIP(hipEventCreate(&e)); return DGI_OK; }
+struct StreamPair {
+    hipStream_t a = nullptr, b = nullptr;
+    ~StreamPair() { if (a) (void)hipStreamDestroy(a); if (b) (void)hipStreamDestroy(b); }
+    dgi_status_t create() {
+        DGI_HIP(hipStreamCreateWithFlags(&a, hipStreamNonBlocking));
+        DGI_HIP(hipStreamCreateWithFlags(&b, hipStreamNonBlocking));
+        return DGI_OK;
+    }
 };
 
 // the device address of page-locked host memory; an error for anything else
@@ -47,10 +80,24 @@ dgi_status_t device_view(const void* host, const char* what, void** dev) {
     return DGI_OK;
 }
 
+// Device rows to host memory.  Equal leading dimensions: one contiguous copy by the DMA engine.  Otherwise a
+// kernel writes the rows through the mapped host address: a pitched DMA copy of sub-kilobyte rows ran at
+// 14 GB/s here, a third of the link.
+dgi_status_t store_rows(const void* src_dev, int64_t ld_src, void* dst_host, void* dst_host_dev, int64_t ld_dst, int64_t rows, int width, int eb,
+                        hipStream_t s) {
+    if (rows == 0) return DGI_OK;
+    if (ld_src == ld_dst) {
+        DGI_HIP(hipMemcpyAsync(dst_host, src_dev, (size_t)((rows - 1) * ld_dst + width) * eb, hipMemcpyDeviceToHost, s));
+        return DGI_OK;
+    }
+    return launch_permute_rows(src_dev, ld_src, dst_host_dev, ld_dst, rows, width, eb, nullptr, true, s);
+}
+
 template <typename IdxT>
 dgi_status_t infer_host(const dgi_graph* g, const dgi_layer_t* layers, int32_t L, const void* x_host, int64_t ld_x, void* out_host,
                         int64_t ld_out, const dgi_infer_opts_t& o, dgi_host_stats_t* hs, hipStream_t s) {
     const auto t_start = std::chrono::steady_clock::now();
+    std::lock_guard<std::mutex> hs_lock(g->hs_mutex);  // one dgi_infer_host at a time per graph handle
     const int64_t N = g->N;
     const double avg_deg = N > 0 ? (double)g->E / (double)N : 0.0;
     void* x_dev = nullptr;
@@ -58,23 +105,78 @@ dgi_status_t infer_host(const dgi_graph* g, const dgi_layer_t* layers, int32_t L
     DGI_TRY(device_view(x_host, "x_host", &x_dev));
     DGI_TRY(device_view(out_host, "out_host", &out_dev));
 
-    // hidden layers in host memory, used alternately
-    HostBuf hid[2];
+    uint64_t budget = o.mem_budget_bytes;
+    if (budget == 0) {
+        size_t free_b = 0, total_b = 0;
+        DGI_HIP(hipMemGetInfo(&free_b, &total_b));
+        budget = (uint64_t)(0.9 * (double)(free_b + g->ws_bytes));  // the graph handle's cached arena counts as available
+    }
+    // When x, the output and the device-resident schedule's buffers all fit the budget, nothing needs to leave the
+    // device between layers: one copy in, dgi_infer, one copy out.
+    {
+        const int xb = layers[0].feat_dtype == DGI_BF16 ? 2 : 4, yb = layers[L - 1].out_dtype == DGI_BF16 ? 2 : 4;
+        const int64_t ld_xd = round_up(layers[0].in_dim, 16 / xb), ld_yd = round_up(layers[L - 1].out_dim, 16 / yb);
+        const uint64_t io_bytes = (uint64_t)N * ld_xd * xb + (uint64_t)N * ld_yd * yb + 512;
+        if (io_bytes < budget && !o.host_stream_always) {
+            Buf xd, yd;
+            DGI_TRY(xd.alloc((size_t)N * ld_xd * xb));
+            DGI_TRY(yd.alloc((size_t)N * ld_yd * yb));
+            dgi_infer_opts_t r = o;
+            dgi_stats_t rs;
+            r.mem_budget_bytes = budget - io_bytes;
+            r.stats = &rs;
+            Slot t;  // for its events
+            DGI_TRY(t.create());
+            DGI_HIP(hipEventRecord(t.ev[0], s));
+            DGI_HIP(hipMemcpy2DAsync(xd.p, (size_t)ld_xd * xb, x_host, (size_t)ld_x * xb, (size_t)layers[0].in_dim * xb, (size_t)N, hipMemcpyHostToDevice, s));
+            DGI_HIP(hipEventRecord(t.ev[1], s));
+            const dgi_status_t rc = dgi_infer(g, layers, L, xd.p, ld_xd, yd.p, ld_yd, &r, s);
+            if (rc == DGI_OK) {
+                DGI_HIP(hipEventRecord(t.ev[2], s));
+                DGI_TRY(store_rows(yd.p, ld_yd, out_host, out_dev, ld_out, N, layers[L - 1].out_dim, yb, s));
+                DGI_HIP(hipEventRecord(t.ev[3], s));
+                DGI_HIP(hipStreamSynchronize(s));
+                if (hs) {
+                    float t01 = 0.f, t23 = 0.f;
+                    DGI_HIP(hipEventElapsedTime(&t01, t.ev[0], t.ev[1]));
+                    DGI_HIP(hipEventElapsedTime(&t23, t.ev[2], t.ev[3]));
+                    hs->load_ms[0] = t01; hs->store_ms[L - 1] = t23;
+                    for (int l = 0; l < L; ++l) { hs->compute_ms[l] = rs.layer_ms[l]; hs->batches[l] = rs.batches[l]; }
+                    hs->input_rows[0] = N; hs->input_bytes[0] = N * (int64_t)layers[0].in_dim * xb;
+                    hs->output_bytes[L - 1] = N * (int64_t)layers[L - 1].out_dim * yb;
+                    hs->budget_bytes = (int64_t)budget; hs->peak_batch_bytes = rs.workspace_bytes + (int64_t)io_bytes;
+                    hs->oom_retries = rs.oom_retries; hs->device_resident = 1;
+                    hs->total_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_start).count();
+                }
+                return DGI_OK;
+            }
+            if (rc != DGI_ERR_OOM) return rc;
+            DGI_HIP(hipStreamSynchronize(s));  // the hidden layers do not fit: stream them through host memory
+        }
+    }
+
+    // hidden layers in host memory, used alternately (kept in the graph handle between calls)
     size_t hid_bytes = 0;
     for (int l = 0; l + 1 < L; ++l) {
         const int eb = layers[l].out_dtype == DGI_BF16 ? 2 : 4;
         hid_bytes = std::max<size_t>(hid_bytes, (size_t)N * (size_t)round_up(layers[l].out_dim, 16 / eb) * eb);
     }
     const int n_hidden = L >= 3 ? 2 : (L == 2 ? 1 : 0);
-    for (int i = 0; i < n_hidden; ++i) DGI_TRY(hid[i].alloc(hid_bytes));
+    if (n_hidden > 0 && (g->hs_hid_bytes < hid_bytes || (n_hidden == 2 && !g->hs_hid[1]))) {
+        for (int i = 0; i < 2; ++i) { (void)hipHostFree(g->hs_hid[i]); g->hs_hid[i] = nullptr; }
+        g->hs_hid_bytes = 0;
+        for (int i = 0; i < n_hidden; ++i) DGI_HIP(hipHostMalloc(&g->hs_hid[i], std::max<size_t>(hid_bytes, 16), hipHostMallocDefault));
+        g->hs_hid_bytes = hid_bytes;
+    }
+    void* const* hid = g->hs_hid;
 
     // N-sized device scratch and the batch arena (M of Eq. 2)
-    Buf depth, arena;
+    Buf depth;
     Scratch sc;
     DGI_TRY(depth.alloc(N * 4));
     DGI_TRY(sc.alloc(N, s));
-    uint64_t budget = o.mem_budget_bytes;
-    if (budget == 0) {
+    if (o.mem_budget_bytes == 0) {  // the attempt above may have left an arena in the graph handle: give it back, measure again
+        DGI_TRY(release_infer_arena(g));
         size_t free_b = 0, total_b = 0;
         DGI_HIP(hipMemGetInfo(&free_b, &total_b));
         budget = (uint64_t)(0.9 * (double)free_b);
@@ -88,25 +190,42 @@ dgi_status_t infer_host(const dgi_graph* g, const dgi_layer_t* layers, int32_t L
         whole = std::max<uint64_t>(whole, (uint64_t)g->E * 4 + (uint64_t)(N + 1) * 20 + (uint64_t)N * round_up(layers[l].in_dim, 16 / xb) * xb +
                                               (uint64_t)N * round_up(layers[l].out_dim, 16 / yb) * yb + 2 * ws + 8192);
     }
-    const uint64_t M = std::min(budget, whole);
+    // Two slots of M bytes each (M is Eq. 2's expected consumption of one batch); everything at once if it fits.
+    const bool all_fits = whole <= budget / 2;
+    const uint64_t M = (all_fits ? whole : budget / 2) / 256 * 256;
     DGI_REQUIRE(M >= 65536, DGI_ERR_OOM, "infer_host: memory budget %llu bytes is too small", (unsigned long long)budget);
-    DGI_TRY(arena.alloc(M));
-    Events ev;
-    DGI_TRY(ev.create());
+    if (g->hs_arena_bytes < 2 * M || g->hs_arena_bytes > 3 * M + ((uint64_t)64 << 20)) {  // too small, or far beyond this call's budget
+        (void)hipFree(g->hs_arena); g->hs_arena = nullptr; g->hs_arena_bytes = 0;
+        DGI_HIP(hipMalloc(reinterpret_cast<void**>(&g->hs_arena), 2 * M));
+        g->hs_arena_bytes = 2 * M;
+    }
+    Slot slot[2];
+    StreamPair st;
+    DGI_TRY(st.create());
+    struct SyncOnExit {  // declared last, so on every return path the streams drain before the slots are torn down
+        hipStream_t a, b;
+        ~SyncOnExit() { (void)hipStreamSynchronize(a); (void)hipStreamSynchronize(b); }
+    } drain{st.a, st.b};
+    for (int i = 0; i < 2; ++i) { DGI_TRY(slot[i].create()); slot[i].mem = g->hs_arena + (uint64_t)i * M; }
     if (hs) { hs->budget_bytes = (int64_t)M; }
+    DGI_HIP(hipStreamSynchronize(s));  // the caller's earlier work on its stream (x_host may come from it)
+    const hipStream_t sa = st.a, sb = st.b;
 
     const void* cur = x_dev;
     int64_t ld_cur = ld_x;
+    int64_t k = 0;  // batch counter: slot k % 2
     for (int l = 0; l < L; ++l) {
         const dgi_layer_t& Ly = layers[l];
         const int xb = Ly.feat_dtype == DGI_BF16 ? 2 : 4, yb = Ly.out_dtype == DGI_BF16 ? 2 : 4;
         const int64_t ld_xs = round_up(Ly.in_dim, 16 / xb), ld_os = round_up(Ly.out_dim, 16 / yb);
         const bool last = l == L - 1;
-        char* dst_host = last ? static_cast<char*>(out_host) : static_cast<char*>(hid[l % 2].p);
+        char* dst_host = last ? static_cast<char*>(out_host) : static_cast<char*>(hid[l % 2]);
         const int64_t ld_dst = last ? ld_out : ld_os;
+        char* dst_dev = nullptr;
+        DGI_HIP(hipHostGetDevicePointer(reinterpret_cast<void**>(&dst_dev), dst_host, 0));
 
-        int64_t n_t = o.batch_size > 0 ? o.batch_size : (o.init_node_threshold > 0 ? o.init_node_threshold : 65536);
-        int64_t n_i = o.batch_size > 0 ? INT64_MAX / 4
+        int64_t n_t = o.batch_size > 0 ? o.batch_size : (all_fits ? N : (o.init_node_threshold > 0 ? o.init_node_threshold : 65536));
+        int64_t n_i = (o.batch_size > 0 || all_fits) ? INT64_MAX / 4
                                        : (o.init_edge_threshold > 0 ? o.init_edge_threshold : (int64_t)std::max(1.0, (double)n_t * std::max(avg_deg, 1.0)));
         int64_t b = 0;
         while (b < N) {
@@ -122,63 +241,57 @@ dgi_status_t infer_host(const dgi_graph* g, const dgi_layer_t* layers, int32_t L
                 n_t = std::min(n_t, std::max<int64_t>(rows / 2, 1));
                 return DGI_OK;
             };
-            // ---- (i) input set ------------------------------------------------------------------------------
-            DGI_HIP(hipEventRecord(ev.ev[0], s));
-            hipLaunchKernelGGL(batch_depth_kernel, dim3(grid_for(N)), dim3(kBlock), 0, s, depth.as<int32_t>(), N, b, e);
+            Slot& S = slot[k % 2];
+            DGI_TRY(S.retire(hs));  // its previous batch (two batches ago) must have left the slot
+            // ---- (i) input set, on the first stream ---------------------------------------------------------------
+            DGI_HIP(hipEventRecord(S.ev[0], sa));
+            hipLaunchKernelGGL(batch_depth_kernel, dim3(grid_for(N)), dim3(kBlock), 0, sa, depth.as<int32_t>(), N, b, e);
             if (e_b > 0)
-                hipLaunchKernelGGL(mark_sources_kernel, dim3(grid_for(e_b)), dim3(kBlock), 0, s, g->d_indices, g->h_indptr[b], g->h_indptr[e], depth.as<int32_t>());
+                hipLaunchKernelGGL(mark_sources_kernel, dim3(grid_for(e_b)), dim3(kBlock), 0, sa, g->d_indices, g->h_indptr[b], g->h_indptr[e], depth.as<int32_t>());
             int64_t n_sub = 0;
-            DGI_TRY(sc.count_level(depth.as<int32_t>(), N, 0, &n_sub, s));
-            // ---- device memory of this batch (M_k), carved from the arena ----------------------------------------
+            DGI_TRY(sc.count_level(depth.as<int32_t>(), N, 0, &n_sub, sa));
+            // ---- device memory of this batch (M_k), carved from the slot -------------------------------------------------
             uint64_t off = 0;
             auto carve = [&](uint64_t bytes) { const uint64_t at = off; off += (uint64_t)round_up((int64_t)std::max<uint64_t>(bytes, 16), 256); return at; };
             const uint64_t o_idx = carve((uint64_t)e_b * 4), o_ptr = carve((uint64_t)(n_sub + 1) * 8), o_deg = carve((uint64_t)(n_sub + 1) * 8);
             const uint64_t o_U = carve((uint64_t)n_sub * 4), o_x = carve((uint64_t)n_sub * ld_xs * xb), o_y = carve((uint64_t)rows * ld_os * yb);
             if (off > M) { DGI_TRY(shrink()); continue; }
-            char* A = arena.as<char>();
+            char* A = S.mem;
             int64_t e_sub = 0;
-            DGI_TRY(sub_rows<IdxT>(g, depth.as<int32_t>(), sc, n_sub, (int32_t*)(A + o_U), (int64_t*)(A + o_deg), (int64_t*)(A + o_ptr), &e_sub, s));
+            DGI_TRY(sub_rows<IdxT>(g, depth.as<int32_t>(), sc, n_sub, (int32_t*)(A + o_U), (int64_t*)(A + o_deg), (int64_t*)(A + o_ptr), &e_sub, sa));
             DGI_REQUIRE(e_sub == e_b, DGI_ERR_DEVICE, "infer_host: sub-problem has %lld edges, expected %lld", (long long)e_sub, (long long)e_b);
-            GraphGuard sub;
-            DGI_TRY(sub_graph<IdxT>(g, sc, n_sub, e_sub, (const int32_t*)(A + o_U), (const int64_t*)(A + o_ptr), (int32_t*)(A + o_idx), &sub, s));
+            DGI_TRY(sub_graph<IdxT>(g, sc, n_sub, e_sub, (const int32_t*)(A + o_U), (const int64_t*)(A + o_ptr), (int32_t*)(A + o_idx), &S.sub, sa));
             // the batch's rows are one run of local ids: [lb, lb + rows)
             int32_t lb = 0;
-            DGI_HIP(hipMemcpyAsync(&lb, sc.loc.as<int32_t>() + b, 4, hipMemcpyDeviceToHost, s));
-            DGI_HIP(hipStreamSynchronize(s));
+            DGI_HIP(hipMemcpyAsync(&lb, sc.loc.as<int32_t>() + b, 4, hipMemcpyDeviceToHost, sa));
+            DGI_HIP(hipStreamSynchronize(sa));
             uint64_t ws_bytes = 0;
-            DGI_TRY(dgi_layer_workspace_bytes(sub.g, &Ly, lb, lb + rows, &ws_bytes));
+            DGI_TRY(dgi_layer_workspace_bytes(S.sub.g, &Ly, lb, lb + rows, &ws_bytes));
             const uint64_t o_ws = carve(ws_bytes);
-            const uint64_t M_k = off + sub.g->device_bytes;
-            if (M_k > M) { DGI_TRY(shrink()); continue; }
-            // ---- (ii) rows of the input set, read from host memory by the device ----------------------------------
-            DGI_TRY(launch_permute_rows(cur, ld_cur, A + o_x, ld_xs, n_sub, Ly.in_dim, xb, (const int32_t*)(A + o_U), true, s));
-            DGI_HIP(hipEventRecord(ev.ev[1], s));
-            // ---- (iii) the layer on the sub-problem; output row v lands at (v - lb) of the batch's matrix --------------
+            const uint64_t M_k = off + S.sub.g->device_bytes;
+            if (M_k > M) { S.sub.reset(); DGI_TRY(shrink()); continue; }
+            // ---- (ii) rows of the input set, read from host memory by the device --------------------------------------
+            DGI_TRY(launch_permute_rows(cur, ld_cur, A + o_x, ld_xs, n_sub, Ly.in_dim, xb, (const int32_t*)(A + o_U), true, sa));
+            DGI_HIP(hipEventRecord(S.ev[1], sa));
+            // ---- (iii) the layer on the sub-problem, on the second stream; output row v lands at (v - lb) ----------------
+            DGI_HIP(hipStreamWaitEvent(sb, S.ev[1], 0));
             char* y_base = A + o_y - (int64_t)lb * ld_os * yb;
-            DGI_TRY(dgi_layer_forward(sub.g, &Ly, A + o_x, ld_xs, y_base, ld_os, lb, lb + rows, A + o_ws, ws_bytes, s));
-            DGI_HIP(hipEventRecord(ev.ev[2], s));
-            // ---- (iv) dump the batch's rows ------------------------------------------------------------------------
-            DGI_HIP(hipMemcpy2DAsync(dst_host + (size_t)b * ld_dst * yb, (size_t)ld_dst * yb, A + o_y, (size_t)ld_os * yb, (size_t)Ly.out_dim * yb,
-                                     (size_t)rows, hipMemcpyDeviceToHost, s));
-            DGI_HIP(hipEventRecord(ev.ev[3], s));
-            DGI_HIP(hipStreamSynchronize(s));  // the arena and the sub-problem are reused by the next batch
-            if (hs) {
-                float t01 = 0.f, t12 = 0.f, t23 = 0.f;
-                DGI_HIP(hipEventElapsedTime(&t01, ev.ev[0], ev.ev[1]));
-                DGI_HIP(hipEventElapsedTime(&t12, ev.ev[1], ev.ev[2]));
-                DGI_HIP(hipEventElapsedTime(&t23, ev.ev[2], ev.ev[3]));
-                hs->load_ms[l] += t01; hs->compute_ms[l] += t12; hs->store_ms[l] += t23;
-                hs->batches[l] += 1;
-                hs->input_rows[l] += n_sub;
-                hs->input_bytes[l] += n_sub * (int64_t)Ly.in_dim * xb;
-                hs->output_bytes[l] += rows * (int64_t)Ly.out_dim * yb;
-                hs->peak_batch_bytes = std::max<int64_t>(hs->peak_batch_bytes, (int64_t)M_k);
-            }
-            if (o.batch_size == 0) DGI_TRY(dgi_threshold_update((double)M, (double)M_k, &n_t, &n_i));  // Eq. 2
+            DGI_TRY(dgi_layer_forward(S.sub.g, &Ly, A + o_x, ld_xs, y_base, ld_os, lb, lb + rows, A + o_ws, ws_bytes, sb));
+            DGI_HIP(hipEventRecord(S.ev[2], sb));
+            // ---- (iv) dump the batch's rows ------------------------------------------------------------------------------
+            DGI_TRY(store_rows(A + o_y, ld_os, dst_host + (size_t)b * ld_dst * yb, dst_dev + (size_t)b * ld_dst * yb, ld_dst, rows, Ly.out_dim, yb, sb));
+            DGI_HIP(hipEventRecord(S.ev[3], sb));
+            S.pending = true; S.layer = l; S.n_sub = n_sub; S.rows = rows; S.M_k = M_k;
+            S.in_bytes = n_sub * (int64_t)Ly.in_dim * xb; S.out_bytes = rows * (int64_t)Ly.out_dim * yb;
+            if (o.batch_size == 0 && !all_fits) DGI_TRY(dgi_threshold_update((double)M, (double)M_k, &n_t, &n_i));  // Eq. 2
             b = e;
+            ++k;
         }
-        // H^{l-1} is dead from here on: its buffer takes H^{l+1}
-        DGI_HIP(hipHostGetDevicePointer(const_cast<void**>(&cur), dst_host, 0));
+        // layer l+1 reads what layer l dumped: both slots must have stored their batches.  H^{l-1} is dead from
+        // here on: its buffer takes H^{l+1}.
+        DGI_TRY(slot[0].retire(hs));
+        DGI_TRY(slot[1].retire(hs));
+        cur = dst_dev;
         ld_cur = ld_dst;
     }
     if (hs) hs->total_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_start).count();

@@ -69,6 +69,14 @@ struct dgi_graph {
     mutable std::mutex ws_mutex;
     mutable char* ws_ptr = nullptr;
     mutable uint64_t ws_bytes = 0;
+    // dgi_infer_host's buffers, kept between calls for the same reason (page-locking gigabytes of host memory is
+    // slow as well): the device memory of its two batch slots and the two host matrices of the hidden layers.
+    // Guarded by hs_mutex for the whole call.
+    mutable std::mutex hs_mutex;
+    mutable char* hs_arena = nullptr;
+    mutable uint64_t hs_arena_bytes = 0;
+    mutable void* hs_hid[2] = {nullptr, nullptr};
+    mutable uint64_t hs_hid_bytes = 0;
 };
 
 namespace dgi {
@@ -167,7 +175,8 @@ dgi_status_t launch_fill_zero(void* p, uint64_t bytes, hipStream_t stream);
 // out[r, c] = in[r, c] * scale[r]  (rows x width, dtype fp32 or bf16)
 dgi_status_t launch_scale_rows(const void* in, int64_t ld_in, void* out, int64_t ld_out, int64_t rows, int width,
                                int elem_bytes, const float* scale, hipStream_t stream);
-// out[perm ? perm[r] : r] rows <- in rows (gather_inverse=false: out[perm[r]] = in[r]; true: out[r] = in[perm[r]])
+// rows of `width` elements between matrices with different leading dimensions: gather=false: out[perm[r]] = in[r];
+// gather=true: out[r] = in[perm[r]]; perm == nullptr is the identity (a strided copy)
 dgi_status_t launch_permute_rows(const void* in, int64_t ld_in, void* out, int64_t ld_out, int64_t rows, int width,
                                  int elem_bytes, const int32_t* perm, bool gather, hipStream_t stream);
 
@@ -182,6 +191,9 @@ dgi_status_t reorder_permutation_device(const dgi_graph* g, int method, int32_t*
 // host-side permutations (dgi_reorder.cpp)
 dgi_status_t reorder_permutation(int64_t N, const int64_t* indptr, const int32_t* indices, int method, uint64_t seed,
                                  int32_t* perm_new_of_old);
+
+// frees dgi_infer's cached arena (takes ws_mutex; dgi_infer_host calls it while holding hs_mutex)
+dgi_status_t release_infer_arena(const dgi_graph* g);
 
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
