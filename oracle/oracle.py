@@ -149,3 +149,14 @@ def infer_jk(indptr, indices, layers, x):
         h = layer_forward(indptr, indices, layer, h)
         hs.append(h)
     return layer_forward(indptr, indices, layers[-1], np.concatenate(hs, axis=1))
+
+
+def infer_sampled(indptr, indices, layers, x, fanout, seed):
+    """Sampling inference (Section 2): layer l runs on its own sampled graph (oracle/sampler.py); degrees in the
+    mean and GCN normalisers are those of the sampled graph."""
+    from . import sampler
+    h = _f32(x)
+    for l, layer in enumerate(layers):
+        ip, ix = sampler.sample_csr(indptr, indices, fanout, seed, l)
+        h = layer_forward(ip, ix, layer, h)
+    return h
