@@ -269,6 +269,23 @@ dgi_status_t dgi_infer_host(const dgi_graph_t* g, const dgi_layer_t* layers, int
                             int64_t ld_x, void* out_host, int64_t ld_out, const dgi_infer_opts_t* opts,
                             dgi_host_stats_t* hstats, void* hip_stream);
 
+/* Sampling inference (Section 2: each node aggregates a sampled subset of its in-neighbours; the paper's
+ * experiments use a fan-out of 10 for all layers).
+ * dgi_graph_sample: the sampled graph of layer `layer` as a new handle (free it with dgi_graph_free).  A row with
+ * at most `fanout` in-edges keeps them all; otherwise it keeps the `fanout` edges with the smallest keys, in stored
+ * order, a uniform sample without replacement.  The key of the edge at position e of `indices` is the upper 32
+ * bits of output number layer*E + e + 1 of the SplitMix64 generator seeded with `seed` (equal keys ordered by
+ * position in the row), so the sample is a pure function of (graph, fanout, seed, layer).  Waits for completion.
+ * dgi_infer_sampled: layer l of the model runs on dgi_graph_sample(g, fanout, seed, l) with the ordinary
+ * layer-wise schedule (dgi_infer on one layer; opts as there, perm_new_of_old / jk_concat / stats unsupported);
+ * the mean and GCN normalisers use the degrees of the sampled graph.  x, out: DEVICE, as for dgi_infer.  Waits
+ * for completion. */
+dgi_status_t dgi_graph_sample(const dgi_graph_t* g, int32_t fanout, uint64_t seed, int32_t layer, void* hip_stream,
+                              dgi_graph_t** g_out);
+dgi_status_t dgi_infer_sampled(const dgi_graph_t* g, const dgi_layer_t* layers, int32_t num_layers, const void* x,
+                               int64_t ld_x, void* out, int64_t ld_out, int32_t fanout, uint64_t seed,
+                               const dgi_infer_opts_t* opts, void* hip_stream);
+
 /* ------------------------------------------------------------------------------------------------
  * Host-side planning helpers (no device access; usable without a GPU).
  *

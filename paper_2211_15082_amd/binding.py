@@ -90,7 +90,7 @@ class GraphInfoStruct(ctypes.Structure):
 
 EXPORTS = [
     "dgi_graph_load", "dgi_graph_free", "dgi_graph_release_workspace", "dgi_graph_info", "dgi_graph_vector", "dgi_graph_csr", "dgi_graph_reorder",
-    "dgi_layer_forward", "dgi_layer_workspace_bytes", "dgi_infer", "dgi_infer_partial", "dgi_infer_host", "dgi_plan_batch_end", "dgi_threshold_update",
+    "dgi_layer_forward", "dgi_layer_workspace_bytes", "dgi_infer", "dgi_infer_partial", "dgi_infer_host", "dgi_graph_sample", "dgi_infer_sampled", "dgi_plan_batch_end", "dgi_threshold_update",
     "dgi_threshold_halve", "dgi_batch_input_set_size", "dgi_reorder_permutation", "dgi_status_string",
     "dgi_last_error", "dgi_version",
 ]
@@ -305,6 +305,23 @@ def infer_partial(graph, layer_structs, x, targets, out, batch_size=0, mem_budge
     n = ps.num_layers
     return {"set_size": list(ps.set_size)[:n + 1], "all_nodes_from_layer": ps.all_nodes_from_layer,
             "sub_nodes": ps.sub_nodes, "sub_edges": ps.sub_edges}
+
+
+def graph_sample(graph, fanout, seed, layer):
+    """The sampled graph of one layer (a new Graph handle)."""
+    h = ctypes.c_void_p()
+    _check(_lib.dgi_graph_sample(graph.handle, ctypes.c_int32(fanout), ctypes.c_uint64(seed), ctypes.c_int32(layer), _stream(), ctypes.byref(h)))
+    return Graph(h)
+
+
+def infer_sampled(graph, layer_structs, x, out, fanout, seed, batch_size=0, mem_budget_bytes=0):
+    arr = (LayerStruct * len(layer_structs))(*layer_structs)
+    opts = OptsStruct()
+    opts.batch_size = int(batch_size)
+    opts.mem_budget_bytes = int(mem_budget_bytes)
+    _check(_lib.dgi_infer_sampled(graph.handle, arr, ctypes.c_int32(len(layer_structs)), _dptr(x), ctypes.c_int64(x.stride(0)),
+                                  _dptr(out), ctypes.c_int64(out.stride(0)), ctypes.c_int32(fanout), ctypes.c_uint64(seed),
+                                  ctypes.byref(opts), _stream()))
 
 
 def infer_host(graph, layer_structs, x_host, out_host, batch_size=0, mem_budget_bytes=0, init_node_threshold=0,

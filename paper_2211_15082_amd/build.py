@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdgi.so")
-SOURCES = ["dgi_api.hip", "dgi_graph.hip", "dgi_aggregate.hip", "dgi_gat.hip", "dgi_gemm.hip", "dgi_reorder.cpp", "dgi_reorder_gpu.hip", "dgi_partial.hip", "dgi_host.hip"]
+SOURCES = ["dgi_api.hip", "dgi_graph.hip", "dgi_aggregate.hip", "dgi_gat.hip", "dgi_gemm.hip", "dgi_reorder.cpp", "dgi_reorder_gpu.hip", "dgi_partial.hip", "dgi_host.hip", "dgi_sample.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + INCLUDE, "-I" + CSRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

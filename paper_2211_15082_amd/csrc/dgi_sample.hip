@@ -1,0 +1,174 @@
+// Sampling inference (Section 2 of the DGI paper: every node aggregates a sampled subset of its in-neighbours,
+// fan-out 10 in the paper's experiments).  Each layer draws its own sample; layer-wise execution then runs the
+// ordinary schedule on the sampled graph, so a node still reads 1-hop inputs only.
+//
+// Sampling rule: a row with at most `fanout` in-edges keeps them all; otherwise it keeps the `fanout` edges with
+// the smallest keys, in stored order.  The key of the edge at position e of `indices` in layer l is the upper 32
+// bits of output number l*E + e + 1 of SplitMix64 (Steele, Lea, Flood 2014) seeded with `seed`; equal keys are
+// ordered by position in the row.  The keys are a counter-based function of (seed, layer, e), so the sample does
+// not depend on scheduling, and a host implementation of the same rule reproduces it exactly.
+#include <algorithm>
+#include <vector>
+
+#include "dgi_internal.h"
+
+namespace dgi {
+namespace {
+
+__device__ __forceinline__ uint64_t splitmix64_output(uint64_t seed, uint64_t k) {
+    uint64_t z = seed + 0x9E3779B97F4A7C15ull * k;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// One wavefront (= one workgroup) per destination row, rows strided over the grid.  A long row finds its
+// fanout-th smallest (key, position) pair by an 8-pass radix select over the 64-bit pair (a 256-bin histogram in
+// LDS per pass), then keeps the pairs up to that threshold with an order-preserving wave compaction.
+template <typename IdxT>
+__global__ __launch_bounds__(64) void sample_rows_kernel(const IdxT* indptr, const int32_t* indices, int64_t N, int fanout, uint64_t seed,
+                                                         uint64_t key_base /* l*E + 1 */, const int64_t* new_indptr, int32_t* new_indices) {
+    __shared__ uint32_t hist[256];
+    const int lane = threadIdx.x;
+    for (int64_t v = blockIdx.x; v < N; v += gridDim.x) {
+        const int64_t a = (int64_t)indptr[v], d = (int64_t)indptr[v + 1] - a, o = new_indptr[v];
+        if (d <= fanout) {
+            for (int64_t j = lane; j < d; j += 64) new_indices[o + j] = indices[a + j];
+            continue;
+        }
+        auto value = [&](int64_t j) { return (splitmix64_output(seed, key_base + (uint64_t)(a + j)) & 0xFFFFFFFF00000000ull) | (uint64_t)j; };
+        uint64_t prefix = 0;  // the bytes of the threshold found so far (the high ones)
+        uint32_t need = (uint32_t)fanout;  // rank of the threshold among the values that share `prefix`
+        for (int p = 7; p >= 0; --p) {
+            for (int i = lane; i < 256; i += 64) hist[i] = 0u;
+            __syncthreads();
+            for (int64_t j = lane; j < d; j += 64) {
+                const uint64_t val = value(j);
+                if (p == 7 || (val >> (8 * (p + 1))) == prefix) atomicAdd(&hist[(val >> (8 * p)) & 255u], 1u);
+            }
+            __syncthreads();
+            const uint32_t c0 = hist[4 * lane], c1 = hist[4 * lane + 1], c2 = hist[4 * lane + 2], c3 = hist[4 * lane + 3];
+            const uint32_t mine = c0 + c1 + c2 + c3;
+            uint32_t incl = mine;
+#pragma unroll
+            for (int sft = 1; sft < 64; sft <<= 1) {
+                const uint32_t up = __shfl_up(incl, sft, 64);
+                if (lane >= sft) incl += up;
+            }
+            const uint32_t excl = incl - mine;
+            // exactly one lane holds the bucket where the running count reaches `need`
+            const bool here = excl < need && need <= incl;
+            uint32_t bucket = 0, below = 0;
+            if (here) {
+                uint32_t run = excl;
+                if (run + c0 >= need) { bucket = 4 * lane; below = run; }
+                else if ((run += c0) + c1 >= need) { bucket = 4 * lane + 1; below = run; }
+                else if ((run += c1) + c2 >= need) { bucket = 4 * lane + 2; below = run; }
+                else { run += c2; bucket = 4 * lane + 3; below = run; }
+            }
+            const unsigned long long m = __ballot(here);
+            const int src = __ffsll((long long)m) - 1;
+            bucket = __shfl(bucket, src, 64);
+            below = __shfl(below, src, 64);
+            need -= below;
+            prefix = (prefix << 8) | bucket;
+            __syncthreads();
+        }
+        // prefix is now the fanout-th smallest value: keep what does not exceed it, in stored order
+        int64_t base = o;
+        for (int64_t j0 = 0; j0 < d; j0 += 64) {
+            const int64_t j = j0 + lane;
+            const bool keep = j < d && value(j) <= prefix;
+            const unsigned long long m = __ballot(keep);
+            const int64_t at = base + __popcll(m & ((1ull << lane) - 1ull));
+            if (keep && at < o + fanout) new_indices[at] = indices[a + j];  // (exactly fanout values pass; the bound keeps a row inside its slots regardless)
+            base += __popcll(m);
+        }
+    }
+}
+
+}  // namespace
+}  // namespace dgi
+
+using namespace dgi;
+
+extern "C" dgi_status_t dgi_graph_sample(const dgi_graph_t* g, int32_t fanout, uint64_t seed, int32_t layer, void* hip_stream,
+                                         dgi_graph_t** g_out) {
+    DGI_REQUIRE(g && g_out, DGI_ERR_INVALID_ARG, "graph_sample: NULL argument");
+    *g_out = nullptr;
+    DGI_REQUIRE(fanout >= 1, DGI_ERR_INVALID_ARG, "graph_sample: fan-out must be at least 1");
+    DGI_REQUIRE(layer >= 0 && layer < DGI_MAX_LAYERS, DGI_ERR_INVALID_ARG, "graph_sample: bad layer index");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const int64_t N = g->N;
+    std::vector<int64_t> ip((size_t)N + 1, 0);
+    for (int64_t v = 0; v < N; ++v) ip[v + 1] = ip[v] + std::min<int64_t>(g->h_indptr[v + 1] - g->h_indptr[v], fanout);
+    const int64_t Es = ip[N];
+    int64_t* d_ip = nullptr;
+    int32_t* d_ix = nullptr;
+    DGI_HIP(hipMalloc(reinterpret_cast<void**>(&d_ip), (size_t)(N + 1) * 8));
+    hipError_t err = hipMalloc(reinterpret_cast<void**>(&d_ix), std::max<size_t>((size_t)Es * 4, 16));
+    auto fail = [&](dgi_status_t st) { (void)hipFree(d_ip); (void)hipFree(d_ix); return st; };
+    if (err != hipSuccess) { set_error("graph_sample: %s", hipGetErrorString(err)); return fail(err == hipErrorOutOfMemory ? DGI_ERR_OOM : DGI_ERR_DEVICE); }
+    err = hipMemcpyAsync(d_ip, ip.data(), (size_t)(N + 1) * 8, hipMemcpyHostToDevice, s);
+    if (err == hipSuccess && N > 0) {
+        const unsigned grid = (unsigned)std::min<int64_t>(N, (int64_t)1 << 22);
+        const uint64_t key_base = (uint64_t)layer * (uint64_t)g->E + 1ull;
+        if (g->itype == DGI_I64)
+            hipLaunchKernelGGL(sample_rows_kernel<int64_t>, dim3(grid), dim3(64), 0, s, (const int64_t*)g->d_indptr, g->d_indices, N, (int)fanout, seed,
+                               key_base, d_ip, d_ix);
+        else
+            hipLaunchKernelGGL(sample_rows_kernel<int32_t>, dim3(grid), dim3(64), 0, s, (const int32_t*)g->d_indptr, g->d_indices, N, (int)fanout, seed,
+                               key_base, d_ip, d_ix);
+        err = hipGetLastError();
+    }
+    if (err == hipSuccess) err = hipStreamSynchronize(s);  // `ip` is a host temporary
+    if (err != hipSuccess) { set_error("graph_sample: %s", hipGetErrorString(err)); return fail(DGI_ERR_DEVICE); }
+    dgi_graph_t* ng = nullptr;
+    const dgi_status_t st = dgi_graph_load(N, Es, d_ip, DGI_I64, d_ix, DGI_DEVICE, s, &ng);
+    if (st != DGI_OK) return fail(st);
+    ng->own_csr = true;  // the handle frees the sampled arrays
+    *g_out = ng;
+    return DGI_OK;
+}
+
+extern "C" dgi_status_t dgi_infer_sampled(const dgi_graph_t* g, const dgi_layer_t* layers, int32_t num_layers, const void* x, int64_t ld_x,
+                                          void* out, int64_t ld_out, int32_t fanout, uint64_t seed, const dgi_infer_opts_t* opts,
+                                          void* hip_stream) {
+    DGI_REQUIRE(g && layers, DGI_ERR_INVALID_ARG, "infer_sampled: NULL argument");
+    DGI_REQUIRE(num_layers >= 1 && num_layers <= DGI_MAX_LAYERS, DGI_ERR_INVALID_ARG, "infer_sampled: 1..%d layers supported", DGI_MAX_LAYERS);
+    dgi_infer_opts_t o{};
+    if (opts) o = *opts;
+    DGI_REQUIRE(!o.perm_new_of_old && !o.jk_concat, DGI_ERR_UNSUPPORTED, "infer_sampled: permutation and jumping-knowledge options are not supported");
+    o.stats = nullptr;
+    for (int l = 1; l < num_layers; ++l) {
+        DGI_REQUIRE(layers[l].in_dim == layers[l - 1].out_dim, DGI_ERR_INVALID_ARG, "layer %d: in_dim != previous out_dim", l);
+        DGI_REQUIRE(layers[l].feat_dtype == layers[l - 1].out_dtype, DGI_ERR_INVALID_ARG, "layer %d: feat_dtype != previous out_dtype", l);
+    }
+    const int64_t N = g->N;
+    if (N == 0) return DGI_OK;
+    DGI_REQUIRE(x && out, DGI_ERR_INVALID_ARG, "infer_sampled: NULL buffer");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    struct Hidden { void* p = nullptr; ~Hidden() { (void)hipFree(p); } } hid[2];
+    size_t hid_bytes = 16;
+    for (int l = 0; l + 1 < num_layers; ++l) {
+        const int eb = layers[l].out_dtype == DGI_BF16 ? 2 : 4;
+        hid_bytes = std::max<size_t>(hid_bytes, (size_t)N * (size_t)round_up(layers[l].out_dim, 16 / eb) * eb);
+    }
+    for (int i = 0; i < std::min(2, num_layers - 1); ++i) DGI_HIP(hipMalloc(&hid[i].p, hid_bytes));
+    const void* cur = x;
+    int64_t ld_cur = ld_x;
+    for (int l = 0; l < num_layers; ++l) {
+        const bool last = l == num_layers - 1;
+        const int eb = layers[l].out_dtype == DGI_BF16 ? 2 : 4;
+        void* dst = last ? out : hid[l % 2].p;
+        const int64_t ld_dst = last ? ld_out : round_up(layers[l].out_dim, 16 / eb);
+        dgi_graph_t* gs = nullptr;
+        DGI_TRY(dgi_graph_sample(g, fanout, seed, l, s, &gs));
+        const dgi_status_t st = dgi_infer(gs, &layers[l], 1, cur, ld_cur, dst, ld_dst, &o, s);  // waits for completion
+        dgi_graph_free(gs);
+        DGI_TRY(st);
+        cur = dst;
+        ld_cur = ld_dst;
+    }
+    return DGI_OK;
+}
