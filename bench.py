@@ -165,6 +165,32 @@ def host_resident(args, cfg, g, structs, B):
         "oom_retries": st["oom_retries"], "peak_batch_bytes": st["peak_batch_bytes"], "device_resident": st["device_resident"]}))
 
 
+def sampling(args, cfg, g, structs, x, out, B):
+    """Sampling inference (Section 2; the paper's experiments use fan-out 10): every layer draws its sample on the
+    device and runs the ordinary schedule on the sampled graph.  Separate line, never the headline value."""
+    import torch
+    n, e = cfg["num_nodes"], int(cfg["indices"].numel())
+    for _ in range(max(args.warmup, 1)):
+        B.infer_sampled(g, structs, x, out, args.fanout, 1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        B.infer_sampled(g, structs, x, out, args.fanout, 2 + i)
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / args.steps
+    t0 = time.perf_counter()
+    gs = B.graph_sample(g, args.fanout, 1, 0)
+    torch.cuda.synchronize()
+    t_sample = time.perf_counter() - t0
+    kept = gs.info()["num_edges"]
+    gs.free()
+    print(json.dumps({"metric": "sampling inference: seconds per full-graph pass", "value": sec, "unit": "s", "higher_is_better": False,
+                      "n_gpus": 1, "steps": args.steps, "warmup": max(args.warmup, 1), "data": "synthetic",
+                      "config": {"workload": cfg["name"] + " [fan-out %d]" % args.fanout, "num_nodes": n, "num_edges": e,
+                                 "sampled_edges_per_layer": kept},
+                      "sample_one_layer_ms": t_sample * 1e3, "sampled_edges_per_second": len(structs) * kept / sec}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -175,6 +201,7 @@ def main():
     ap.add_argument("--batch-size", type=int, default=0, help="destination rows per batch; 0 = dynamic")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ablation", action="store_true", help="reordering x batch-size ablation instead of the timed run")
+    ap.add_argument("--fanout", type=int, default=0, help="sampling inference with this fan-out per layer (prints its own JSON line)")
     ap.add_argument("--host-resident", action="store_true",
                     help="embeddings in pinned host memory, batches streamed in (dgi_infer_host); prints its own JSON line")
     ap.add_argument("--allow-device-resident", action="store_true",
@@ -216,6 +243,9 @@ def main():
 
     if args.ablation:
         ablation(args, cfg, g, structs, x, out, B)
+        return
+    if args.fanout > 0:
+        sampling(args, cfg, g, structs, x, out, B)
         return
     if args.host_resident:
         del out

@@ -203,8 +203,8 @@ dgi_status_t dgi_layer_workspace_bytes(const dgi_graph_t* g, const dgi_layer_t* 
  *   layers[l].in_dim must equal layers[l-1].out_dim and feat_dtype must equal the previous out_dtype.
  * The call takes its hidden buffers and temporaries (Algorithm 2's H^l and per-batch buffers) from one
  * arena within opts->mem_budget_bytes.  The arena is allocated with hipMalloc on the first call, kept in
- * the graph handle and reused by later calls (reallocated when a call needs more, or far less under a
- * smaller budget); dgi_graph_release_workspace or dgi_graph_free returns it.  Calls on one graph handle
+ * the graph handle and reused by later calls (reallocated when a call needs more, or when it is larger than
+ * the call's budget); dgi_graph_release_workspace or dgi_graph_free returns it.  Calls on one graph handle
  * are serialised by a lock.  The call waits for its work on the stream before returning.
  * opts may be NULL (all defaults). */
 dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layers, int32_t num_layers, const void* x,
@@ -278,8 +278,9 @@ dgi_status_t dgi_infer_host(const dgi_graph_t* g, const dgi_layer_t* layers, int
  * position in the row), so the sample is a pure function of (graph, fanout, seed, layer).  Waits for completion.
  * dgi_infer_sampled: layer l of the model runs on dgi_graph_sample(g, fanout, seed, l) with the ordinary
  * layer-wise schedule (dgi_infer on one layer; opts as there, perm_new_of_old / jk_concat / stats unsupported);
- * the mean and GCN normalisers use the degrees of the sampled graph.  x, out: DEVICE, as for dgi_infer.  Waits
- * for completion. */
+ * the mean and GCN normalisers use the degrees of the sampled graph.  x, out: DEVICE, as for dgi_infer.  The
+ * hidden layers and the schedule's arena are kept in g's handle between calls (dgi_graph_release_workspace returns
+ * them); calls on one handle are serialised.  Waits for completion. */
 dgi_status_t dgi_graph_sample(const dgi_graph_t* g, int32_t fanout, uint64_t seed, int32_t layer, void* hip_stream,
                               dgi_graph_t** g_out);
 dgi_status_t dgi_infer_sampled(const dgi_graph_t* g, const dgi_layer_t* layers, int32_t num_layers, const void* x,

@@ -460,8 +460,8 @@ extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layer
     const uint64_t temp_cap = std::max<uint64_t>(std::min<uint64_t>(budget - persistent, temp_full_max), 256);
 
     const uint64_t arena_bytes = persistent + temp_cap + 1024;
-    if (g->ws_bytes < arena_bytes || g->ws_bytes > arena_bytes + arena_bytes / 2 + ((uint64_t)64 << 20)) {
-        // (re)allocate: too small, or far larger than this call may use under its budget
+    if (g->ws_bytes < arena_bytes || g->ws_bytes > std::max<uint64_t>(budget, arena_bytes)) {
+        // (re)allocate: too small, or larger than this call's budget allows it to hold
         if (g->ws_ptr) { DGI_HIP(hipStreamSynchronize(s)); (void)hipFree(g->ws_ptr); g->ws_ptr = nullptr; g->ws_bytes = 0; }
         DGI_HIP(hipMalloc(reinterpret_cast<void**>(&g->ws_ptr), arena_bytes));
         g->ws_bytes = arena_bytes;

@@ -67,7 +67,7 @@ void find_hubs(dgi_graph* g) {
 }
 
 // Shared tail of load / reorder: the handle already has N, E, itype, device CSR and h_indptr.
-dgi_status_t finish_graph(dgi_graph* g, hipStream_t stream) {
+dgi_status_t finish_graph(dgi_graph* g, hipStream_t stream, bool no_hubs = false) {
     DGI_TRY(dev_alloc(&g->d_deg_out, g->N, g));
     DGI_TRY(dev_alloc(&g->d_rs_in, g->N, g));
     DGI_TRY(dev_alloc(&g->d_rs_out, g->N, g));
@@ -100,7 +100,8 @@ dgi_status_t finish_graph(dgi_graph* g, hipStream_t stream) {
     (void)hipFree(d_bad);
     DGI_TRY(st);
     DGI_REQUIRE(bad == 0, DGI_ERR_BAD_GRAPH, "indices hold a value outside [0, num_nodes)");
-    find_hubs(g);
+    if (no_hubs) { g->h_hub_rows.clear(); g->h_hub_chunk_ptr.assign(1, 0); }
+    else find_hubs(g);
     const size_t nh = g->h_hub_rows.size();
     DGI_TRY(dev_alloc(&g->d_hub_rows, nh, g));
     DGI_TRY(dev_alloc(&g->d_hub_chunk_ptr, nh + 1, g));
@@ -120,6 +121,26 @@ dgi_status_t validate_indptr(const dgi_graph* g) {
 }
 
 }  // namespace
+
+// A handle over device arrays the library built itself (int64 indptr), taking ownership of them and of the host
+// copy of indptr: no download, no validation of indptr.  With max_degree >= 0 and no hub rows possible the host
+// scan for hubs is skipped as well.
+dgi_status_t graph_adopt(int64_t N, int64_t E, int64_t* d_indptr, int32_t* d_indices, std::vector<int64_t>&& h_indptr, int64_t max_degree,
+                         hipStream_t stream, dgi_graph_t** out) {
+    dgi_graph* g = new dgi_graph();
+    g->N = N; g->E = E; g->itype = DGI_I64;
+    (void)hipGetDevice(&g->device);
+    g->d_indptr = d_indptr; g->d_indices = d_indices; g->own_csr = true;
+    g->device_bytes = (uint64_t)(N + 1) * 8 + (uint64_t)E * 4;
+    g->h_indptr = std::move(h_indptr);
+    const bool skip_hub_scan = max_degree >= 0 && max_degree <= kHubDegree;
+    dgi_status_t st = finish_graph(g, stream, skip_hub_scan);
+    if (st != DGI_OK) { dgi_graph_free(g); return st; }
+    if (skip_hub_scan) g->max_in_degree = max_degree;
+    *out = g;
+    return DGI_OK;
+}
+
 }  // namespace dgi
 
 using namespace dgi;

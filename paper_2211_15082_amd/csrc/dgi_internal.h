@@ -192,6 +192,10 @@ dgi_status_t reorder_permutation_device(const dgi_graph* g, int method, int32_t*
 dgi_status_t reorder_permutation(int64_t N, const int64_t* indptr, const int32_t* indices, int method, uint64_t seed,
                                  int32_t* perm_new_of_old);
 
+// handle over device CSR arrays built by the library (int64 indptr); takes ownership of the arrays and of h_indptr
+dgi_status_t graph_adopt(int64_t N, int64_t E, int64_t* d_indptr, int32_t* d_indices, std::vector<int64_t>&& h_indptr, int64_t max_degree,
+                         hipStream_t stream, dgi_graph_t** out);
+
 // frees dgi_infer's cached arena (takes ws_mutex; dgi_infer_host calls it while holding hs_mutex)
 dgi_status_t release_infer_arena(const dgi_graph* g);
 

@@ -8,6 +8,9 @@
 // ordered by position in the row.  The keys are a counter-based function of (seed, layer, e), so the sample does
 // not depend on scheduling, and a host implementation of the same rule reproduces it exactly.
 #include <algorithm>
+#include <mutex>
+#include <thread>
+#include <utility>
 #include <vector>
 
 #include "dgi_internal.h"
@@ -37,6 +40,18 @@ __global__ __launch_bounds__(64) void sample_rows_kernel(const IdxT* indptr, con
             continue;
         }
         auto value = [&](int64_t j) { return (splitmix64_output(seed, key_base + (uint64_t)(a + j)) & 0xFFFFFFFF00000000ull) | (uint64_t)j; };
+        if (d <= 64) {  // the whole row sits in the wavefront: rank every value against the others
+            const uint64_t mine = lane < d ? value(lane) : ~0ull;
+            int rank = 0;
+            for (int i = 0; i < (int)d; ++i) {
+                const uint64_t other = ((uint64_t)__shfl((uint32_t)(mine >> 32), i, 64) << 32) | (uint32_t)i;  // the low half is the position
+                rank += other < mine ? 1 : 0;
+            }
+            const bool keep = lane < d && rank < fanout;
+            const unsigned long long m = __ballot(keep);
+            if (keep) new_indices[o + __popcll(m & ((1ull << lane) - 1ull))] = indices[a + lane];
+            continue;
+        }
         uint64_t prefix = 0;  // the bytes of the threshold found so far (the high ones)
         uint32_t need = (uint32_t)fanout;  // rank of the threshold among the values that share `prefix`
         for (int p = 7; p >= 0; --p) {
@@ -100,8 +115,33 @@ extern "C" dgi_status_t dgi_graph_sample(const dgi_graph_t* g, int32_t fanout, u
     DGI_REQUIRE(layer >= 0 && layer < DGI_MAX_LAYERS, DGI_ERR_INVALID_ARG, "graph_sample: bad layer index");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const int64_t N = g->N;
-    std::vector<int64_t> ip((size_t)N + 1, 0);
-    for (int64_t v = 0; v < N; ++v) ip[v + 1] = ip[v] + std::min<int64_t>(g->h_indptr[v + 1] - g->h_indptr[v], fanout);
+    // indptr of the sample = prefix sums of min(degree, fanout): on the host in parallel chunks (the handle keeps a
+    // host copy for batch planning), uploaded from there
+    std::vector<int64_t> ip((size_t)N + 1);
+    ip[0] = 0;
+    {
+        const int T = (int)std::max<int64_t>(1, std::min<int64_t>({(int64_t)std::thread::hardware_concurrency(), (int64_t)16, N / 65536 + 1}));
+        std::vector<int64_t> chunk_sum((size_t)T + 1, 0);
+        auto range = [&](int t) { return std::make_pair(N * t / T, N * (t + 1) / T); };
+        auto run = [&](auto&& fn) {
+            std::vector<std::thread> th;
+            for (int t = 1; t < T; ++t) th.emplace_back(fn, t);
+            fn(0);
+            for (auto& x : th) x.join();
+        };
+        run([&](int t) {
+            const auto r = range(t);
+            int64_t sum = 0;
+            for (int64_t v = r.first; v < r.second; ++v) sum += std::min<int64_t>(g->h_indptr[v + 1] - g->h_indptr[v], fanout);
+            chunk_sum[t + 1] = sum;
+        });
+        for (int t = 0; t < T; ++t) chunk_sum[t + 1] += chunk_sum[t];
+        run([&](int t) {
+            const auto r = range(t);
+            int64_t acc = chunk_sum[t];
+            for (int64_t v = r.first; v < r.second; ++v) { acc += std::min<int64_t>(g->h_indptr[v + 1] - g->h_indptr[v], fanout); ip[v + 1] = acc; }
+        });
+    }
     const int64_t Es = ip[N];
     int64_t* d_ip = nullptr;
     int32_t* d_ix = nullptr;
@@ -121,14 +161,10 @@ extern "C" dgi_status_t dgi_graph_sample(const dgi_graph_t* g, int32_t fanout, u
                                key_base, d_ip, d_ix);
         err = hipGetLastError();
     }
-    if (err == hipSuccess) err = hipStreamSynchronize(s);  // `ip` is a host temporary
+    if (err == hipSuccess) err = hipStreamSynchronize(s);  // `ip` moves into the handle next
     if (err != hipSuccess) { set_error("graph_sample: %s", hipGetErrorString(err)); return fail(DGI_ERR_DEVICE); }
-    dgi_graph_t* ng = nullptr;
-    const dgi_status_t st = dgi_graph_load(N, Es, d_ip, DGI_I64, d_ix, DGI_DEVICE, s, &ng);
-    if (st != DGI_OK) return fail(st);
-    ng->own_csr = true;  // the handle frees the sampled arrays
-    *g_out = ng;
-    return DGI_OK;
+    // the handle owns d_ip / d_ix from here on (graph_adopt frees them if it fails)
+    return graph_adopt(N, Es, d_ip, d_ix, std::move(ip), std::min<int64_t>(g->max_in_degree, fanout), s, g_out);
 }
 
 extern "C" dgi_status_t dgi_infer_sampled(const dgi_graph_t* g, const dgi_layer_t* layers, int32_t num_layers, const void* x, int64_t ld_x,
@@ -148,15 +184,32 @@ extern "C" dgi_status_t dgi_infer_sampled(const dgi_graph_t* g, const dgi_layer_
     if (N == 0) return DGI_OK;
     DGI_REQUIRE(x && out, DGI_ERR_INVALID_ARG, "infer_sampled: NULL buffer");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    struct Hidden { void* p = nullptr; ~Hidden() { (void)hipFree(p); } } hid[2];
-    size_t hid_bytes = 16;
+    // Hidden layers: two buffers carved from the device memory the handle keeps for dgi_infer_host (the two calls
+    // exclude each other through hs_mutex), so repeated calls allocate nothing.
+    std::lock_guard<std::mutex> hs_lock(g->hs_mutex);
+    size_t hid_bytes = 256;
     for (int l = 0; l + 1 < num_layers; ++l) {
         const int eb = layers[l].out_dtype == DGI_BF16 ? 2 : 4;
-        hid_bytes = std::max<size_t>(hid_bytes, (size_t)N * (size_t)round_up(layers[l].out_dim, 16 / eb) * eb);
+        hid_bytes = std::max<size_t>(hid_bytes, (size_t)round_up((int64_t)((size_t)N * (size_t)round_up(layers[l].out_dim, 16 / eb) * eb), 256));
     }
-    for (int i = 0; i < std::min(2, num_layers - 1); ++i) DGI_HIP(hipMalloc(&hid[i].p, hid_bytes));
+    const int n_hidden = std::min(2, num_layers - 1);
+    if (n_hidden > 0 && g->hs_arena_bytes < (uint64_t)n_hidden * hid_bytes) {
+        (void)hipFree(g->hs_arena); g->hs_arena = nullptr; g->hs_arena_bytes = 0;
+        DGI_HIP(hipMalloc(reinterpret_cast<void**>(&g->hs_arena), (size_t)n_hidden * hid_bytes));
+        g->hs_arena_bytes = (uint64_t)n_hidden * hid_bytes;
+    }
+    struct { void* p; } hid[2] = {{g->hs_arena}, {g->hs_arena ? g->hs_arena + hid_bytes : nullptr}};
     const void* cur = x;
     int64_t ld_cur = ld_x;
+    // dgi_infer keeps its arena in the graph handle; the sampled graphs live for one layer each, so the arena is
+    // handed from one to the next instead of being allocated per layer
+    // ... and between calls it stays in the full graph's handle, where dgi_infer would keep its own.
+    std::lock_guard<std::mutex> ws_lock(g->ws_mutex);
+    struct Arena {
+        const dgi_graph* home; char* p; uint64_t bytes;
+        ~Arena() { home->ws_ptr = p; home->ws_bytes = bytes; }
+    } arena{g, g->ws_ptr, g->ws_bytes};
+    g->ws_ptr = nullptr; g->ws_bytes = 0;
     for (int l = 0; l < num_layers; ++l) {
         const bool last = l == num_layers - 1;
         const int eb = layers[l].out_dtype == DGI_BF16 ? 2 : 4;
@@ -164,7 +217,11 @@ extern "C" dgi_status_t dgi_infer_sampled(const dgi_graph_t* g, const dgi_layer_
         const int64_t ld_dst = last ? ld_out : round_up(layers[l].out_dim, 16 / eb);
         dgi_graph_t* gs = nullptr;
         DGI_TRY(dgi_graph_sample(g, fanout, seed, l, s, &gs));
+        gs->ws_ptr = arena.p; gs->ws_bytes = arena.bytes;
+        arena.p = nullptr; arena.bytes = 0;
         const dgi_status_t st = dgi_infer(gs, &layers[l], 1, cur, ld_cur, dst, ld_dst, &o, s);  // waits for completion
+        arena.p = gs->ws_ptr; arena.bytes = gs->ws_bytes;
+        gs->ws_ptr = nullptr; gs->ws_bytes = 0;
         dgi_graph_free(gs);
         DGI_TRY(st);
         cur = dst;
