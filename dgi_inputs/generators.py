@@ -55,7 +55,9 @@ def power_law_cdf(n, gamma, max_expected_degree, endpoints, device):
                 hi = mid
         i0 = hi
     w = (i + i0).pow(-alpha)
-    cdf = torch.cumsum(w, 0)
+    # prefix sums on the host: a device scan combines its partial sums in a timing-dependent order, which moves the
+    # last bits of the CDF and with them a handful of the billions of draws from one run to the next
+    cdf = torch.cumsum(w.cpu(), 0).to(device)
     return cdf / cdf[-1], i0
 
 

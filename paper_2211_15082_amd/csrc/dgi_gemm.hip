@@ -11,7 +11,6 @@
 // in flight while the current one is multiplied).  LDS rows are padded by 16 bytes so that the 16-byte
 // fragment reads of 8 consecutive lanes cover all banks.
 #include <algorithm>
-#include <cstdlib>
 
 #include "dgi_device.h"
 #include "dgi_internal.h"
@@ -342,8 +341,7 @@ dgi_status_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
     p.M = a.M; p.Nout = a.Nout;
     {
         const int ob = p.out_bf16 ? 2 : 4;
-        static const bool scalar_only = [] { const char* e = getenv("DGI_TUNE_GEMM_EPI"); return e && atoi(e) == 0; }();
-        p.y_vec = !scalar_only && ((uintptr_t)a.Y % 16 == 0) && ((a.ld_y * ob) % 16 == 0);
+        p.y_vec = ((uintptr_t)a.Y % 16 == 0) && ((a.ld_y * ob) % 16 == 0);
     }
     p.out_scale = a.out_scale; p.row0 = a.row0;
     // 128-wide column tiles: a 256-wide tile would read A once but leaves one wavefront per SIMD and measured slower
