@@ -324,14 +324,18 @@ extern "C" dgi_status_t dgi_graph_release_workspace(dgi_graph_t* g) {
     if (!g) return DGI_OK;
     DGI_TRY(release_infer_arena(g));
     std::lock_guard<std::mutex> hs_lock(g->hs_mutex);
-    if (g->hs_arena || g->hs_hid[0] || g->hs_hid[1]) {
+    if (g->hs_arena || g->hs_hid[0] || g->hs_hid[1] || g->ss_d_ip || g->ss_d_ix) {
         DGI_HIP(hipDeviceSynchronize());
         (void)hipFree(g->hs_arena);
         (void)hipHostFree(g->hs_hid[0]);
         (void)hipHostFree(g->hs_hid[1]);
+        (void)hipFree(g->ss_d_ip);
+        (void)hipFree(g->ss_d_ix);
         g->hs_arena = nullptr; g->hs_arena_bytes = 0;
         g->hs_hid[0] = g->hs_hid[1] = nullptr; g->hs_hid_bytes = 0;
+        g->ss_d_ip = nullptr; g->ss_d_ix = nullptr; g->ss_ix_cap = 0;
     }
+    std::vector<int64_t>().swap(g->ss_ip);
     return DGI_OK;
 }
 

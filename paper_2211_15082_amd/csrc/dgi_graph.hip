@@ -122,21 +122,22 @@ dgi_status_t validate_indptr(const dgi_graph* g) {
 
 }  // namespace
 
-// A handle over device arrays the library built itself (int64 indptr), taking ownership of them and of the host
-// copy of indptr: no download, no validation of indptr.  With max_degree >= 0 and no hub rows possible the host
-// scan for hubs is skipped as well.
+// A handle over device arrays the library built itself (int64 indptr), taking the host copy of indptr and, with
+// own_arrays, the device arrays too: no download, no validation of indptr.  With max_degree >= 0 and no hub rows
+// possible the host scan for hubs is skipped as well.  On failure nothing is adopted: the caller still owns the arrays.
 dgi_status_t graph_adopt(int64_t N, int64_t E, int64_t* d_indptr, int32_t* d_indices, std::vector<int64_t>&& h_indptr, int64_t max_degree,
-                         hipStream_t stream, dgi_graph_t** out) {
+                         bool own_arrays, hipStream_t stream, dgi_graph_t** out) {
     dgi_graph* g = new dgi_graph();
     g->N = N; g->E = E; g->itype = DGI_I64;
     (void)hipGetDevice(&g->device);
-    g->d_indptr = d_indptr; g->d_indices = d_indices; g->own_csr = true;
+    g->d_indptr = d_indptr; g->d_indices = d_indices; g->own_csr = false;
     g->device_bytes = (uint64_t)(N + 1) * 8 + (uint64_t)E * 4;
     g->h_indptr = std::move(h_indptr);
     const bool skip_hub_scan = max_degree >= 0 && max_degree <= kHubDegree;
     dgi_status_t st = finish_graph(g, stream, skip_hub_scan);
-    if (st != DGI_OK) { dgi_graph_free(g); return st; }
+    if (st != DGI_OK) { h_indptr = std::move(g->h_indptr); dgi_graph_free(g); return st; }
     if (skip_hub_scan) g->max_in_degree = max_degree;
+    g->own_csr = own_arrays;
     *out = g;
     return DGI_OK;
 }
@@ -160,6 +161,8 @@ extern "C" dgi_status_t dgi_graph_free(dgi_graph_t* g) {
     (void)hipFree(g->hs_arena);
     (void)hipHostFree(g->hs_hid[0]);
     (void)hipHostFree(g->hs_hid[1]);
+    (void)hipFree(g->ss_d_ip);
+    (void)hipFree(g->ss_d_ix);
     delete g;
     return DGI_OK;
 }

@@ -77,6 +77,12 @@ struct dgi_graph {
     mutable uint64_t hs_arena_bytes = 0;
     mutable void* hs_hid[2] = {nullptr, nullptr};
     mutable uint64_t hs_hid_bytes = 0;
+    // dgi_infer_sampled builds one sampled graph per layer: its host indptr, device indptr and device indices
+    // live here between layers and calls (the sampled handle borrows them).  Guarded by hs_mutex as well.
+    mutable std::vector<int64_t> ss_ip;
+    mutable int64_t* ss_d_ip = nullptr;
+    mutable int32_t* ss_d_ix = nullptr;
+    mutable uint64_t ss_ix_cap = 0;  // entries
 };
 
 namespace dgi {
@@ -194,7 +200,7 @@ dgi_status_t reorder_permutation(int64_t N, const int64_t* indptr, const int32_t
 
 // handle over device CSR arrays built by the library (int64 indptr); takes ownership of the arrays and of h_indptr
 dgi_status_t graph_adopt(int64_t N, int64_t E, int64_t* d_indptr, int32_t* d_indices, std::vector<int64_t>&& h_indptr, int64_t max_degree,
-                         hipStream_t stream, dgi_graph_t** out);
+                         bool own_arrays, hipStream_t stream, dgi_graph_t** out);
 
 // frees dgi_infer's cached arena (takes ws_mutex; dgi_infer_host calls it while holding hs_mutex)
 dgi_status_t release_infer_arena(const dgi_graph* g);

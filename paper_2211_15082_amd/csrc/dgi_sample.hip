@@ -7,7 +7,10 @@
 // bits of output number l*E + e + 1 of SplitMix64 (Steele, Lea, Flood 2014) seeded with `seed`; equal keys are
 // ordered by position in the row.  The keys are a counter-based function of (seed, layer, e), so the sample does
 // not depend on scheduling, and a host implementation of the same rule reproduces it exactly.
+#include <hipcub/hipcub.hpp>
+
 #include <algorithm>
+#include <climits>
 #include <mutex>
 #include <thread>
 #include <utility>
@@ -102,22 +105,26 @@ __global__ __launch_bounds__(64) void sample_rows_kernel(const IdxT* indptr, con
     }
 }
 
-}  // namespace
-}  // namespace dgi
+// in-degrees of the sample, as int64, at out[1 + v] (out[0] = 0): the input of the device prefix sum
+template <typename IdxT>
+__global__ void min_degree_kernel(const IdxT* indptr, int64_t N, int fanout, int64_t* out) {
+    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v <= N; v += (int64_t)gridDim.x * blockDim.x) {
+        if (v == N) { out[0] = 0; continue; }
+        const int64_t d = (int64_t)indptr[v + 1] - (int64_t)indptr[v];
+        out[v + 1] = d < fanout ? d : fanout;
+    }
+}
 
-using namespace dgi;
-
-extern "C" dgi_status_t dgi_graph_sample(const dgi_graph_t* g, int32_t fanout, uint64_t seed, int32_t layer, void* hip_stream,
-                                         dgi_graph_t** g_out) {
-    DGI_REQUIRE(g && g_out, DGI_ERR_INVALID_ARG, "graph_sample: NULL argument");
-    *g_out = nullptr;
-    DGI_REQUIRE(fanout >= 1, DGI_ERR_INVALID_ARG, "graph_sample: fan-out must be at least 1");
-    DGI_REQUIRE(layer >= 0 && layer < DGI_MAX_LAYERS, DGI_ERR_INVALID_ARG, "graph_sample: bad layer index");
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+// The sampled graph of one layer.  With `cached` the host indptr vector and the device arrays come from (and stay
+// in) g's handle and the new handle borrows the device arrays; the caller must hold g->hs_mutex and hand the host
+// vector back (g->ss_ip = std::move(sampled->h_indptr)) before freeing the sampled handle.
+dgi_status_t sample_graph(const dgi_graph* g, int fanout, uint64_t seed, int layer, bool cached, hipStream_t s, dgi_graph_t** g_out) {
     const int64_t N = g->N;
-    // indptr of the sample = prefix sums of min(degree, fanout): on the host in parallel chunks (the handle keeps a
-    // host copy for batch planning), uploaded from there
-    std::vector<int64_t> ip((size_t)N + 1);
+    // host indptr of the sample = prefix sums of min(degree, fanout), in parallel chunks (the handle keeps a host copy
+    // for batch planning); the device copy is computed on the device, so nothing crosses the host link
+    std::vector<int64_t> ip;
+    if (cached) ip = std::move(g->ss_ip);
+    ip.resize((size_t)N + 1);
     ip[0] = 0;
     {
         const int T = (int)std::max<int64_t>(1, std::min<int64_t>({(int64_t)std::thread::hardware_concurrency(), (int64_t)16, N / 65536 + 1}));
@@ -143,28 +150,71 @@ extern "C" dgi_status_t dgi_graph_sample(const dgi_graph_t* g, int32_t fanout, u
         });
     }
     const int64_t Es = ip[N];
-    int64_t* d_ip = nullptr;
-    int32_t* d_ix = nullptr;
-    DGI_HIP(hipMalloc(reinterpret_cast<void**>(&d_ip), (size_t)(N + 1) * 8));
-    hipError_t err = hipMalloc(reinterpret_cast<void**>(&d_ix), std::max<size_t>((size_t)Es * 4, 16));
-    auto fail = [&](dgi_status_t st) { (void)hipFree(d_ip); (void)hipFree(d_ix); return st; };
-    if (err != hipSuccess) { set_error("graph_sample: %s", hipGetErrorString(err)); return fail(err == hipErrorOutOfMemory ? DGI_ERR_OOM : DGI_ERR_DEVICE); }
-    err = hipMemcpyAsync(d_ip, ip.data(), (size_t)(N + 1) * 8, hipMemcpyHostToDevice, s);
-    if (err == hipSuccess && N > 0) {
-        const unsigned grid = (unsigned)std::min<int64_t>(N, (int64_t)1 << 22);
-        const uint64_t key_base = (uint64_t)layer * (uint64_t)g->E + 1ull;
-        if (g->itype == DGI_I64)
-            hipLaunchKernelGGL(sample_rows_kernel<int64_t>, dim3(grid), dim3(64), 0, s, (const int64_t*)g->d_indptr, g->d_indices, N, (int)fanout, seed,
-                               key_base, d_ip, d_ix);
-        else
-            hipLaunchKernelGGL(sample_rows_kernel<int32_t>, dim3(grid), dim3(64), 0, s, (const int32_t*)g->d_indptr, g->d_indices, N, (int)fanout, seed,
-                               key_base, d_ip, d_ix);
-        err = hipGetLastError();
+    auto give_back = [&]() { if (cached) g->ss_ip = std::move(ip); };
+    int64_t* d_ip = cached ? g->ss_d_ip : nullptr;
+    int32_t* d_ix = cached ? g->ss_d_ix : nullptr;
+    void* d_tmp = nullptr;
+    auto fail = [&](dgi_status_t st) {
+        (void)hipFree(d_tmp);
+        if (!cached) { (void)hipFree(d_ip); (void)hipFree(d_ix); }
+        give_back();
+        return st;
+    };
+    hipError_t err = hipSuccess;
+    if (!d_ip) {
+        err = hipMalloc(reinterpret_cast<void**>(&d_ip), (size_t)(N + 1) * 8);
+        if (err == hipSuccess && cached) g->ss_d_ip = d_ip;
     }
-    if (err == hipSuccess) err = hipStreamSynchronize(s);  // `ip` moves into the handle next
+    if (err == hipSuccess && (!d_ix || (cached && g->ss_ix_cap < (uint64_t)Es))) {
+        if (cached) { (void)hipFree(g->ss_d_ix); g->ss_d_ix = nullptr; g->ss_ix_cap = 0; }
+        err = hipMalloc(reinterpret_cast<void**>(&d_ix), std::max<size_t>((size_t)Es * 4, 16));
+        if (err == hipSuccess && cached) { g->ss_d_ix = d_ix; g->ss_ix_cap = (uint64_t)std::max<int64_t>(Es, 4); }
+    }
+    size_t tmp_bytes = 0;
+    if (err == hipSuccess) err = hipcub::DeviceScan::InclusiveSum(nullptr, tmp_bytes, d_ip, d_ip, (int)(N + 1), s);
+    if (err == hipSuccess) err = hipMalloc(&d_tmp, std::max<size_t>(tmp_bytes, 16));
+    if (err != hipSuccess) { set_error("graph_sample: %s", hipGetErrorString(err)); return fail(err == hipErrorOutOfMemory ? DGI_ERR_OOM : DGI_ERR_DEVICE); }
+    {
+        const unsigned grid1 = (unsigned)std::min<int64_t>((N + 256) / 256, (int64_t)1 << 20);
+        const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(N, (int64_t)1 << 22));
+        const uint64_t key_base = (uint64_t)layer * (uint64_t)g->E + 1ull;
+        if (g->itype == DGI_I64) {
+            hipLaunchKernelGGL(min_degree_kernel<int64_t>, dim3(grid1), dim3(256), 0, s, (const int64_t*)g->d_indptr, N, fanout, d_ip);
+            err = hipcub::DeviceScan::InclusiveSum(d_tmp, tmp_bytes, d_ip, d_ip, (int)(N + 1), s);
+            if (err == hipSuccess && N > 0)
+                hipLaunchKernelGGL(sample_rows_kernel<int64_t>, dim3(grid), dim3(64), 0, s, (const int64_t*)g->d_indptr, g->d_indices, N, fanout, seed, key_base,
+                                   d_ip, d_ix);
+        } else {
+            hipLaunchKernelGGL(min_degree_kernel<int32_t>, dim3(grid1), dim3(256), 0, s, (const int32_t*)g->d_indptr, N, fanout, d_ip);
+            err = hipcub::DeviceScan::InclusiveSum(d_tmp, tmp_bytes, d_ip, d_ip, (int)(N + 1), s);
+            if (err == hipSuccess && N > 0)
+                hipLaunchKernelGGL(sample_rows_kernel<int32_t>, dim3(grid), dim3(64), 0, s, (const int32_t*)g->d_indptr, g->d_indices, N, fanout, seed, key_base,
+                                   d_ip, d_ix);
+        }
+        if (err == hipSuccess) err = hipGetLastError();
+    }
+    if (err == hipSuccess) err = hipStreamSynchronize(s);
     if (err != hipSuccess) { set_error("graph_sample: %s", hipGetErrorString(err)); return fail(DGI_ERR_DEVICE); }
-    // the handle owns d_ip / d_ix from here on (graph_adopt frees them if it fails)
-    return graph_adopt(N, Es, d_ip, d_ix, std::move(ip), std::min<int64_t>(g->max_in_degree, fanout), s, g_out);
+    (void)hipFree(d_tmp);
+    d_tmp = nullptr;
+    const dgi_status_t st = graph_adopt(N, Es, d_ip, d_ix, std::move(ip), std::min<int64_t>(g->max_in_degree, fanout), !cached, s, g_out);
+    if (st != DGI_OK) return fail(st);  // graph_adopt handed `ip` back
+    return DGI_OK;
+}
+
+}  // namespace
+}  // namespace dgi
+
+using namespace dgi;
+
+extern "C" dgi_status_t dgi_graph_sample(const dgi_graph_t* g, int32_t fanout, uint64_t seed, int32_t layer, void* hip_stream,
+                                         dgi_graph_t** g_out) {
+    DGI_REQUIRE(g && g_out, DGI_ERR_INVALID_ARG, "graph_sample: NULL argument");
+    *g_out = nullptr;
+    DGI_REQUIRE(fanout >= 1, DGI_ERR_INVALID_ARG, "graph_sample: fan-out must be at least 1");
+    DGI_REQUIRE(layer >= 0 && layer < DGI_MAX_LAYERS, DGI_ERR_INVALID_ARG, "graph_sample: bad layer index");
+    DGI_REQUIRE(g->N < (int64_t)INT_MAX - 1, DGI_ERR_UNSUPPORTED, "graph_sample: at most 2^31 - 3 nodes");
+    return sample_graph(g, fanout, seed, layer, false, static_cast<hipStream_t>(hip_stream), g_out);
 }
 
 extern "C" dgi_status_t dgi_infer_sampled(const dgi_graph_t* g, const dgi_layer_t* layers, int32_t num_layers, const void* x, int64_t ld_x,
@@ -175,6 +225,8 @@ extern "C" dgi_status_t dgi_infer_sampled(const dgi_graph_t* g, const dgi_layer_
     dgi_infer_opts_t o{};
     if (opts) o = *opts;
     DGI_REQUIRE(!o.perm_new_of_old && !o.jk_concat, DGI_ERR_UNSUPPORTED, "infer_sampled: permutation and jumping-knowledge options are not supported");
+    DGI_REQUIRE(fanout >= 1, DGI_ERR_INVALID_ARG, "infer_sampled: fan-out must be at least 1");
+    DGI_REQUIRE(g->N < (int64_t)INT_MAX - 1, DGI_ERR_UNSUPPORTED, "infer_sampled: at most 2^31 - 3 nodes");
     o.stats = nullptr;
     for (int l = 1; l < num_layers; ++l) {
         DGI_REQUIRE(layers[l].in_dim == layers[l - 1].out_dim, DGI_ERR_INVALID_ARG, "layer %d: in_dim != previous out_dim", l);
@@ -216,12 +268,13 @@ extern "C" dgi_status_t dgi_infer_sampled(const dgi_graph_t* g, const dgi_layer_
         void* dst = last ? out : hid[l % 2].p;
         const int64_t ld_dst = last ? ld_out : round_up(layers[l].out_dim, 16 / eb);
         dgi_graph_t* gs = nullptr;
-        DGI_TRY(dgi_graph_sample(g, fanout, seed, l, s, &gs));
+        DGI_TRY(sample_graph(g, fanout, seed, l, true, s, &gs));
         gs->ws_ptr = arena.p; gs->ws_bytes = arena.bytes;
         arena.p = nullptr; arena.bytes = 0;
         const dgi_status_t st = dgi_infer(gs, &layers[l], 1, cur, ld_cur, dst, ld_dst, &o, s);  // waits for completion
         arena.p = gs->ws_ptr; arena.bytes = gs->ws_bytes;
         gs->ws_ptr = nullptr; gs->ws_bytes = 0;
+        g->ss_ip = std::move(gs->h_indptr);  // the host vector goes back to the cache; the device arrays were borrowed
         dgi_graph_free(gs);
         DGI_TRY(st);
         cur = dst;
