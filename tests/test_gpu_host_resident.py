@@ -135,6 +135,11 @@ def test_host_resident_bf16_and_argument_checks():
     st = bd.infer_host(g, list(structs), x, out, batch_size=1000, stream_always=True)
     assert st["batches"] == [3, 3]
     assert max_rel_err(out.numpy(), want) <= TOL_BF16
+    # an empty graph is a no-op
+    g0 = bd.graph_load(np.zeros(1, np.int64), np.zeros(0, np.int32))
+    st0 = bd.infer_host(g0, list(structs), torch.empty((0, 64), dtype=torch.bfloat16, pin_memory=True),
+                        torch.empty((0, 24), dtype=torch.float32, pin_memory=True))
+    assert st0["batches"] == [0, 0]
     # pageable host memory and device memory are refused
     with pytest.raises(bd.DgiError) as ei:
         bd.infer_host(g, list(structs), X.clone(), out)

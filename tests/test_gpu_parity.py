@@ -452,3 +452,14 @@ def test_fused_layer_with_eight_or_more_column_blocks(storage, dims, agg):
     got = gpu_layer(g, layer, X, storage=storage)
     want = oracle.layer_forward(indptr, indices, layer, X)
     assert max_rel_err(got, want) <= (TOL_BF16 if storage == "bf16" else TOL_F32)
+
+
+@pytest.mark.parametrize("k,scale", [(2, 0.05), (4, 0.002), (5, 0.02)])
+def test_device_side_input_generation_is_reproducible(k, scale):
+    # the seeded generators must give the same graph and features on every run, also when they run on the GPU
+    a = configs.make_config(k, scale=scale, device="cuda")
+    b = configs.make_config(k, scale=scale, device="cuda")
+    assert torch.equal(a["indptr"], b["indptr"]) and torch.equal(a["indices"], b["indices"])
+    assert torch.equal(a["x"], b["x"])
+    for La, Lb in zip(a["layers"], b["layers"]):
+        assert torch.equal(La["W_neigh"], Lb["W_neigh"])

@@ -39,6 +39,15 @@ def test_device_sampler_equals_the_oracle_sampler(itype):
         bd.graph_sample(g, 0, 1, 0)
     g0 = bd.graph_load(np.zeros(1, np.int64), np.zeros(0, np.int32))
     assert bd.graph_sample(g0, 10, 1, 0).info()["num_nodes"] == 0
+    # a graph without edges, and sampling inference on an empty graph
+    g1 = bd.graph_load(np.zeros(6, np.int64), np.zeros(0, np.int32))
+    assert bd.graph_sample(g1, 10, 1, 0).info()["num_edges"] == 0
+    ls, keep = bd.make_layer(dict(agg="mean", act="none", W_self=rnd((4, 4), 1), W_neigh=rnd((4, 4), 2), bias=None))
+    bd.infer_sampled(g0, [ls], torch.empty(0, 4, device="cuda"), torch.empty(0, 4, device="cuda"), 10, 1)
+    x1 = torch.ones(5, 4, device="cuda")
+    o1 = torch.empty(5, 4, device="cuda")
+    bd.infer_sampled(g1, [ls], x1, o1, 10, 1)   # no neighbours: out = x W_self
+    assert np.allclose(o1.cpu().numpy(), np.ones((5, 4), np.float32) @ rnd((4, 4), 1), rtol=1e-5)
 
 
 @pytest.mark.parametrize("kind", ["sage", "gcn", "gat"])
