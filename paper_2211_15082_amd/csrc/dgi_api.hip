@@ -171,10 +171,11 @@ struct KernelTimer;  // defined below
 
 // One batch of destination rows [b,e): the body of the inner loop of Algorithm 2.
 // in_prescaled: the rows of h_in already carry the GCN source factor d_out(u)^-1/2; out_scale: per-node factor
-// to fold into this layer's output rows (the next GCN layer's source factor), or NULL.
+// to fold into this layer's output rows (the next GCN layer's source factor), or NULL.  h_out's first row is
+// destination row out_base (0: the whole output matrix; b: a buffer that holds just this batch).
 dgi_status_t run_batch(const dgi_graph* g, const dgi_layer_t* L, const LayerPlan& P, const void* h_in, int64_t ld_in,
                        void* h_out, int64_t ld_out, int64_t b, int64_t e, const void* Wt, const void* Z, void* temp,
-                       hipStream_t s, KernelTimer* timer, bool in_prescaled, const float* out_scale);
+                       hipStream_t s, KernelTimer* timer, bool in_prescaled, const float* out_scale, int64_t out_base = 0);
 
 // HIP-event timing of kernel classes on the caller's stream.
 struct KernelTimer {
@@ -198,7 +199,7 @@ enum { SPAN_AGG = 0, SPAN_GEMM = 1, SPAN_LAYER = 2, SPAN_TOTAL = 3, SPAN_HUB = 4
 
 dgi_status_t run_batch(const dgi_graph* g, const dgi_layer_t* L, const LayerPlan& P, const void* h_in, int64_t ld_in,
                        void* h_out, int64_t ld_out, int64_t b, int64_t e, const void* Wt, const void* Z, void* temp,
-                       hipStream_t s, KernelTimer* timer, bool in_prescaled, const float* out_scale) {
+                       hipStream_t s, KernelTimer* timer, bool in_prescaled, const float* out_scale, int64_t out_base) {
     if (e <= b) return DGI_OK;
     const int ob = elem_bytes(L->out_dtype);
     const int mode = (P.mode == MODE_GCN && in_prescaled) ? (int)MODE_GCN_PRE : P.mode;
@@ -206,7 +207,7 @@ dgi_status_t run_batch(const dgi_graph* g, const dgi_layer_t* L, const LayerPlan
         GatArgs a;
         a.g = g; a.Zx = (const float*)Z; a.ld_z = P.z_ld; a.heads = L->heads; a.head_dim = L->out_dim / L->heads;
         a.attn_slope = L->attn_slope;
-        a.out = (char*)h_out + b * ld_out * ob; a.ld_out = ld_out; a.out_row0 = b; a.out_dtype = L->out_dtype;
+        a.out = (char*)h_out + (b - out_base) * ld_out * ob; a.ld_out = ld_out; a.out_row0 = b; a.out_dtype = L->out_dtype;
         a.bias = L->bias; a.act = L->act; a.act_slope = L->act_slope; a.row_begin = b; a.row_end = e;
         if (timer) DGI_TRY(timer->begin(SPAN_AGG));
         DGI_TRY(launch_gat(a, s));
@@ -221,7 +222,7 @@ dgi_status_t run_batch(const dgi_graph* g, const dgi_layer_t* L, const LayerPlan
         const int zb = elem_bytes(P.z_dtype);
         a.S = (const char*)Z + (int64_t)P.z_neigh_col * zb; a.ld_s = P.z_ld; a.s_dtype = P.z_dtype; a.width = L->out_dim;
         a.self = P.has_self ? Z : nullptr; a.ld_self = P.z_ld;
-        a.out = (char*)h_out + b * ld_out * ob; a.ld_out = ld_out; a.out_row0 = b; a.out_dtype = L->out_dtype;
+        a.out = (char*)h_out + (b - out_base) * ld_out * ob; a.ld_out = ld_out; a.out_row0 = b; a.out_dtype = L->out_dtype;
         a.bias = L->bias; a.act = L->act; a.act_slope = L->act_slope; a.out_scale = out_scale;
         if (timer) DGI_TRY(timer->begin(SPAN_AGG));
         DGI_TRY(launch_aggregate(a, 0, s));
@@ -233,7 +234,7 @@ dgi_status_t run_batch(const dgi_graph* g, const dgi_layer_t* L, const LayerPlan
         fa.g = g; fa.mode = mode; fa.H = h_in; fa.ld_h = ld_in; fa.dtype = L->feat_dtype; fa.K = L->in_dim;
         fa.Wt = Wt; fa.ldw = P.ldw; fa.K1p = P.K1p; fa.has_self = P.has_self; fa.N = L->out_dim;
         fa.bias = L->bias; fa.act = L->act; fa.act_slope = L->act_slope; fa.out_scale = out_scale;
-        fa.out = (char*)h_out + b * ld_out * ob; fa.ld_out = ld_out; fa.out_row0 = b; fa.out_dtype = L->out_dtype;
+        fa.out = (char*)h_out + (b - out_base) * ld_out * ob; fa.ld_out = ld_out; fa.out_row0 = b; fa.out_dtype = L->out_dtype;
         fa.row_begin = b; fa.row_end = e;
         fa.temp = fused_temp_bytes(g, b, e, L->in_dim) ? temp : nullptr;
         if (fa.temp) {
@@ -263,7 +264,7 @@ dgi_status_t run_batch(const dgi_graph* g, const dgi_layer_t* L, const LayerPlan
     }
     ga.Wt = Wt; ga.ldw = P.ldw; ga.K1p = P.K1p;
     ga.bias = L->bias; ga.act = L->act; ga.act_slope = L->act_slope;
-    ga.Y = (char*)h_out + b * ld_out * ob; ga.ld_y = ld_out; ga.out_dtype = L->out_dtype;
+    ga.Y = (char*)h_out + (b - out_base) * ld_out * ob; ga.ld_y = ld_out; ga.out_dtype = L->out_dtype;
     ga.M = e - b; ga.Nout = L->out_dim;
     ga.out_scale = out_scale; ga.row0 = b;
     if (timer) DGI_TRY(timer->begin(SPAN_GEMM));
@@ -351,9 +352,8 @@ extern "C" dgi_status_t dgi_layer_workspace_bytes(const dgi_graph_t* g, const dg
     return DGI_OK;
 }
 
-extern "C" dgi_status_t dgi_layer_forward(const dgi_graph_t* g, const dgi_layer_t* layer, const void* h_in, int64_t ld_in,
-                                          void* h_out, int64_t ld_out, int64_t dst_begin, int64_t dst_end, void* workspace,
-                                          uint64_t workspace_bytes, void* hip_stream) {
+dgi_status_t dgi::layer_forward_rows(const dgi_graph* g, const dgi_layer_t* layer, const void* h_in, int64_t ld_in, void* h_out, int64_t ld_out,
+                                     int64_t out_base, int64_t dst_begin, int64_t dst_end, void* workspace, uint64_t workspace_bytes, hipStream_t s) {
     DGI_REQUIRE(g != nullptr, DGI_ERR_INVALID_ARG, "graph is NULL");
     LayerPlan P;
     DGI_TRY(plan_layer(g, layer, h_in, ld_in, &P));
@@ -366,11 +366,17 @@ extern "C" dgi_status_t dgi_layer_forward(const dgi_graph_t* g, const dgi_layer_
     DGI_REQUIRE(workspace != nullptr && workspace_bytes >= f.total, DGI_ERR_INVALID_ARG,
                 "workspace too small: %llu bytes given, %llu needed", (unsigned long long)workspace_bytes, (unsigned long long)f.total);
     DGI_REQUIRE((uintptr_t)workspace % 256 == 0, DGI_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
     char* ws = static_cast<char*>(workspace);
     DGI_TRY(prepare_weights(layer, P, ws + f.wt_off, s));
     if (P.transform_first) DGI_TRY(run_transform(layer, P, h_in, ld_in, ws + f.wt_off, ws + f.z_off, 0, g->N, s));
-    return run_batch(g, layer, P, h_in, ld_in, h_out, ld_out, dst_begin, dst_end, ws + f.wt_off, ws + f.z_off, ws + f.temp_off, s, nullptr, false, nullptr);
+    return run_batch(g, layer, P, h_in, ld_in, h_out, ld_out, dst_begin, dst_end, ws + f.wt_off, ws + f.z_off, ws + f.temp_off, s, nullptr, false, nullptr,
+                     out_base);
+}
+
+extern "C" dgi_status_t dgi_layer_forward(const dgi_graph_t* g, const dgi_layer_t* layer, const void* h_in, int64_t ld_in,
+                                          void* h_out, int64_t ld_out, int64_t dst_begin, int64_t dst_end, void* workspace,
+                                          uint64_t workspace_bytes, void* hip_stream) {
+    return layer_forward_rows(g, layer, h_in, ld_in, h_out, ld_out, 0, dst_begin, dst_end, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
 extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layers, int32_t num_layers, const void* x,

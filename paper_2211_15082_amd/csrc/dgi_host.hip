@@ -273,10 +273,9 @@ dgi_status_t infer_host(const dgi_graph* g, const dgi_layer_t* layers, int32_t L
             // ---- (ii) rows of the input set, read from host memory by the device --------------------------------------
             DGI_TRY(launch_permute_rows(cur, ld_cur, A + o_x, ld_xs, n_sub, Ly.in_dim, xb, (const int32_t*)(A + o_U), true, sa));
             DGI_HIP(hipEventRecord(S.ev[1], sa));
-            // ---- (iii) the layer on the sub-problem, on the second stream; output row v lands at (v - lb) ----------------
+            // ---- (iii) the layer on the sub-problem, on the second stream; the output buffer starts at row lb ----------------
             DGI_HIP(hipStreamWaitEvent(sb, S.ev[1], 0));
-            char* y_base = A + o_y - (int64_t)lb * ld_os * yb;
-            DGI_TRY(dgi_layer_forward(S.sub.g, &Ly, A + o_x, ld_xs, y_base, ld_os, lb, lb + rows, A + o_ws, ws_bytes, sb));
+            DGI_TRY(layer_forward_rows(S.sub.g, &Ly, A + o_x, ld_xs, A + o_y, ld_os, lb, lb, lb + rows, A + o_ws, ws_bytes, sb));
             DGI_HIP(hipEventRecord(S.ev[2], sb));
             // ---- (iv) dump the batch's rows ------------------------------------------------------------------------------
             DGI_TRY(store_rows(A + o_y, ld_os, dst_host + (size_t)b * ld_dst * yb, dst_dev + (size_t)b * ld_dst * yb, ld_dst, rows, Ly.out_dim, yb, sb));

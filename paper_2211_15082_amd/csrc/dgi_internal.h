@@ -202,6 +202,10 @@ dgi_status_t reorder_permutation(int64_t N, const int64_t* indptr, const int32_t
 dgi_status_t graph_adopt(int64_t N, int64_t E, int64_t* d_indptr, int32_t* d_indices, std::vector<int64_t>&& h_indptr, int64_t max_degree,
                          bool own_arrays, hipStream_t stream, dgi_graph_t** out);
 
+// dgi_layer_forward with an output buffer whose first row is destination row out_base (0 = the whole matrix)
+dgi_status_t layer_forward_rows(const dgi_graph* g, const dgi_layer_t* layer, const void* h_in, int64_t ld_in, void* h_out, int64_t ld_out,
+                                int64_t out_base, int64_t dst_begin, int64_t dst_end, void* workspace, uint64_t workspace_bytes, hipStream_t s);
+
 // frees dgi_infer's cached arena (takes ws_mutex; dgi_infer_host calls it while holding hs_mutex)
 dgi_status_t release_infer_arena(const dgi_graph* g);
 
