@@ -47,6 +47,7 @@ struct AggParams {
     int64_t out_row0;
     int out_bf16;
     int out_vec_ok;
+    int self_vec_ok;       // self rows can be read in 16-byte pieces
     const void* self;
     int64_t ld_self;
     const float* bias;
@@ -235,6 +236,57 @@ __device__ __forceinline__ void finish_store(const AggParams& p, int64_t v, int6
     else static_cast<float*>(p.out)[o] = val;
 }
 
+// The same epilogue for the VEC consecutive elements a lane owns (columns col .. col+VEC-1 of row v), stored as one
+// 16-byte piece when the output layout allows it: element-wise 2- or 4-byte stores of a row reach HBM as partial
+// lines (measured: three times the bytes of the output matrix).  Arithmetic per element is that of finish_store.
+template <typename T>
+__device__ __forceinline__ void store_chunk(const AggParams& p, int64_t v, int64_t out_row, int col, const float* sum, float scale) {
+    constexpr int VEC = Row<T>::VEC;
+    if (!(p.out_vec_ok && col + VEC <= p.width)) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i)
+            if (col + i < p.width) finish_store<T>(p, v, out_row, col + i, sum[i], scale);
+        return;
+    }
+    float val[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) val[i] = sum[i] * scale;
+    if (p.self) {
+        const T* srow = static_cast<const T*>(p.self) + v * p.ld_self + col;
+        float f[VEC];
+        if (p.self_vec_ok) {
+            Row<T>::unpack(*reinterpret_cast<const typename Row<T>::Raw*>(srow), f);
+        } else {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) f[i] = Row<T>::one(srow + i);
+        }
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) val[i] += f[i];
+    }
+    if (p.bias) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) val[i] += p.bias[col + i];
+    }
+    const float os = p.out_scale ? p.out_scale[v] : 1.f;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+        val[i] = activate(val[i], p.act, p.act_slope);
+        if (p.out_scale) val[i] *= os;
+    }
+    const int64_t o = out_row * p.ld_out + col;
+    if (p.out_bf16) {
+        uint32_t w[(VEC + 1) / 2];
+#pragma unroll
+        for (int i = 0; i < VEC / 2; ++i) w[i] = (uint32_t)float_to_bf16(val[2 * i]) | ((uint32_t)float_to_bf16(val[2 * i + 1]) << 16);
+        // VEC bf16 values are 8 bytes (fp32 sources) or 16 bytes (bf16 sources)
+        if constexpr (VEC == 4) *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + o) = make_uint2(w[0], w[1]);
+        else *reinterpret_cast<uint4*>(static_cast<uint16_t*>(p.out) + o) = make_uint4(w[0], w[1], w[(VEC > 4) ? 2 : 0], w[(VEC > 4) ? 3 : 0]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < VEC; i += 4) *reinterpret_cast<float4*>(static_cast<float*>(p.out) + o + i) = make_float4(val[i], val[i + 1], val[i + 2], val[i + 3]);
+    }
+}
+
 template <int MODE, typename IdxT>
 __device__ __forceinline__ float row_scale(const AggParams& p, int64_t v, IdxT deg) {
     if (MODE == MODE_MEAN) return deg > 0 ? 1.0f / (float)deg : 0.f;
@@ -319,30 +371,7 @@ __device__ __forceinline__ void rows_tile_grouped(const AggParams& p, int64_t bi
             }
         }
     }
-    if (mine && col_ok) {
-        const float scale = row_scale<MODE, int64_t>(p, v, deg);
-        const bool plain = !p.self && !p.bias && p.act == DGI_ACT_NONE && !p.out_scale;
-        if (plain && p.out_vec_ok && col + VEC <= p.width) {
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) acc[i] *= scale;
-            const int64_t o = (v - p.out_row0) * p.ld_out + col;
-            if (p.out_bf16) {
-                uint32_t w[VEC / 2];
-#pragma unroll
-                for (int i = 0; i < VEC / 2; ++i) w[i] = (uint32_t)float_to_bf16(acc[2 * i]) | ((uint32_t)float_to_bf16(acc[2 * i + 1]) << 16);
-#pragma unroll
-                for (int i = 0; i < VEC / 2; i += 2) *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + o + 2 * i) = make_uint2(w[i], w[i + 1]);
-            } else {
-#pragma unroll
-                for (int i = 0; i < VEC; i += 4)
-                    *reinterpret_cast<float4*>(static_cast<float*>(p.out) + o + i) = make_float4(acc[i], acc[i + 1], acc[i + 2], acc[i + 3]);
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < VEC; ++i)
-                if (col + i < p.width) finish_store<T>(p, v, v - p.out_row0, col + i, acc[i], scale);
-        }
-    }
+    if (mine && col_ok) store_chunk<T>(p, v, v - p.out_row0, col, acc, row_scale<MODE, int64_t>(p, v, deg));
     // ---- phase B: the wavefront's long rows, all lane groups on one row at a time ------------------------------
     IdxT bound[RPW + 1];
 #pragma unroll
@@ -361,11 +390,7 @@ __device__ __forceinline__ void rows_tile_grouped(const AggParams& p, int64_t bi
         for (int i = 0; i < VEC; ++i) a2[i] = 0.f;
         gather_range<T, G, MODE, UNROLL>(p, (int64_t)rb, (int64_t)re, lane, 0, a2);
         combine_groups<G, VEC>(a2);
-        if (sub == 0 && col_ok) {
-#pragma unroll
-            for (int i = 0; i < VEC; ++i)
-                if (col + i < p.width) finish_store<T>(p, vr, vr - p.out_row0, col + i, a2[i], scale);
-        }
+        if (sub == 0 && col_ok) store_chunk<T>(p, vr, vr - p.out_row0, col, a2, scale);
     }
 }
 
@@ -410,30 +435,7 @@ __device__ __forceinline__ void rows_tile(const AggParams& p, int64_t bid) {
             gather_range<T, G, MODE, UNROLL>(p, (int64_t)eb, (int64_t)ee, lane, col0, acc, true, cur);
             combine_groups<G, VEC>(acc);
             const int c = col0 + gl * VEC;
-            if (sub == 0 && c < p.width) {
-                const bool plain = !p.self && !p.bias && p.act == DGI_ACT_NONE && !p.out_scale;
-                if (plain && p.out_vec_ok && c + VEC <= p.width) {
-                    const int64_t o = (v - p.out_row0) * p.ld_out + c;
-                    if (p.out_bf16) {
-                        uint32_t w[VEC / 2];
-#pragma unroll
-                        for (int i = 0; i < VEC / 2; ++i)
-                            w[i] = (uint32_t)float_to_bf16(acc[2 * i] * scale) | ((uint32_t)float_to_bf16(acc[2 * i + 1] * scale) << 16);
-#pragma unroll
-                        for (int i = 0; i < VEC / 2; i += 2)
-                            *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + o + 2 * i) = make_uint2(w[i], w[i + 1]);
-                    } else {
-#pragma unroll
-                        for (int i = 0; i < VEC; i += 4)
-                            *reinterpret_cast<float4*>(static_cast<float*>(p.out) + o + i) =
-                                make_float4(acc[i] * scale, acc[i + 1] * scale, acc[i + 2] * scale, acc[i + 3] * scale);
-                    }
-                } else {
-#pragma unroll
-                    for (int i = 0; i < VEC; ++i)
-                        if (c + i < p.width) finish_store<T>(p, v, v - p.out_row0, c + i, acc[i], scale);
-                }
-            }
+            if (sub == 0 && c < p.width) store_chunk<T>(p, v, v - p.out_row0, c, acc, scale);
         }
     }
 }
@@ -966,6 +968,7 @@ dgi_status_t launch_aggregate(const AggArgs& a, int stage, hipStream_t stream) {
     const bool fast = ((uintptr_t)a.S % 16 == 0) && ((a.ld_s * sbytes) % 16 == 0) &&
                       (round_up(a.width, 16 / sbytes) <= a.ld_s);
     p.out_vec_ok = ((uintptr_t)a.out % 16 == 0) && ((a.ld_out * obytes) % 16 == 0);
+    p.self_vec_ok = a.self && ((uintptr_t)a.self % 16 == 0) && ((a.ld_self * sbytes) % 16 == 0);
     const bool i64 = g->itype == DGI_I64;
     if (a.s_dtype == DGI_BF16) {
         return i64 ? dispatch_mode<uint16_t, int64_t>(p, g, a.mode, fast, stage, stream)
