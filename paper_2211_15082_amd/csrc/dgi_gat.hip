@@ -28,6 +28,7 @@ struct GatParams {
     int64_t ld_out;
     int64_t out_row0;
     int out_bf16;
+    int out_vec_ok;  // output rows can be written in 16-byte (fp32) / 8-byte (bf16) pieces of 4 columns
     const float* bias;
     int act;
     float act_slope;
@@ -40,6 +41,30 @@ __device__ __forceinline__ void store_out(const GatParams& p, int64_t v, int c, 
     const int64_t o = (v - p.out_row0) * p.ld_out + c;
     if (p.out_bf16) static_cast<uint16_t*>(p.out)[o] = float_to_bf16(val);
     else static_cast<float*>(p.out)[o] = val;
+}
+
+// the 4 consecutive columns a lane owns, as one store where the layout allows it
+__device__ __forceinline__ void store_out4(const GatParams& p, int64_t v, int col, const float* a, float inv) {
+    if (!(p.out_vec_ok && col + 4 <= p.HF)) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (col + i < p.HF) store_out(p, v, col + i, a[i] * inv);
+        return;
+    }
+    float val[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        val[i] = a[i] * inv;
+        if (p.bias) val[i] += p.bias[col + i];
+        val[i] = activate(val[i], p.act, p.act_slope);
+    }
+    const int64_t o = (v - p.out_row0) * p.ld_out + col;
+    if (p.out_bf16)
+        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + o) =
+            make_uint2((uint32_t)float_to_bf16(val[0]) | ((uint32_t)float_to_bf16(val[1]) << 16),
+                       (uint32_t)float_to_bf16(val[2]) | ((uint32_t)float_to_bf16(val[3]) << 16));
+    else
+        *reinterpret_cast<float4*>(static_cast<float*>(p.out) + o) = make_float4(val[0], val[1], val[2], val[3]);
 }
 
 // Requires: all 4 columns of a lane belong to one head (heads == 1 or F % 4 == 0), 16-byte aligned rows.
@@ -121,10 +146,7 @@ __global__ __launch_bounds__(kWaves * 64) void gat_rows_kernel(GatParams p) {
             m = M;
         }
         if (sub == 0 && col_ok) {
-            const float inv = l > 0.f ? 1.0f / l : 0.f;
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if (col + i < p.HF) store_out(p, v, col + i, acc[i] * inv);
+            store_out4(p, v, col, acc, l > 0.f ? 1.0f / l : 0.f);
         }
     }
 }
@@ -204,6 +226,7 @@ dgi_status_t launch_gat(const GatArgs& a, hipStream_t stream) {
     p.heads = a.heads; p.F = a.head_dim; p.HF = a.heads * a.head_dim;
     p.slope = a.attn_slope;
     p.out = a.out; p.ld_out = a.ld_out; p.out_row0 = a.out_row0; p.out_bf16 = a.out_dtype == DGI_BF16;
+    p.out_vec_ok = ((uintptr_t)a.out % 16 == 0) && ((a.ld_out * (p.out_bf16 ? 2 : 4)) % 16 == 0);
     p.bias = a.bias; p.act = a.act; p.act_slope = a.act_slope;
     p.row_begin = a.row_begin; p.row_end = a.row_end;
     DGI_REQUIRE(a.ld_z >= p.HF + 2 * a.heads, DGI_ERR_INVALID_ARG, "gat: ld_z too small for [z|el|er]");
