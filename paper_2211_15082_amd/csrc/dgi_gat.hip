@@ -7,6 +7,10 @@
 // single sweep: every lane group keeps a running maximum m, a running denominator l and the weighted
 // sum rescaled by exp(m_old - m_new) per block of UNROLL neighbours; the lane groups are merged at the
 // end with the same rule.  Scores are shifted by the running maximum before exp, so nothing overflows.
+// Rows with more than kHubDegree in-edges get a whole workgroup (see gat_rows_kernel), merged in a fixed order,
+// so the result of a row does not depend on scheduling or on the batch it falls in.
+#include <algorithm>
+
 #include "dgi_device.h"
 #include "dgi_internal.h"
 
@@ -33,6 +37,9 @@ struct GatParams {
     int act;
     float act_slope;
     int64_t row_begin, row_end;
+    // rows with more than kHubDegree in-edges inside [row_begin,row_end): hub_rows[hub_begin..hub_end), one workgroup each
+    const int64_t* hub_rows;
+    int64_t hub_begin, hub_end;
 };
 
 __device__ __forceinline__ void store_out(const GatParams& p, int64_t v, int c, float val) {
@@ -67,11 +74,96 @@ __device__ __forceinline__ void store_out4(const GatParams& p, int64_t v, int co
         *reinterpret_cast<float4*>(static_cast<float*>(p.out) + o) = make_float4(val[0], val[1], val[2], val[3]);
 }
 
-// Requires: all 4 columns of a lane belong to one head (heads == 1 or F % 4 == 0), 16-byte aligned rows.
-template <typename IdxT, int G>
-__global__ __launch_bounds__(kWaves * 64) void gat_rows_kernel(GatParams p) {
+// Running softmax state of one lane: maximum score m, denominator l, weighted sum of its 4 columns.
+struct Soft {
+    float m, l, acc[4];
+};
+
+__device__ __forceinline__ void soft_merge(Soft& a, float m2, float l2, const float* acc2) {
+    const float M = fmaxf(a.m, m2);
+    const float x = __expf(a.m - M), y = __expf(m2 - M);
+    a.l = a.l * x + l2 * y;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a.acc[i] = a.acc[i] * x + acc2[i] * y;
+    a.m = M;
+}
+
+// Single sweep with a running maximum over the 64-edge blocks e0 = first, first + step, ... of the list [., ee),
+// lane groups side by side on NSUB neighbours; ends with the lane groups merged (every lane holds the result).
+template <int G>
+__device__ __forceinline__ Soft gat_sweep(const GatParams& p, int64_t first, int64_t ee, int64_t step, int lane, float er, const float* zbase,
+                                         const float* elbase, bool col_ok) {
     constexpr int NSUB = 64 / G;
     constexpr int UNROLL = (G == 64) ? 8 : 4;
+    const int sub = lane / G;
+    Soft st;
+    st.m = kNegBig; st.l = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) st.acc[i] = 0.f;
+    for (int64_t e0 = first; e0 < ee; e0 += step) {
+        const int64_t left = ee - e0;
+        const int cnt = left < 64 ? (int)left : 64;
+        const int my = lane < cnt ? p.indices[e0 + lane] : 0;
+        for (int j = 0; j < cnt; j += NSUB * UNROLL) {
+            float4 z[UNROLL];
+            float sc[UNROLL];
+            bool ok[UNROLL];
+            int64_t off[UNROLL];
+#pragma unroll
+            for (int t = 0; t < UNROLL; ++t) {
+                const int k = j + t * NSUB + sub;
+                ok[t] = k < cnt;
+                const int ks = ok[t] ? k : 0;
+                const int u = (G == 64) ? __builtin_amdgcn_readlane(my, ks) : __shfl(my, ks, 64);
+                off[t] = (int64_t)u * p.ld_z;
+            }
+#pragma unroll
+            for (int t = 0; t < UNROLL; ++t) {
+                sc[t] = elbase[off[t]];
+                z[t] = col_ok ? *reinterpret_cast<const float4*>(zbase + off[t]) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+            float mx = st.m;
+#pragma unroll
+            for (int t = 0; t < UNROLL; ++t) {
+                float s = sc[t] + er;
+                s = s > 0.f ? s : p.slope * s;
+                sc[t] = ok[t] ? s : kNegBig;
+                mx = fmaxf(mx, sc[t]);
+            }
+            const float corr = __expf(st.m - mx);
+            st.l *= corr;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) st.acc[i] *= corr;
+            st.m = mx;
+#pragma unroll
+            for (int t = 0; t < UNROLL; ++t) {
+                const float w = ok[t] ? __expf(sc[t] - mx) : 0.f;
+                st.l += w;
+                st.acc[0] = fmaf(w, z[t].x, st.acc[0]);
+                st.acc[1] = fmaf(w, z[t].y, st.acc[1]);
+                st.acc[2] = fmaf(w, z[t].z, st.acc[2]);
+                st.acc[3] = fmaf(w, z[t].w, st.acc[3]);
+            }
+        }
+    }
+#pragma unroll
+    for (int o = G; o < 64; o <<= 1) {  // merge the lane groups
+        float other[4];
+        const float m2 = __shfl_xor(st.m, o, 64), l2 = __shfl_xor(st.l, o, 64);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) other[i] = __shfl_xor(st.acc[i], o, 64);
+        soft_merge(st, m2, l2, other);
+    }
+    return st;
+}
+
+// Requires: all 4 columns of a lane belong to one head (heads == 1 or F % 4 == 0), 16-byte aligned rows.
+// The first hub_end - hub_begin workgroups take one hub row each (they are the longest work items, so they go
+// first): its four wavefronts sweep interleaved 64-edge blocks of the list and their states are merged in
+// wavefront order through LDS.  The other workgroups take kRowsPerWg consecutive rows, one wavefront per row.
+template <typename IdxT, int G>
+__global__ __launch_bounds__(kWaves * 64) void gat_rows_kernel(GatParams p) {
+    __shared__ float part[kWaves][6][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sub = lane / G, gl = lane % G;
     const int col = gl * 4;
@@ -80,74 +172,37 @@ __global__ __launch_bounds__(kWaves * 64) void gat_rows_kernel(GatParams p) {
     const IdxT* indptr = static_cast<const IdxT*>(p.indptr);
     const float* zbase = p.Zx + col;
     const float* elbase = p.Zx + p.HF + h;
-    const int64_t v0 = p.row_begin + (int64_t)blockIdx.x * kRowsPerWg;
+    const int64_t n_hub = p.hub_end - p.hub_begin;
+    if ((int64_t)blockIdx.x < n_hub) {
+        const int64_t v = p.hub_rows[p.hub_begin + blockIdx.x];
+        const int64_t eb = (int64_t)indptr[v], ee = (int64_t)indptr[v + 1];
+        const float er = p.Zx[v * p.ld_z + p.HF + p.heads + h];
+        Soft st = gat_sweep<G>(p, eb + 64 * wave, ee, 64 * kWaves, lane, er, zbase, elbase, col_ok);
+        part[wave][0][lane] = st.m;
+        part[wave][1][lane] = st.l;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) part[wave][2 + i][lane] = st.acc[i];
+        __syncthreads();
+        if (wave == 0) {
+            for (int w = 1; w < kWaves; ++w) {
+                float other[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) other[i] = part[w][2 + i][lane];
+                soft_merge(st, part[w][0][lane], part[w][1][lane], other);
+            }
+            if (sub == 0 && col_ok) store_out4(p, v, col, st.acc, st.l > 0.f ? 1.0f / st.l : 0.f);
+        }
+        return;
+    }
+    const int64_t v0 = p.row_begin + ((int64_t)blockIdx.x - n_hub) * kRowsPerWg;
     for (int r = wave; r < kRowsPerWg; r += kWaves) {
         const int64_t v = v0 + r;
         if (v >= p.row_end) break;
         const int64_t eb = (int64_t)indptr[v], ee = (int64_t)indptr[v + 1];
+        if (n_hub > 0 && ee - eb > kHubDegree) continue;  // a hub workgroup has it
         const float er = p.Zx[v * p.ld_z + p.HF + p.heads + h];
-        float m = kNegBig, l = 0.f;
-        float acc[4] = {0.f, 0.f, 0.f, 0.f};
-        for (int64_t e0 = eb; e0 < ee; e0 += 64) {
-            const int64_t left = ee - e0;
-            const int cnt = left < 64 ? (int)left : 64;
-            const int my = lane < cnt ? p.indices[e0 + lane] : 0;
-            for (int j = 0; j < cnt; j += NSUB * UNROLL) {
-                float4 z[UNROLL];
-                float sc[UNROLL];
-                bool ok[UNROLL];
-                int64_t off[UNROLL];
-#pragma unroll
-                for (int t = 0; t < UNROLL; ++t) {
-                    const int k = j + t * NSUB + sub;
-                    ok[t] = k < cnt;
-                    const int ks = ok[t] ? k : 0;
-                    const int u = (G == 64) ? __builtin_amdgcn_readlane(my, ks) : __shfl(my, ks, 64);
-                    off[t] = (int64_t)u * p.ld_z;
-                }
-#pragma unroll
-                for (int t = 0; t < UNROLL; ++t) {
-                    sc[t] = elbase[off[t]];
-                    z[t] = col_ok ? *reinterpret_cast<const float4*>(zbase + off[t]) : make_float4(0.f, 0.f, 0.f, 0.f);
-                }
-                float mx = m;
-#pragma unroll
-                for (int t = 0; t < UNROLL; ++t) {
-                    float s = sc[t] + er;
-                    s = s > 0.f ? s : p.slope * s;
-                    sc[t] = ok[t] ? s : kNegBig;
-                    mx = fmaxf(mx, sc[t]);
-                }
-                const float corr = __expf(m - mx);
-                l *= corr;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) acc[i] *= corr;
-                m = mx;
-#pragma unroll
-                for (int t = 0; t < UNROLL; ++t) {
-                    const float w = ok[t] ? __expf(sc[t] - mx) : 0.f;
-                    l += w;
-                    acc[0] = fmaf(w, z[t].x, acc[0]);
-                    acc[1] = fmaf(w, z[t].y, acc[1]);
-                    acc[2] = fmaf(w, z[t].z, acc[2]);
-                    acc[3] = fmaf(w, z[t].w, acc[3]);
-                }
-            }
-        }
-        // merge the lane groups
-#pragma unroll
-        for (int o = G; o < 64; o <<= 1) {
-            const float m2 = __shfl_xor(m, o, 64), l2 = __shfl_xor(l, o, 64);
-            const float M = fmaxf(m, m2);
-            const float a = __expf(m - M), b = __expf(m2 - M);
-            l = l * a + l2 * b;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) acc[i] = acc[i] * a + __shfl_xor(acc[i], o, 64) * b;
-            m = M;
-        }
-        if (sub == 0 && col_ok) {
-            store_out4(p, v, col, acc, l > 0.f ? 1.0f / l : 0.f);
-        }
+        const Soft st = gat_sweep<G>(p, eb, ee, 64, lane, er, zbase, elbase, col_ok);
+        if (sub == 0 && col_ok) store_out4(p, v, col, st.acc, st.l > 0.f ? 1.0f / st.l : 0.f);
     }
 }
 
@@ -184,7 +239,7 @@ __global__ __launch_bounds__(kWaves * 64) void gat_rows_generic_kernel(GatParams
 template <typename IdxT, int G>
 dgi_status_t launch_g(const GatParams& p, hipStream_t stream) {
     const int64_t rows = p.row_end - p.row_begin;
-    const int64_t grid = (rows + kRowsPerWg - 1) / kRowsPerWg;
+    const int64_t grid = (rows + kRowsPerWg - 1) / kRowsPerWg + (p.hub_end - p.hub_begin);
     DGI_REQUIRE(grid * kWaves * 64 < (int64_t)1 << 32, DGI_ERR_INVALID_ARG, "gat: row range too large for one launch");
     hipLaunchKernelGGL((gat_rows_kernel<IdxT, G>), dim3((unsigned)grid), dim3(kWaves * 64), 0, stream, p);
     DGI_HIP(hipGetLastError());
@@ -229,6 +284,12 @@ dgi_status_t launch_gat(const GatArgs& a, hipStream_t stream) {
     p.out_vec_ok = ((uintptr_t)a.out % 16 == 0) && ((a.ld_out * (p.out_bf16 ? 2 : 4)) % 16 == 0);
     p.bias = a.bias; p.act = a.act; p.act_slope = a.act_slope;
     p.row_begin = a.row_begin; p.row_end = a.row_end;
+    {
+        const auto& hr = g->h_hub_rows;
+        p.hub_rows = g->d_hub_rows;
+        p.hub_begin = std::lower_bound(hr.begin(), hr.end(), a.row_begin) - hr.begin();
+        p.hub_end = std::lower_bound(hr.begin(), hr.end(), a.row_end) - hr.begin();
+    }
     DGI_REQUIRE(a.ld_z >= p.HF + 2 * a.heads, DGI_ERR_INVALID_ARG, "gat: ld_z too small for [z|el|er]");
     const bool fast = ((uintptr_t)a.Zx % 16 == 0) && (a.ld_z % 4 == 0) && (a.heads == 1 || a.head_dim % 4 == 0) && p.HF <= 256;
     return g->itype == DGI_I64 ? dispatch<int64_t>(p, fast, stream) : dispatch<int32_t>(p, fast, stream);
