@@ -151,9 +151,16 @@ __device__ __forceinline__ int64_t xcd_tile(int64_t bid) {
 // Adds  sum_{e in [eb,ee)} coef(indices[e]) * S[indices[e], col0 + gl*VEC .. +VEC)  into acc (per lane;
 // the 64/G lane groups hold disjoint subsets of the edges).  When `preloaded` is set, `first_my` holds
 // indices[eb + lane] (0 beyond the row) fetched earlier by the caller.
-template <typename T, int G, int MODE, int UNROLL>
+struct NoOp {
+    __device__ __forceinline__ void operator()() const {}
+};
+
+// `between` is called once per block of UNROLL row loads, right after they have been issued and before their
+// data is needed: independent work placed there overlaps the memory latency (wave-uniform control flow only).
+template <typename T, int G, int MODE, int UNROLL, typename Between = NoOp>
 __device__ __forceinline__ void gather_range(const AggParams& p, int64_t eb, int64_t ee, int lane, int col0,
-                                             float (&acc)[Row<T>::VEC], bool preloaded = false, int first_my = 0) {
+                                             float (&acc)[Row<T>::VEC], bool preloaded = false, int first_my = 0,
+                                             Between&& between = Between()) {
     constexpr int VEC = Row<T>::VEC;
     constexpr int NSUB = 64 / G;
     using Raw = typename Row<T>::Raw;
@@ -190,6 +197,7 @@ __device__ __forceinline__ void gather_range(const AggParams& p, int64_t eb, int
 #pragma unroll
                 for (int t = 0; t < UNROLL; ++t) raw[t] = Row<T>::zero();
             }
+            between();
             // the per-source coefficients are handed out only now, so the row loads above do not wait for them
 #pragma unroll
             for (int t = 0; t < UNROLL; ++t) {
@@ -510,7 +518,8 @@ __device__ __forceinline__ uint4 pack_row_chunk(const float* f) {  // VEC floats
 // LDS; without SL they are read from global memory straight into fragment layout (smaller tile, but every
 // column block re-reads them with 32 cache lines per load instruction).
 template <typename T, typename IdxT, int G, int MODE, int W, bool SL>
-__global__ __launch_bounds__(W * 64) void fused_layer_kernel(FusedParams fp) {
+__global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(W == 8 ? 4 : 1)))  // 8-wavefront form: two workgroups per CU
+void fused_layer_kernel(FusedParams fp) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     T* tile = reinterpret_cast<T*>(lds_raw);
     const AggParams& p = fp.a;
@@ -539,6 +548,58 @@ __global__ __launch_bounds__(W * 64) void fused_layer_kernel(FusedParams fp) {
                 *reinterpret_cast<uint4*>(trow + ch * VEC) =
                     (v < p.row_end && ch * VEC < K) ? *reinterpret_cast<const uint4*>(srow + ch * VEC) : make_uint4(0u, 0u, 0u, 0u);
         }
+    }
+
+    // MFMA fragment layout: lane = (row or column lane % 32, K half lane / 32), 16 bytes of K per lane and step
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int nblk = (fp.N + 31) / 32;
+    const int ksteps = Kp / (2 * VEC);
+    const T* a_lds = tile + lrow * fp.lds_ld + lhalf * VEC;
+    auto mma = [&](floatx16_t& acc, const uint4& a, const uint4& b) {
+        if (sizeof(T) == 4) {
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+        } else {
+            bf16x8_t av, bv;
+            __builtin_memcpy(&av, &a, 16);
+            __builtin_memcpy(&bv, &b, 16);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc, 0, 0, 0);
+        }
+    };
+    // Interleaving (8-wavefront form): the transform of the rows' own features does not depend on the gather, so
+    // each wavefront works through it for its first column block in the shadow of its own row loads: a few MFMA
+    // steps after every block of loads, with the weight fragments of the next steps fetched one block ahead (they
+    // must be issued before the row loads that follow, or waiting for them would wait for those loads too).
+    constexpr bool IL = SL && W == 8;
+    constexpr int UQ = (sizeof(T) == 4 && sizeof(IdxT) == 4) ? 4 : 2;  // what the register budget of two workgroups per CU allows
+    floatx16_t acc0;
+    uint4 bq[UQ];
+    int ksq = 0;
+    const bool own_blk = IL && wave < nblk;
+    const T* w0 = static_cast<const T*>(fp.Wt) + (int64_t)(wave * 32 + lrow < fp.N ? wave * 32 + lrow : fp.N - 1) * fp.ldw + lhalf * VEC;
+    auto fetch_bq = [&]() {
+#pragma unroll
+        for (int u = 0; u < UQ; ++u)
+            bq[u] = (own_blk && ksq + u < ksteps) ? *reinterpret_cast<const uint4*>(w0 + (ksq + u) * 2 * VEC) : make_uint4(0u, 0u, 0u, 0u);
+    };
+    auto self_step = [&]() {
+        if (!own_blk || ksq >= ksteps) return;
+        uint4 a[UQ];
+#pragma unroll
+        for (int u = 0; u < UQ; ++u)
+            a[u] = ksq + u < ksteps ? *reinterpret_cast<const uint4*>(a_lds + (ksq + u) * 2 * VEC) : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+        for (int u = 0; u < UQ; ++u) mma(acc0, a[u], bq[u]);
+        ksq += UQ;
+        fetch_bq();
+    };
+    if (IL) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc0[i] = 0.f;
+        __syncthreads();  // every row's own features are in the tile
+        fetch_bq();
     }
 
     // ---- phase 1: aggregate 32/W rows per wavefront into the tile -------------------------------------
@@ -584,7 +645,8 @@ __global__ __launch_bounds__(W * 64) void fused_layer_kernel(FusedParams fp) {
             float acc[VEC];
 #pragma unroll
             for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
-            gather_range<T, G, MODE, UNROLL>(p, (int64_t)eb, (int64_t)ee, lane, col0, acc, true, cur);
+            if constexpr (IL) gather_range<T, G, MODE, UNROLL>(p, (int64_t)eb, (int64_t)ee, lane, col0, acc, true, cur, self_step);
+            else gather_range<T, G, MODE, UNROLL>(p, (int64_t)eb, (int64_t)ee, lane, col0, acc, true, cur);
             combine_groups<G, VEC>(acc);
             const int c = col0 + gl * VEC;
             if (sub == 0 && c < Kp) {  // columns in [K, Kp) hold zeros (no lane gathered them)
@@ -594,6 +656,9 @@ __global__ __launch_bounds__(W * 64) void fused_layer_kernel(FusedParams fp) {
             }
         }
     }
+    if (IL) {
+        while (own_blk && ksq < ksteps) self_step();  // what the gather did not cover
+    }
     __syncthreads();
 
     // ---- phase 2: out[32 x N] = act([h_v | tile] . Wt^T + bias) on the matrix cores ------------------------
@@ -601,32 +666,20 @@ __global__ __launch_bounds__(W * 64) void fused_layer_kernel(FusedParams fp) {
     // for the rows' own features without SL).  B operand: the packed weight through L2.  A wavefront owns
     // column blocks wave, wave+W, ... one at a time (two per sweep would halve the A reads but costs
     // registers, i.e. gather occupancy: measured slower).
-    const int lrow = lane & 31, lhalf = lane >> 5;
-    const int nblk = (fp.N + 31) / 32;
-    const int ksteps = Kp / (2 * VEC);
     const int64_t vrow = vt + lrow;
-    const T* a_lds = tile + lrow * fp.lds_ld + lhalf * VEC;
     const T* a_self = static_cast<const T*>(p.S) + (vrow < p.row_end ? vrow : p.row_begin) * p.ld_s + lhalf * VEC;
     const bool self_row = fp.has_self && vrow < p.row_end;
-    auto mma = [&](floatx16_t& acc, const uint4& a, const uint4& b) {
-        if (sizeof(T) == 4) {
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
-        } else {
-            bf16x8_t av, bv;
-            __builtin_memcpy(&av, &a, 16);
-            __builtin_memcpy(&bv, &b, 16);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc, 0, 0, 0);
-        }
-    };
     for (int cb = wave; cb < nblk; cb += W) {
         const int n = cb * 32 + lrow;
         const T* w = static_cast<const T*>(fp.Wt) + (int64_t)(n < fp.N ? n : fp.N - 1) * fp.ldw + lhalf * VEC;
         floatx16_t acc;
+        const bool resumed = IL && cb == wave;  // its own-feature half was accumulated during the gather
+        if (resumed) {
+            acc = acc0;
+        } else {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+            for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+        }
         constexpr int U = 4;
         if (!SL && fp.has_self) {  // K block of the rows' own features: columns [0, Kp) of the packed weight
             for (int ks = 0; ks < ksteps; ks += U) {
@@ -646,7 +699,7 @@ __global__ __launch_bounds__(W * 64) void fused_layer_kernel(FusedParams fp) {
         // loop over the whole LDS row [h_v | m_v] against columns [0, 2 Kp) (the host checks K1p == Kp)
         const int lsteps = SL ? 2 * ksteps : ksteps;
         const int wcol = SL ? 0 : fp.K1p;
-        for (int ks = 0; ks < lsteps; ks += U) {
+        for (int ks = resumed ? ksteps : 0; ks < lsteps; ks += U) {
             uint4 a[U], b[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
