@@ -463,3 +463,40 @@ def test_device_side_input_generation_is_reproducible(k, scale):
     assert torch.equal(a["x"], b["x"])
     for La, Lb in zip(a["layers"], b["layers"]):
         assert torch.equal(La["W_neigh"], Lb["W_neigh"])
+
+
+@pytest.mark.parametrize("kind", ["gat", "gcn", "sage_bf16"])
+def test_batch_size_invariance_with_hub_rows(kind):
+    # rows with thousands of in-edges take the chunked / whole-workgroup paths: their results must not depend on
+    # where the batch boundaries fall either (fixed merge order)
+    bd = B()
+    n = 4000
+    indptr, indices = random_csr(n, 6.0, seed=71, hub=(1234, 5000))
+    indptr2, indices2 = random_csr(n, 6.0, seed=71, hub=(3999, 2000))   # a second graph with the hub in the last row
+    X = rnd((n, 64), 1)
+    if kind == "gat":
+        layers = [dict(agg="gat", act="elu", W_neigh=rnd((64, 64), 2, 0.3), heads=4, attn_src=rnd((4, 16), 3, 0.5),
+                       attn_dst=rnd((4, 16), 4, 0.5), bias=rnd((64,), 5)),
+                  dict(agg="gat", act="none", W_neigh=rnd((64, 16), 6, 0.3), heads=1, attn_src=rnd((1, 16), 7, 0.5),
+                       attn_dst=rnd((1, 16), 8, 0.5), bias=None)]
+        storage = "f32"
+    elif kind == "gcn":
+        layers = [dict(agg="gcn", act="relu", W_neigh=rnd((64, 64), 2, 0.2), bias=rnd((64,), 4)),
+                  dict(agg="gcn", act="none", W_neigh=rnd((64, 16), 5, 0.2), bias=None)]
+        storage = "f32"
+    else:
+        W = [torch.from_numpy(rnd(s, i, 0.1)).to(torch.bfloat16).float().numpy() for i, s in enumerate([(64, 64), (64, 64), (64, 16), (64, 16)])]
+        layers = [dict(agg="mean", act="relu", W_self=W[0], W_neigh=W[1], bias=None, out_storage="bf16"),
+                  dict(agg="sum", act="none", W_self=W[2], W_neigh=W[3], bias=None, out_storage="f32")]
+        storage = "bf16"
+    for ip, ix in ((indptr, indices), (indptr2, indices2)):
+        g = bd.graph_load(ip, ix)
+        structs, keep = zip(*[bd.make_layer(L, feat_dtype=storage if i == 0 else L_prev.get("out_storage", "f32"))
+                              for i, (L, L_prev) in enumerate(zip(layers, [None] + layers[:-1]))])
+        x = torch.from_numpy(X).cuda().to(torch.bfloat16 if storage == "bf16" else torch.float32)
+        ref = torch.empty(n, 16, dtype=torch.float32, device="cuda")
+        bd.infer(g, list(structs), x, ref, batch_size=n)
+        for bs in (1, 333, 1235, 0):
+            out = torch.full((n, 16), 777.0, dtype=torch.float32, device="cuda")
+            bd.infer(g, list(structs), x, out, batch_size=bs)
+            assert torch.equal(out, ref), (kind, bs)
