@@ -194,3 +194,11 @@ def test_argument_validation_fails_before_any_device_work():
         B.plan_batch_end(np.zeros(4, np.int64), 3, 5, 1, 1)
     assert ei.value.status == B.ERR_INVALID_ARG and "begin" in str(ei.value)
     assert lib.dgi_reorder_permutation(ctypes.c_int64(2), None, None, 1, ctypes.c_uint64(0), None) == B.ERR_INVALID_ARG
+
+
+def test_public_header_is_plain_c(tmp_path):
+    # the boundary is a C ABI: the header must compile as C99 on its own, with no C++ or HIP types in it
+    import subprocess
+    src = tmp_path / "use.c"
+    src.write_text('#include "dgi.h"\nint main(void) { dgi_infer_opts_t o; dgi_host_stats_t h; (void)o; (void)h; return (int)sizeof(dgi_layer_t) == 0; }\n')
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), "-fsyntax-only", str(src)], check=True)
