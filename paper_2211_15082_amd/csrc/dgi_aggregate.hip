@@ -81,7 +81,8 @@ struct AggParams {
 // The fused layer kernel: gather description + the dense transform that consumes the aggregated tile.
 struct FusedParams {
     AggParams a;           // S = H^{l-1}, width = K; out/self/bias/act unused
-    const void* Wt;        // packed transposed weights [N x ldw]: self block at column 0, neighbour block at K1p
+    const void* Wf;        // packed weights in MFMA fragment order: [column block][K step][lane][16 bytes]; K steps run over
+                           // the self block (columns [0, K1p) of the row-order matrix) and then the neighbour block
     int64_t ldw;
     int K1p;
     int has_self;
@@ -587,11 +588,14 @@ void fused_layer_kernel(FusedParams fp) {
     uint4 bq[UQ];
     int ksq = 0;
     const bool own_blk = IL && wave < nblk;
-    const T* w0 = static_cast<const T*>(fp.Wt) + (int64_t)(wave * 32 + lrow < fp.N ? wave * 32 + lrow : fp.N - 1) * fp.ldw + lhalf * VEC;
+    // B operand of column block cb, K step ks: 64 consecutive 16-byte pieces, one per lane
+    const int64_t ks_tot = fp.ldw / (2 * VEC);
+    const T* wf_lane = static_cast<const T*>(fp.Wf) + lane * VEC;
+    const T* w0 = wf_lane + (int64_t)wave * ks_tot * 64 * VEC;
     auto fetch_bq = [&]() {
 #pragma unroll
         for (int u = 0; u < UQ; ++u)
-            bq[u] = (own_blk && ksq + u < ksteps) ? *reinterpret_cast<const uint4*>(w0 + (ksq + u) * 2 * VEC) : make_uint4(0u, 0u, 0u, 0u);
+            bq[u] = (own_blk && ksq + u < ksteps) ? *reinterpret_cast<const uint4*>(w0 + (int64_t)(ksq + u) * 64 * VEC) : make_uint4(0u, 0u, 0u, 0u);
     };
     auto self_step = [&]() {
         if (!own_blk || ksq >= ksteps) return;
@@ -680,7 +684,7 @@ void fused_layer_kernel(FusedParams fp) {
     const bool self_row = fp.has_self && vrow < p.row_end;
     for (int cb = wave; cb < nblk; cb += W) {
         const int n = cb * 32 + lrow;
-        const T* w = static_cast<const T*>(fp.Wt) + (int64_t)(n < fp.N ? n : fp.N - 1) * fp.ldw + lhalf * VEC;
+        const T* w = wf_lane + (int64_t)cb * ks_tot * 64 * VEC;
         floatx16_t acc;
         const bool resumed = IL && cb == wave;  // its own-feature half was accumulated during the gather
         if (resumed) {
@@ -698,7 +702,7 @@ void fused_layer_kernel(FusedParams fp) {
                     const int k = (ks + u) * 2 * VEC;  // + lhalf * VEC is inside the base pointers
                     const bool in = ks + u < ksteps;
                     a[u] = (in && self_row && k + lhalf * VEC < K) ? *reinterpret_cast<const uint4*>(a_self + k) : make_uint4(0u, 0u, 0u, 0u);
-                    b[u] = in ? *reinterpret_cast<const uint4*>(w + k) : make_uint4(0u, 0u, 0u, 0u);
+                    b[u] = in ? *reinterpret_cast<const uint4*>(w + (int64_t)(ks + u) * 64 * VEC) : make_uint4(0u, 0u, 0u, 0u);
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) mma(acc, a[u], b[u]);
@@ -707,14 +711,14 @@ void fused_layer_kernel(FusedParams fp) {
         // K block of the aggregated neighbourhood: columns [K1p, K1p + Kp) of the packed weight; with SL one
         // loop over the whole LDS row [h_v | m_v] against columns [0, 2 Kp) (the host checks K1p == Kp)
         const int lsteps = SL ? 2 * ksteps : ksteps;
-        const int wcol = SL ? 0 : fp.K1p;
+        const int wks = SL ? 0 : fp.K1p / (2 * VEC);  // first K step of the block in the fragment-order weight
         for (int ks = resumed ? ksteps : 0; ks < lsteps; ks += U) {
             uint4 a[U], b[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int k = (ks + u) * 2 * VEC;
                 const bool in = ks + u < lsteps;
-                b[u] = in ? *reinterpret_cast<const uint4*>(w + wcol + k) : make_uint4(0u, 0u, 0u, 0u);
+                b[u] = in ? *reinterpret_cast<const uint4*>(w + (int64_t)(wks + ks + u) * 64 * VEC) : make_uint4(0u, 0u, 0u, 0u);
                 a[u] = in ? *reinterpret_cast<const uint4*>(a_lds + k) : make_uint4(0u, 0u, 0u, 0u);
             }
 #pragma unroll
@@ -941,7 +945,7 @@ constexpr size_t kFusedMaxLds = 128 * 1024;
 bool fused_supported(const FusedArgs& a) {
     const int eb = a.dtype == DGI_BF16 ? 2 : 4, E = 16 / eb;
     if ((uintptr_t)a.H % 16 || (a.ld_h * eb) % 16 || a.K % E || a.K / E <= 8) return false;
-    if ((uintptr_t)a.Wt % 16 || a.ldw % (2 * E) || a.K1p % (2 * E)) return false;
+    if (a.ldw % (2 * E) || a.K1p % (2 * E)) return false;
     if (a.ldw != a.K1p + round_up(a.K, 2 * E)) return false;
     return (size_t)kFusedRows * (size_t)(round_up(a.K, 2 * E) + E) * eb <= kFusedMaxLds;
 }
@@ -968,7 +972,8 @@ dgi_status_t launch_fused(const FusedArgs& a, int stage, hipStream_t stream) {
     p.row_begin = a.row_begin; p.row_end = a.row_end;
     p.hub_rows = g->d_hub_rows; p.hub_chunk_ptr = g->d_hub_chunk_ptr;
     p.wpad = (int)round_up(a.K, 8);
-    fp.Wt = a.Wt; fp.ldw = a.ldw; fp.K1p = a.K1p; fp.has_self = a.has_self ? 1 : 0; fp.N = a.N;
+    DGI_REQUIRE(a.Wf != nullptr && (uintptr_t)a.Wf % 16 == 0, DGI_ERR_INVALID_ARG, "fused: fragment-order weights missing or misaligned");
+    fp.Wf = a.Wf; fp.ldw = a.ldw; fp.K1p = a.K1p; fp.has_self = a.has_self ? 1 : 0; fp.N = a.N;
     fp.bias = a.bias; fp.act = a.act; fp.act_slope = a.act_slope; fp.out_scale = a.out_scale;
     fp.out = a.out; fp.ld_out = a.ld_out; fp.out_row0 = a.out_row0; fp.out_bf16 = a.out_dtype == DGI_BF16;
     fp.lds_ld = (int)(round_up(a.K, 2 * E) + E);

@@ -38,7 +38,8 @@ struct LayerPlan {
     int K1p = 0;          // column of the packed weight where the second K block starts
     int64_t ldw = 0;      // packed weight leading dimension (elements)
     int w_rows = 0;       // packed weight rows (= GEMM output columns)
-    uint64_t wt_bytes = 0;
+    uint64_t wt_bytes = 0;   // packed weights: row order, then (fused plans) the fragment-order copy at wf_off
+    uint64_t wf_off = 0;
     int mode = MODE_SUM;
     // transform-first: Z = H Wt^T for all nodes
     int z_cols = 0;       // GEMM output columns
@@ -121,6 +122,10 @@ dgi_status_t plan_layer(const dgi_graph* g, const dgi_layer_t* L, const void* h_
         p.fused = want && fused_supported(fa);
     }
     p.wt_bytes = (uint64_t)round_up((int64_t)p.w_rows * p.ldw * p.eb, 256);
+    if (p.fused) {
+        p.wf_off = p.wt_bytes;
+        p.wt_bytes += (uint64_t)round_up((int64_t)fragment_weight_elems(p.w_rows, p.ldw) * p.eb, 256);
+    }
     *P = p;
     return DGI_OK;
 }
@@ -139,7 +144,9 @@ dgi_status_t prepare_weights(const dgi_layer_t* L, const LayerPlan& P, void* Wt,
         return launch_pack_weight(L->W_neigh, L->feat_dtype, L->in_dim, L->out_dim, neigh, P.ldw, 0, s);
     }
     if (P.has_self) DGI_TRY(launch_pack_weight(L->W_self, L->feat_dtype, L->in_dim, L->out_dim, Wt, P.ldw, 0, s));
-    return launch_pack_weight(L->W_neigh, L->feat_dtype, L->in_dim, L->out_dim, Wt, P.ldw, P.K1p, s);
+    DGI_TRY(launch_pack_weight(L->W_neigh, L->feat_dtype, L->in_dim, L->out_dim, Wt, P.ldw, P.K1p, s));
+    if (P.fused) DGI_TRY(launch_pack_fragments(Wt, L->feat_dtype, P.w_rows, P.ldw, (char*)Wt + P.wf_off, s));
+    return DGI_OK;
 }
 
 // Transform-first: Z[r,:] = H[r,:] Wt^T for rows [r0,r1) of the graph.
@@ -233,6 +240,7 @@ dgi_status_t run_batch(const dgi_graph* g, const dgi_layer_t* L, const LayerPlan
         FusedArgs fa;
         fa.g = g; fa.mode = mode; fa.H = h_in; fa.ld_h = ld_in; fa.dtype = L->feat_dtype; fa.K = L->in_dim;
         fa.Wt = Wt; fa.ldw = P.ldw; fa.K1p = P.K1p; fa.has_self = P.has_self; fa.N = L->out_dim;
+        fa.Wf = (const char*)Wt + P.wf_off;
         fa.bias = L->bias; fa.act = L->act; fa.act_slope = L->act_slope; fa.out_scale = out_scale;
         fa.out = (char*)h_out + (b - out_base) * ld_out * ob; fa.ld_out = ld_out; fa.out_row0 = b; fa.out_dtype = L->out_dtype;
         fa.row_begin = b; fa.row_end = e;

@@ -250,6 +250,21 @@ __global__ void pack_weight_kernel(const T* W, int K, int Nout, T* Wt, int64_t l
     Wt[(int64_t)n * ldw + koff + k] = W[i];
 }
 
+template <typename T>
+__global__ void pack_fragments_kernel(const T* Wt, int64_t ldw, int N, int64_t total, T* Wf) {
+    constexpr int VEC = 16 / (int)sizeof(T);
+    const int64_t KS = ldw / (2 * VEC);
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x) {
+        const int i = (int)(idx % VEC);
+        const int lane = (int)((idx / VEC) % 64);
+        const int64_t ks = (idx / (VEC * 64)) % KS;
+        const int64_t cb = idx / (VEC * 64 * KS);
+        const int64_t n = cb * 32 + (lane & 31);
+        const int64_t k = ks * 2 * VEC + (lane >> 5) * VEC + i;
+        Wf[idx] = n < N ? Wt[n * ldw + k] : T(0);
+    }
+}
+
 __global__ void pack_gat_attn_kernel(const float* W, int K, int heads, int F, const float* a_src, const float* a_dst,
                                      float* Wt, int64_t ldw) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -363,6 +378,20 @@ dgi_status_t launch_pack_weight(const void* W, int dtype, int K, int Nout, void*
         hipLaunchKernelGGL(pack_weight_kernel<uint16_t>, dim3(grid), dim3(256), 0, stream, (const uint16_t*)W, K, Nout, (uint16_t*)Wt, ldw, koff);
     else
         hipLaunchKernelGGL(pack_weight_kernel<float>, dim3(grid), dim3(256), 0, stream, (const float*)W, K, Nout, (float*)Wt, ldw, koff);
+    DGI_HIP(hipGetLastError());
+    return DGI_OK;
+}
+
+dgi_status_t launch_pack_fragments(const void* Wt, int dtype, int N, int64_t ldw, void* Wf, hipStream_t stream) {
+    const int64_t total = (int64_t)fragment_weight_elems(N, ldw);
+    if (total == 0) return DGI_OK;
+    const int E = dtype == DGI_BF16 ? 8 : 4;
+    DGI_REQUIRE(ldw % (2 * E) == 0, DGI_ERR_INVALID_ARG, "pack_fragments: leading dimension must be a multiple of the K step");
+    const unsigned grid = (unsigned)std::min<int64_t>((total + 255) / 256, 65536);
+    if (dtype == DGI_BF16)
+        hipLaunchKernelGGL(pack_fragments_kernel<uint16_t>, dim3(grid), dim3(256), 0, stream, (const uint16_t*)Wt, ldw, N, total, (uint16_t*)Wf);
+    else
+        hipLaunchKernelGGL(pack_fragments_kernel<float>, dim3(grid), dim3(256), 0, stream, (const float*)Wt, ldw, N, total, (float*)Wf);
     DGI_HIP(hipGetLastError());
     return DGI_OK;
 }

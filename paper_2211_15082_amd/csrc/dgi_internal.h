@@ -127,12 +127,15 @@ struct FusedArgs {
     int mode = MODE_SUM;
     const void* H = nullptr; int64_t ld_h = 0; int dtype = DGI_F32; int K = 0;
     const void* Wt = nullptr; int64_t ldw = 0; int K1p = 0; bool has_self = false; int N = 0;
+    const void* Wf = nullptr;  // the same weights in MFMA fragment order (launch_pack_fragments); what the kernel reads
     const float* bias = nullptr; int act = DGI_ACT_NONE; float act_slope = 0.f;
     const float* out_scale = nullptr;  // optional per-row factor applied after the activation (indexed by node id)
     void* out = nullptr; int64_t ld_out = 0; int64_t out_row0 = 0; int out_dtype = DGI_F32;
     int64_t row_begin = 0, row_end = 0;
     void* temp = nullptr;  // fused_temp_bytes() of scratch when the range holds hub rows
 };
+// elements of the fragment-order copy of an [N x ldw] packed weight
+inline uint64_t fragment_weight_elems(int N, int64_t ldw) { return (uint64_t)((N + 31) / 32) * 32 * (uint64_t)ldw; }
 bool fused_supported(const FusedArgs& a);
 uint64_t fused_temp_bytes(const dgi_graph* g, int64_t row_begin, int64_t row_end, int K);
 // stage 0: hub pre-pass (no-op without hub rows in the range); stage 1: the fused kernel.  Run 0 then 1.
@@ -174,6 +177,10 @@ dgi_status_t launch_gemm(const GemmArgs& a, hipStream_t stream);
 // Wt[n, koff + k] = W[k, n] for k < K, n < Nout (W row-major [K x Nout]); dtype preserved.
 dgi_status_t launch_pack_weight(const void* W, int dtype, int K, int Nout, void* Wt, int64_t ldw, int koff,
                                 hipStream_t stream);
+// Wf[((cb * KS + ks) * 64 + lane) * VEC + i] = Wt[(cb*32 + lane%32) * ldw + ks*2*VEC + (lane/32)*VEC + i] (0 for rows >= N),
+// VEC = elements per 16 bytes, KS = ldw / (2 VEC): the B operand of one 32-column block and K step is 1 KB of
+// consecutive memory, one 16-byte piece per lane, instead of 32 pieces in 32 different rows.
+dgi_status_t launch_pack_fragments(const void* Wt, int dtype, int N, int64_t ldw, void* Wf, hipStream_t stream);
 // GAT: Wt rows [HF, HF+heads) = W a_src^h, rows [HF+heads, HF+2 heads) = W a_dst^h  (fp32 only).
 dgi_status_t launch_pack_gat_attn(const float* W, int K, int heads, int F, const float* a_src, const float* a_dst,
                                   float* Wt, int64_t ldw, hipStream_t stream);
