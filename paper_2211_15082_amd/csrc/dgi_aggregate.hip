@@ -981,15 +981,15 @@ dgi_status_t launch_fused(const FusedArgs& a, int stage, hipStream_t stream) {
         // Variant 2 (self rows in the tile, 8 wavefronts) when every wavefront gets a column block: phase 2 then
         // reads nothing but the weight from outside the workgroup, and half of it runs inside the gather (measured on
         // 256 -> 256 fp32 GraphSAGE, 20 M nodes, degree 20: 104 ms with variant 0, 121 with 1, 99 with 2).  Narrow
-        // outputs would leave wavefronts idle there; with 4 wavefronts the staged tile pays while it stays small
-        // enough not to cost gather occupancy (same graph: 64->64 25.2 -> 23.8 ms, 128->64 43.6 -> 38.2, 128->128
-        // 46.8 -> 45.4, but 256->128 with its 66 KB tile 74 -> 97 ms).
+        // outputs would leave wavefronts idle there.  With 4 wavefronts the staged tile (variant 1) measured within
+        // the run-to-run spread of variant 0 for K <= 128 and clearly slower beyond (256 -> 128: 74 vs 92-97 ms), so
+        // it is only reachable through DGI_TUNE_FUSED_SELF.
         const int Kp = (int)round_up(a.K, 2 * E);
         static const int forced = [] { const char* e = getenv("DGI_TUNE_FUSED_SELF"); return e ? atoi(e) : -1; }();
-        const size_t staged_tile = (size_t)kFusedRows * (size_t)(2 * Kp + E) * eb;
-        const bool can = a.has_self && a.K1p == Kp && (a.mode == MODE_SUM || a.mode == MODE_MEAN) && staged_tile <= 80 * 1024;
+        const bool can = a.has_self && a.K1p == Kp && (a.mode == MODE_SUM || a.mode == MODE_MEAN) &&
+                         (size_t)kFusedRows * (size_t)(2 * Kp + E) * eb <= 80 * 1024;
         int variant = 0;
-        if (can) variant = forced >= 0 ? forced : ((a.N + 31) / 32 >= 8 ? 2 : (staged_tile <= 36 * 1024 ? 1 : 0));
+        if (can) variant = forced >= 0 ? forced : ((a.N + 31) / 32 >= 8 ? 2 : 0);
         fp.self_lds = variant;
         if (variant) fp.lds_ld = 2 * Kp + E;
     }
