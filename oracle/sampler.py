@@ -33,15 +33,21 @@ def edge_keys(num_edges, seed, layer):
     return (splitmix64_output(seed, k) >> np.uint64(32)).astype(np.uint32)
 
 
-def sample_csr(indptr, indices, fanout, seed, layer):
-    """The sampled graph of one layer: (indptr int64, indices int32)."""
+def sample_csr(indptr, indices, fanout, seed, layer, edge_base=0, total_edges=None):
+    """The sampled graph of one layer: (indptr int64, indices int32).  For a slice of consecutive rows of a larger
+    graph (indptr rebased to 0, its share of indices), pass the position of the slice's first edge in the full
+    `indices` array as `edge_base` and the full edge count as `total_edges`: keys belong to positions in the full
+    graph."""
     indptr = np.asarray(indptr, dtype=np.int64)
     indices = np.asarray(indices, dtype=np.int32)
     n, E = indptr.size - 1, indices.size
     deg = np.diff(indptr)
     row = np.repeat(np.arange(n, dtype=np.int64), deg)
     pos = np.arange(E, dtype=np.int64) - indptr[row]
-    keys = edge_keys(E, seed, layer)
+    E_full = E if total_edges is None else int(total_edges)
+    with np.errstate(over="ignore"):
+        k = np.uint64(layer) * np.uint64(E_full) + np.uint64(edge_base) + np.arange(E, dtype=np.uint64) + np.uint64(1)
+    keys = (splitmix64_output(seed, k) >> np.uint64(32)).astype(np.uint32)
     order = np.lexsort((pos, keys, row))            # by row, then key, then position in the row
     rank = np.arange(E, dtype=np.int64) - indptr[row[order]]
     keep = np.zeros(E, dtype=bool)

@@ -143,3 +143,35 @@ def test_config5_full_size_sampled_rows_and_reordering():
     assert max_rel_err(out3[tt].cpu().numpy(), want) <= 1e-4
     sub = torch.arange(0, cfg["num_nodes"], 4001, device="cuda")
     assert max_rel_err(out3[sub].cpu().numpy(), out[sub].cpu().numpy()) <= 1e-4
+
+
+@pytest.mark.timeout(900)
+def test_full_size_sampler_and_host_resident_path():
+    """Config 2 at full size: the device fan-out sampler against the oracle's on three row slices (keys are positions
+    in the full edge array), and host-resident inference under a 2 GB device budget against the device-resident
+    result that the test above checks against the full oracle."""
+    from oracle import sampler
+    from paper_2211_15082_amd import binding as bd
+    cfg = configs.make_config(2, device="cuda")
+    n = cfg["num_nodes"]
+    g, structs, keep, out, stats = _gpu_infer(cfg)
+    ip = cfg["indptr"].cpu().numpy().astype(np.int64)
+    ix = cfg["indices"].cpu().numpy()
+    gs = bd.graph_sample(g, 10, 2024, 1)
+    sip, six = gs.csr()
+    assert np.array_equal(np.diff(sip), np.minimum(np.diff(ip), 10))
+    hub = int(np.argmax(np.diff(ip)))
+    for a in (0, max(0, hub - 5000), n - 20_000):
+        b = min(n, a + 20_000)
+        want_ip, want_ix = sampler.sample_csr(ip[a:b + 1] - ip[a], ix[ip[a]:ip[b]], 10, 2024, 1, edge_base=int(ip[a]), total_edges=ix.size)
+        assert np.array_equal(sip[a:b + 1] - sip[a], want_ip)
+        assert np.array_equal(six[sip[a]:sip[b]], want_ix), a
+    gs.free()
+    x_host = torch.empty(cfg["x"].shape, dtype=torch.float32, pin_memory=True)
+    x_host.copy_(cfg["x"])
+    out_host = torch.empty((n, structs[-1].out_dim), dtype=torch.float32, pin_memory=True)
+    st = bd.infer_host(g, structs, x_host, out_host, mem_budget_bytes=2_000_000_000, stream_always=True)
+    print("host-resident: %.0f ms, batches %s, %.1f GB read over the host link" % (st["total_ms"], st["batches"], sum(st["input_bytes"]) / 1e9), flush=True)
+    assert st["device_resident"] == 0 and min(st["batches"]) > 10 and st["peak_batch_bytes"] <= 1_000_000_000
+    assert max_rel_err(out_host.numpy(), out.cpu().numpy()) <= 1e-4
+    g.release_workspace()

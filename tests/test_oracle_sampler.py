@@ -113,3 +113,14 @@ def test_sampling_inference_special_cases():
     cnt = oracle.infer_sampled(indptr, indices, [dict(agg="sum", act="none", W_self=None, W_neigh=np.ones((1, 1), np.float32), bias=None)],
                                ones, fanout=7, seed=8)
     assert np.array_equal(cnt[:, 0], np.minimum(np.diff(indptr), 7).astype(np.float32))
+
+
+def test_sampling_a_row_slice_equals_the_slice_of_the_sample():
+    indptr, indices = random_csr(900, 7.0, seed=12, hub=(400, 300))
+    full_ip, full_ix = sampler.sample_csr(indptr, indices, 5, seed=77, layer=2)
+    a, b = 350, 620
+    ip = indptr[a:b + 1] - indptr[a]
+    ix = indices[indptr[a]:indptr[b]]
+    sl_ip, sl_ix = sampler.sample_csr(ip, ix, 5, seed=77, layer=2, edge_base=int(indptr[a]), total_edges=indices.size)
+    assert np.array_equal(sl_ip, full_ip[a:b + 1] - full_ip[a])
+    assert np.array_equal(sl_ix, full_ix[full_ip[a]:full_ip[b]])
