@@ -47,6 +47,25 @@ def max_rel_err(got, want):
     return float(np.max(np.abs(got - want) / np.maximum(np.abs(want), floor)))
 
 
+def error_report(got, want):
+    """The three figures every parity report states: the gated one (max relative error with the RMS floor of
+    max_rel_err), and, for information, the 99.9th percentile of the un-floored element-wise relative error over
+    the non-zero expected values and the largest absolute error."""
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    if want.size == 0:
+        return dict(max_rel_floored=0.0, p999_rel_unfloored=0.0, max_abs=0.0)
+    diff = np.abs(got - want)
+    nz = want != 0
+    p999 = float(np.percentile(diff[nz] / np.abs(want[nz]), 99.9)) if nz.any() else 0.0
+    return dict(max_rel_floored=max_rel_err(got, want), p999_rel_unfloored=p999, max_abs=float(diff.max()))
+
+
+def format_error_report(r):
+    return ("max |g-o|/max(|o|, RMS(o)) = %.3e, 99.9th percentile of |g-o|/|o| = %.3e, max |g-o| = %.3e"
+            % (r["max_rel_floored"], r["p999_rel_unfloored"], r["max_abs"]))
+
+
 def act_np(x, act, slope=1.0):
     if act == "relu":
         return np.maximum(x, 0.0)

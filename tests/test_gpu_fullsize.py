@@ -8,7 +8,7 @@ import torch
 
 from dgi_inputs import configs
 from oracle import oracle
-from tests.helpers import max_rel_err, nodewise_oracle
+from tests.helpers import error_report, format_error_report, max_rel_err, nodewise_oracle
 
 pytestmark = pytest.mark.gpu
 
@@ -44,9 +44,9 @@ def test_full_size_against_full_oracle(k):
                         cfg["x"].cpu().numpy())
     got = out.cpu().numpy()
     assert np.isfinite(got).all()
-    err = max_rel_err(got, want)
-    print("cfg%d: max rel err %.3e over %d x %d outputs" % (k, err, *got.shape), flush=True)
-    assert err <= 1e-4
+    rep = error_report(got, want)
+    print("cfg%d: %s over %d x %d outputs" % (k, format_error_report(rep), *got.shape), flush=True)
+    assert rep["max_rel_floored"] <= 1e-4
 
 
 def _sample_targets(cfg, count, seed):
@@ -98,8 +98,9 @@ def test_config4_full_size():
         o = torch.empty(n, structs[l].out_dim, dtype=odt, device="cuda")
         st = bd.infer(g, [structs[l]], h.contiguous(), o, want_stats=True)
         want = nodewise_oracle(cfg["indptr"], cfg["indices"], h, [layers[l]], targets, 1)
-        err = max_rel_err(o[tt].float().cpu().numpy(), want)
-        print("cfg4 layer %d alone: %.1f ms, batches %s, max rel err %.3e on %d rows" % (l + 1, st["total_ms"], st["batches"], err, len(targets)), flush=True)
+        rep = error_report(o[tt].float().cpu().numpy(), want)
+        err = rep["max_rel_floored"]
+        print("cfg4 layer %d alone: %.1f ms, batches %s, %s on %d rows" % (l + 1, st["total_ms"], st["batches"], format_error_report(rep), len(targets)), flush=True)
         assert err <= 2e-2
         del o, h
     torch.cuda.empty_cache()

@@ -7,7 +7,7 @@ import torch
 
 from dgi_inputs import configs
 from oracle import oracle
-from tests.helpers import max_rel_err, random_csr
+from tests.helpers import error_report, format_error_report, max_rel_err, random_csr
 
 pytestmark = pytest.mark.gpu
 
@@ -222,6 +222,22 @@ def test_configs_downscaled_end_to_end(k, scale, tol):
     want = oracle_infer(cfg)
     assert np.isfinite(got).all()
     assert max_rel_err(got, want) <= tol
+
+
+def test_bf16_storage_against_an_oracle_that_rounds_nothing_in_between():
+    # What bf16 storage of the hidden layers costs: the GPU path (hidden layers stored in bf16, fp32 accumulation)
+    # against the oracle run on the same stored inputs and weights but with every hidden layer kept in fp64.
+    # Reported; gated only loosely (two roundings to 8 mantissa bits on the way, each 2^-9 relative at most).
+    cfg = configs.make_config(4, scale=0.0003)
+    got, stats = run_infer(cfg)
+    layers = [dict(L, out_storage="f32") for L in configs.to_numpy_layers(cfg["layers"])]
+    unrounded = oracle.infer(cfg["indptr"].cpu().numpy(), cfg["indices"].cpu().numpy(), layers, cfg["x"].float().cpu().numpy())
+    rounded = oracle_infer(cfg)
+    rep_u, rep_r = error_report(got, unrounded), error_report(got, rounded)
+    print("cfg4 x 0.0003 against the un-rounded oracle: " + format_error_report(rep_u), flush=True)
+    print("cfg4 x 0.0003 against the oracle that rounds hidden layers to bf16: " + format_error_report(rep_r), flush=True)
+    assert rep_r["max_rel_floored"] <= TOL_BF16
+    assert rep_u["max_rel_floored"] <= 5e-2
 
 
 def test_batch_size_invariance_is_bitwise():

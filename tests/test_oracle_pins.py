@@ -354,3 +354,17 @@ def test_jumping_knowledge_stack_matches_dense_algebra():
     want = gcn_dense(A, np.concatenate([h1, h2], axis=1).astype(np.float32), l3["W_neigh"], l3["bias"], "none")
     got = oracle.infer_jk(indptr, indices, [l1, l2, l3], X)
     np.testing.assert_allclose(got, want, rtol=1e-5, atol=1e-5)
+
+
+def test_error_report_figures_on_a_hand_made_case():
+    # the parity metric and the two un-gated figures reported beside it
+    from tests.helpers import error_report
+    want = np.array([[3.0, -4.0], [0.0, 1e-6]])
+    got = np.array([[3.0003, -4.0], [1e-5, 2e-6]])
+    rep = error_report(got, want)
+    rms = np.sqrt((9 + 16 + 0 + 1e-12) / 4)
+    # floored: largest of 3e-4/3, 0/4, 1e-5/rms, 1e-6/rms
+    assert abs(rep["max_rel_floored"] - 1e-4) < 1e-9 and 1e-5 / rms < 1e-4
+    assert abs(rep["max_abs"] - 3e-4) < 1e-12
+    # un-floored over the non-zero expected values: {1e-4, 0, 1.0}; the 99.9th percentile sits just under the max
+    assert 0.99 < rep["p999_rel_unfloored"] <= 1.0
