@@ -90,6 +90,7 @@ dgi_status_t validate_layer(const dgi_layer_t* L) {
 // h_in / ld_in: the layer's input as it will be passed (its alignment decides which kernels can run).
 dgi_status_t plan_layer(const dgi_graph* g, const dgi_layer_t* L, const void* h_in, int64_t ld_in, LayerPlan* P) {
     DGI_TRY(validate_layer(L));
+    DGI_REQUIRE(L->agg != DGI_AGG_GCN || g->has_out_degrees, DGI_ERR_INVALID_ARG, "GCN layer on a graph handle built without out-degrees");
     LayerPlan p;
     p.eb = elem_bytes(L->feat_dtype);
     p.E = 16 / p.eb;

@@ -52,6 +52,7 @@ struct dgi_graph {
     const void* d_indptr = nullptr;     // device, itype entries
     const int32_t* d_indices = nullptr; // device
     bool own_csr = false;               // device CSR allocated by the handle
+    bool has_out_degrees = true;        // d_deg_out / d_rs_out are filled (a sampled graph for a layer without GCN skips the count)
     int32_t* d_deg_out = nullptr;
     float* d_rs_in = nullptr;           // in-degree^-1/2, degree clamped to >= 1
     float* d_rs_out = nullptr;
@@ -207,7 +208,7 @@ dgi_status_t reorder_permutation(int64_t N, const int64_t* indptr, const int32_t
 
 // handle over device CSR arrays built by the library (int64 indptr); takes ownership of the arrays and of h_indptr
 dgi_status_t graph_adopt(int64_t N, int64_t E, int64_t* d_indptr, int32_t* d_indices, std::vector<int64_t>&& h_indptr, int64_t max_degree,
-                         bool own_arrays, hipStream_t stream, dgi_graph_t** out);
+                         bool own_arrays, bool count_out_degrees, hipStream_t stream, dgi_graph_t** out);
 
 // dgi_layer_forward with an output buffer whose first row is destination row out_base (0 = the whole matrix)
 dgi_status_t layer_forward_rows(const dgi_graph* g, const dgi_layer_t* layer, const void* h_in, int64_t ld_in, void* h_out, int64_t ld_out,

@@ -118,7 +118,7 @@ __global__ void min_degree_kernel(const IdxT* indptr, int64_t N, int fanout, int
 // The sampled graph of one layer.  With `cached` the host indptr vector and the device arrays come from (and stay
 // in) g's handle and the new handle borrows the device arrays; the caller must hold g->hs_mutex and hand the host
 // vector back (g->ss_ip = std::move(sampled->h_indptr)) before freeing the sampled handle.
-dgi_status_t sample_graph(const dgi_graph* g, int fanout, uint64_t seed, int layer, bool cached, hipStream_t s, dgi_graph_t** g_out) {
+dgi_status_t sample_graph(const dgi_graph* g, int fanout, uint64_t seed, int layer, bool cached, bool count_out_degrees, hipStream_t s, dgi_graph_t** g_out) {
     const int64_t N = g->N;
     // host indptr of the sample = prefix sums of min(degree, fanout), in parallel chunks (the handle keeps a host copy
     // for batch planning); the device copy is computed on the device, so nothing crosses the host link
@@ -197,7 +197,7 @@ dgi_status_t sample_graph(const dgi_graph* g, int fanout, uint64_t seed, int lay
     if (err != hipSuccess) { set_error("graph_sample: %s", hipGetErrorString(err)); return fail(DGI_ERR_DEVICE); }
     (void)hipFree(d_tmp);
     d_tmp = nullptr;
-    const dgi_status_t st = graph_adopt(N, Es, d_ip, d_ix, std::move(ip), std::min<int64_t>(g->max_in_degree, fanout), !cached, s, g_out);
+    const dgi_status_t st = graph_adopt(N, Es, d_ip, d_ix, std::move(ip), std::min<int64_t>(g->max_in_degree, fanout), !cached, count_out_degrees, s, g_out);
     if (st != DGI_OK) return fail(st);  // graph_adopt handed `ip` back
     return DGI_OK;
 }
@@ -214,7 +214,7 @@ extern "C" dgi_status_t dgi_graph_sample(const dgi_graph_t* g, int32_t fanout, u
     DGI_REQUIRE(fanout >= 1, DGI_ERR_INVALID_ARG, "graph_sample: fan-out must be at least 1");
     DGI_REQUIRE(layer >= 0 && layer < DGI_MAX_LAYERS, DGI_ERR_INVALID_ARG, "graph_sample: bad layer index");
     DGI_REQUIRE(g->N < (int64_t)INT_MAX - 1, DGI_ERR_UNSUPPORTED, "graph_sample: at most 2^31 - 3 nodes");
-    return sample_graph(g, fanout, seed, layer, false, static_cast<hipStream_t>(hip_stream), g_out);
+    return sample_graph(g, fanout, seed, layer, false, true, static_cast<hipStream_t>(hip_stream), g_out);
 }
 
 extern "C" dgi_status_t dgi_infer_sampled(const dgi_graph_t* g, const dgi_layer_t* layers, int32_t num_layers, const void* x, int64_t ld_x,
@@ -268,7 +268,8 @@ extern "C" dgi_status_t dgi_infer_sampled(const dgi_graph_t* g, const dgi_layer_
         void* dst = last ? out : hid[l % 2].p;
         const int64_t ld_dst = last ? ld_out : round_up(layers[l].out_dim, 16 / eb);
         dgi_graph_t* gs = nullptr;
-        DGI_TRY(sample_graph(g, fanout, seed, l, true, s, &gs));
+        // only GCN reads the sampled graph's out-degrees; counting them costs an integer atomic per sampled edge
+        DGI_TRY(sample_graph(g, fanout, seed, l, true, layers[l].agg == DGI_AGG_GCN, s, &gs));
         gs->ws_ptr = arena.p; gs->ws_bytes = arena.bytes;
         arena.p = nullptr; arena.bytes = 0;
         const dgi_status_t st = dgi_infer(gs, &layers[l], 1, cur, ld_cur, dst, ld_dst, &o, s);  // waits for completion
