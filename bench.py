@@ -162,7 +162,8 @@ def host_resident(args, cfg, g, structs, B):
                       "GBps_while_loading": sum(st["input_bytes"]) / max(sum(st["load_ms"]) * 1e-3, 1e-9) / 1e9},
         "per_layer": {k: [round(v, 3) if isinstance(v, float) else v for v in st[k]]
                       for k in ("load_ms", "compute_ms", "store_ms", "batches", "input_rows", "input_bytes", "output_bytes")},
-        "oom_retries": st["oom_retries"], "peak_batch_bytes": st["peak_batch_bytes"], "device_resident": st["device_resident"]}))
+        "oom_retries": st["oom_retries"], "peak_batch_bytes": st["peak_batch_bytes"], "device_resident": st["device_resident"],
+        "slots": st["slots"]}))
 
 
 def sampling(args, cfg, g, structs, x, out, B):

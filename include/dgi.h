@@ -239,9 +239,11 @@ dgi_status_t dgi_infer_partial(const dgi_graph_t* g, const dgi_layer_t* layers, 
  * Per batch [b, e) of destination rows the device (i) marks and compacts the input set I = [b, e) + the sources of the batch's edges, (ii) reads the rows H^{l-1}[I] straight
  * from host memory into a compact device matrix, (iii) relabels the batch's neighbour lists to positions in I
  * and runs the layer (dgi_layer_forward's kernels) on that sub-problem, (iv) copies the rows H^l[b:e] to host.
- * Two batches are in flight: while one computes and dumps on a second stream, the next one is built and loaded
- * (the host link carries both directions at once), so a batch may use M = half of opts->mem_budget_bytes
- * (0 = 90 % of free device memory).  Batch sizes follow Section 4.1 with real memory at stake: the batch's
+ * Up to two batches are in flight: while one computes and dumps on a second stream, the next one is built and loaded
+ * (the host link carries both directions at once); a batch may then use M = half of opts->mem_budget_bytes
+ * (0 = 90 % of free device memory).  Smaller batches load more rows in total, so the library runs one batch at a
+ * time with M = the whole budget instead whenever it estimates, on the first planned batch, that compute and
+ * dump are a small part of a batch's time next to its load (hstats->slots tells which).  Batch sizes follow Section 4.1 with real memory at stake: the batch's
  * device memory M_k (input rows, relabelled lists, output rows, layer workspace) is measured, the thresholds are
  * rescaled by r = M / M_k (Eq. 2), and a batch that does not fit M halves the thresholds and is planned again.
  * When the whole graph fits M, every layer is one batch; when x, the output and dgi_infer's own buffers all fit
@@ -264,6 +266,7 @@ typedef struct {
     int64_t oom_retries;                     /* batches planned again after halving the thresholds */
     int64_t peak_batch_bytes;                /* largest M_k */
     int64_t budget_bytes;                    /* M, the memory one batch may use */
+    int64_t slots;                           /* batches in flight: 1 or 2 (0 when device_resident) */
 } dgi_host_stats_t;
 dgi_status_t dgi_infer_host(const dgi_graph_t* g, const dgi_layer_t* layers, int32_t num_layers, const void* x_host,
                             int64_t ld_x, void* out_host, int64_t ld_out, const dgi_infer_opts_t* opts,

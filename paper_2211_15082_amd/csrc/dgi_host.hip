@@ -183,6 +183,7 @@ dgi_status_t infer_host(const dgi_graph* g, const dgi_layer_t* layers, int32_t L
     }
     // no batch needs more than the whole graph at once
     uint64_t whole = 0;
+    int n_slots = 2;
     for (int l = 0; l < L; ++l) {
         const int xb = layers[l].feat_dtype == DGI_BF16 ? 2 : 4, yb = layers[l].out_dtype == DGI_BF16 ? 2 : 4;
         uint64_t ws = 0;
@@ -190,14 +191,51 @@ dgi_status_t infer_host(const dgi_graph* g, const dgi_layer_t* layers, int32_t L
         whole = std::max<uint64_t>(whole, (uint64_t)g->E * 4 + (uint64_t)(N + 1) * 20 + (uint64_t)N * round_up(layers[l].in_dim, 16 / xb) * xb +
                                               (uint64_t)N * round_up(layers[l].out_dim, 16 / yb) * yb + 2 * ws + 8192);
     }
-    // Two slots of M bytes each (M is Eq. 2's expected consumption of one batch); everything at once if it fits.
-    const bool all_fits = whole <= budget / 2;
-    const uint64_t M = (all_fits ? whole : budget / 2) / 256 * 256;
+    // One slot or two?  Two slots overlap a batch's compute and dump with the next batch's load, but halve M, and
+    // smaller batches load more rows in total (their input sets overlap): measured on a 2.4 M-node power-law graph,
+    // half the slot size means 1.6 times the bytes over the host link (twice, once a batch's input set is most of the
+    // graph).  So two slots pay off only where compute and dump are a large part of a batch's time, as on a graph
+    // whose batches need little beyond their own rows.  Estimated on the first batch the two-slot plan would run
+    // (host link 45 GB/s each way, gathers 5 TB/s, transforms 100 TFLOP/s, 0.2 ms of launches per layer): one slot
+    // unless compute + dump exceed 0.38 of the load, the point where 1.6x the traffic costs as much as the lost
+    // overlap.
+    auto choose_slots = [&]() -> dgi_status_t {
+        const char* const env = getenv("DGI_TUNE_HOST_SLOTS");  // measurements only
+        if (env && *env) { n_slots = atoi(env) == 1 ? 1 : 2; return DGI_OK; }
+        if (whole <= budget) { n_slots = 1; return DGI_OK; }  // a whole layer at once: every row crosses the link once
+        const int64_t n_t = o.batch_size > 0 ? o.batch_size : (o.init_node_threshold > 0 ? o.init_node_threshold : 65536);
+        const int64_t n_i = o.batch_size > 0 ? INT64_MAX / 4
+                                             : (o.init_edge_threshold > 0 ? o.init_edge_threshold : (int64_t)std::max(1.0, (double)n_t * std::max(avg_deg, 1.0)));
+        int64_t e = 0;
+        DGI_TRY(dgi_plan_batch_end(g->h_indptr.data(), DGI_I64, N, 0, std::max<int64_t>(n_t, 1), std::max<int64_t>(n_i, 0), &e));
+        const int64_t e_b = g->h_indptr[e] - g->h_indptr[0];
+        hipLaunchKernelGGL(batch_depth_kernel, dim3(grid_for(N)), dim3(kBlock), 0, s, depth.as<int32_t>(), N, (int64_t)0, e);
+        if (e_b > 0)
+            hipLaunchKernelGGL(mark_sources_kernel, dim3(grid_for(e_b)), dim3(kBlock), 0, s, g->d_indices, g->h_indptr[0], g->h_indptr[e], depth.as<int32_t>());
+        int64_t n_sub = 0;
+        DGI_TRY(sc.count_level(depth.as<int32_t>(), N, 0, &n_sub, s));
+        double load = 0, work = 0;
+        for (int l = 0; l < L; ++l) {
+            const double in_row = (double)layers[l].in_dim * (layers[l].feat_dtype == DGI_BF16 ? 2 : 4);
+            const double out_row = (double)layers[l].out_dim * (layers[l].out_dtype == DGI_BF16 ? 2 : 4);
+            const double k_tot = (double)layers[l].in_dim * (layers[l].W_self ? 2 : 1);
+            load += (double)n_sub * in_row / 45e9;
+            work += (double)e_b * std::max(in_row, out_row) / 5e12 + (double)e * 2.0 * k_tot * layers[l].out_dim / 100e12 + 2e-4 +
+                    (double)e * out_row / 45e9;
+        }
+        n_slots = work > 0.38 * load ? 2 : 1;
+        return DGI_OK;
+    };
+    // One or two slots of M bytes each (M is Eq. 2's expected consumption of one batch); everything at once if it fits.
+    if (whole > budget / 2) DGI_TRY(choose_slots());
+    const bool all_fits = whole <= budget / (uint64_t)n_slots;
+    const uint64_t M = (all_fits ? whole : budget / (uint64_t)n_slots) / 256 * 256;
     DGI_REQUIRE(M >= 65536, DGI_ERR_OOM, "infer_host: memory budget %llu bytes is too small", (unsigned long long)budget);
-    if (g->hs_arena_bytes < 2 * M || g->hs_arena_bytes > 3 * M + ((uint64_t)64 << 20)) {  // too small, or far beyond this call's budget
+    const uint64_t arena = (uint64_t)n_slots * M;
+    if (g->hs_arena_bytes < arena || g->hs_arena_bytes > arena + M / 2 + ((uint64_t)64 << 20)) {  // too small, or far beyond this call's budget
         (void)hipFree(g->hs_arena); g->hs_arena = nullptr; g->hs_arena_bytes = 0;
-        DGI_HIP(hipMalloc(reinterpret_cast<void**>(&g->hs_arena), 2 * M));
-        g->hs_arena_bytes = 2 * M;
+        DGI_HIP(hipMalloc(reinterpret_cast<void**>(&g->hs_arena), arena));
+        g->hs_arena_bytes = arena;
     }
     Slot slot[2];
     StreamPair st;
@@ -206,14 +244,14 @@ dgi_status_t infer_host(const dgi_graph* g, const dgi_layer_t* layers, int32_t L
         hipStream_t a, b;
         ~SyncOnExit() { (void)hipStreamSynchronize(a); (void)hipStreamSynchronize(b); }
     } drain{st.a, st.b};
-    for (int i = 0; i < 2; ++i) { DGI_TRY(slot[i].create()); slot[i].mem = g->hs_arena + (uint64_t)i * M; }
-    if (hs) { hs->budget_bytes = (int64_t)M; }
+    for (int i = 0; i < n_slots; ++i) { DGI_TRY(slot[i].create()); slot[i].mem = g->hs_arena + (uint64_t)i * M; }
+    if (hs) { hs->budget_bytes = (int64_t)M; hs->slots = n_slots; }
     DGI_HIP(hipStreamSynchronize(s));  // the caller's earlier work on its stream (x_host may come from it)
     const hipStream_t sa = st.a, sb = st.b;
 
     const void* cur = x_dev;
     int64_t ld_cur = ld_x;
-    int64_t k = 0;  // batch counter: slot k % 2
+    int64_t k = 0;  // batch counter: slot k % n_slots
     for (int l = 0; l < L; ++l) {
         const dgi_layer_t& Ly = layers[l];
         const int xb = Ly.feat_dtype == DGI_BF16 ? 2 : 4, yb = Ly.out_dtype == DGI_BF16 ? 2 : 4;
@@ -241,8 +279,8 @@ dgi_status_t infer_host(const dgi_graph* g, const dgi_layer_t* layers, int32_t L
                 n_t = std::min(n_t, std::max<int64_t>(rows / 2, 1));
                 return DGI_OK;
             };
-            Slot& S = slot[k % 2];
-            DGI_TRY(S.retire(hs));  // its previous batch (two batches ago) must have left the slot
+            Slot& S = slot[k % n_slots];
+            DGI_TRY(S.retire(hs));  // its previous batch (n_slots batches ago) must have left the slot
             // ---- (i) input set, on the first stream ---------------------------------------------------------------
             DGI_HIP(hipEventRecord(S.ev[0], sa));
             hipLaunchKernelGGL(batch_depth_kernel, dim3(grid_for(N)), dim3(kBlock), 0, sa, depth.as<int32_t>(), N, b, e);

@@ -173,6 +173,9 @@ def test_full_size_sampler_and_host_resident_path():
     out_host = torch.empty((n, structs[-1].out_dim), dtype=torch.float32, pin_memory=True)
     st = bd.infer_host(g, structs, x_host, out_host, mem_budget_bytes=2_000_000_000, stream_always=True)
     print("host-resident: %.0f ms, batches %s, %.1f GB read over the host link" % (st["total_ms"], st["batches"], sum(st["input_bytes"]) / 1e9), flush=True)
-    assert st["device_resident"] == 0 and min(st["batches"]) > 10 and st["peak_batch_bytes"] <= 1_000_000_000
+    # loads dominate on this graph (its batches' input sets overlap heavily), so the library runs one batch at a
+    # time with the whole budget rather than two half-sized ones in flight
+    assert st["device_resident"] == 0 and st["slots"] == 1 and min(st["batches"]) >= 5
+    assert st["peak_batch_bytes"] <= st["budget_bytes"] == 2_000_000_000 // 256 * 256
     assert max_rel_err(out_host.numpy(), out.cpu().numpy()) <= 1e-4
     g.release_workspace()

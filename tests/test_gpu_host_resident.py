@@ -80,6 +80,8 @@ def test_host_resident_inference_matches_the_oracle(kind):
     out2 = torch.full((n, 16), 777.0, dtype=torch.float32, pin_memory=True)
     st2 = bd.infer_host(g, list(structs), x, out2, mem_budget_bytes=2_400_000, init_node_threshold=64, stream_always=True)
     assert max_rel_err(out2.numpy(), want) <= TOL_F32
+    # (launch overheads dominate batches this small, so the library keeps two of them in flight: M is half the budget)
+    assert st2["slots"] == 2
     assert all(nb >= 3 for nb in st2["batches"]) and st2["peak_batch_bytes"] <= st2["budget_bytes"] == 1_200_000 // 256 * 256
     # hidden layers kept in host memory although a whole layer fits a slot: one batch per layer
     out3 = torch.full((n, 16), 777.0, dtype=torch.float32, pin_memory=True)
