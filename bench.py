@@ -152,7 +152,7 @@ def host_resident(args, cfg, g, structs, B):
     stats = [B.infer_host(g, structs, x, out, **kw) for _ in range(args.steps)]
     sec = (time.perf_counter() - t0) / args.steps
     st = stats[-1]
-    moved = sum(st["input_bytes"]) + sum(st["output_bytes"])
+    moved = sum(st["input_bytes"]) + sum(st["output_bytes"]) + sum(st["transform_bytes"])
     print(json.dumps({
         "metric": "full-graph layer-wise inference: aggregated edges per second", "value": len(structs) * e / sec, "unit": "edges/s",
         "n_gpus": 1, "steps": args.steps, "warmup": max(args.warmup, 1), "ms_per_step": sec * 1e3, "higher_is_better": True,
@@ -161,7 +161,7 @@ def host_resident(args, cfg, g, structs, B):
         "host_link": {"bytes_per_step": moved, "GBps_over_whole_step": moved / sec / 1e9,
                       "GBps_while_loading": sum(st["input_bytes"]) / max(sum(st["load_ms"]) * 1e-3, 1e-9) / 1e9},
         "per_layer": {k: [round(v, 3) if isinstance(v, float) else v for v in st[k]]
-                      for k in ("load_ms", "compute_ms", "store_ms", "batches", "input_rows", "input_bytes", "output_bytes")},
+                      for k in ("load_ms", "compute_ms", "store_ms", "batches", "input_rows", "input_bytes", "output_bytes", "transform_bytes")},
         "oom_retries": st["oom_retries"], "peak_batch_bytes": st["peak_batch_bytes"], "device_resident": st["device_resident"],
         "slots": st["slots"]}))
 

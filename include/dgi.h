@@ -246,6 +246,11 @@ dgi_status_t dgi_infer_partial(const dgi_graph_t* g, const dgi_layer_t* layers, 
  * dump are a small part of a batch's time next to its load (hstats->slots tells which).  Batch sizes follow Section 4.1 with real memory at stake: the batch's
  * device memory M_k (input rows, relabelled lists, output rows, layer workspace) is measured, the thresholds are
  * rescaled by r = M / M_k (Eq. 2), and a batch that does not fit M halves the thresholds and is planned again.
+ * A layer that multiplies before it aggregates (out_dim < in_dim, GAT) and whose transformed rows are at most
+ * three quarters as wide as its input rows runs as two passes when it needs more than one batch: H^{l-1} streams
+ * through the device once in contiguous row chunks and Z = H^{l-1} W goes to a page-locked buffer, then the
+ * batches load rows of Z for their input sets and only aggregate (input_bytes counts rows of Z, transform_bytes
+ * the dense pass).
  * When the whole graph fits M, every layer is one batch; when x, the output and dgi_infer's own buffers all fit
  * the budget, the call is one copy in, dgi_infer, one copy out (hstats->device_resident = 1) and the hidden
  * layers never leave the device (opts->host_stream_always = 1 switches that off).  opts->batch_size > 0 fixes
@@ -263,6 +268,7 @@ typedef struct {
     int64_t input_rows[DGI_MAX_LAYERS];      /* sum over batches of |I| (what node reordering shrinks, Section 4.2) */
     int64_t input_bytes[DGI_MAX_LAYERS];     /* bytes read from host memory */
     int64_t output_bytes[DGI_MAX_LAYERS];    /* bytes written to host memory */
+    int64_t transform_bytes[DGI_MAX_LAYERS]; /* dense pass of a transform-first layer: rows of H^{l-1} read + rows of Z written */
     int64_t oom_retries;                     /* batches planned again after halving the thresholds */
     int64_t peak_batch_bytes;                /* largest M_k */
     int64_t budget_bytes;                    /* M, the memory one batch may use */

@@ -75,7 +75,7 @@ class HostStatsStruct(ctypes.Structure):
         ("num_layers", ctypes.c_int32), ("device_resident", ctypes.c_int32), ("total_ms", ctypes.c_double),
         ("load_ms", ctypes.c_double * MAX_LAYERS), ("compute_ms", ctypes.c_double * MAX_LAYERS), ("store_ms", ctypes.c_double * MAX_LAYERS),
         ("batches", ctypes.c_int64 * MAX_LAYERS), ("input_rows", ctypes.c_int64 * MAX_LAYERS), ("input_bytes", ctypes.c_int64 * MAX_LAYERS),
-        ("output_bytes", ctypes.c_int64 * MAX_LAYERS), ("oom_retries", ctypes.c_int64), ("peak_batch_bytes", ctypes.c_int64),
+        ("output_bytes", ctypes.c_int64 * MAX_LAYERS), ("transform_bytes", ctypes.c_int64 * MAX_LAYERS), ("oom_retries", ctypes.c_int64), ("peak_batch_bytes", ctypes.c_int64),
         ("budget_bytes", ctypes.c_int64), ("slots", ctypes.c_int64),
     ]
 

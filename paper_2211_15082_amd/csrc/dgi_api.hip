@@ -334,11 +334,13 @@ extern "C" dgi_status_t dgi_graph_release_workspace(dgi_graph_t* g) {
     if (!g) return DGI_OK;
     DGI_TRY(release_infer_arena(g));
     std::lock_guard<std::mutex> hs_lock(g->hs_mutex);
-    if (g->hs_arena || g->hs_hid[0] || g->hs_hid[1] || g->ss_d_ip || g->ss_d_ix) {
+    if (g->hs_arena || g->hs_hid[0] || g->hs_hid[1] || g->hs_z || g->ss_d_ip || g->ss_d_ix) {
         DGI_HIP(hipDeviceSynchronize());
         (void)hipFree(g->hs_arena);
         (void)hipHostFree(g->hs_hid[0]);
         (void)hipHostFree(g->hs_hid[1]);
+        (void)hipHostFree(g->hs_z);
+        g->hs_z = nullptr; g->hs_z_bytes = 0;
         (void)hipFree(g->ss_d_ip);
         (void)hipFree(g->ss_d_ix);
         g->hs_arena = nullptr; g->hs_arena_bytes = 0;
@@ -380,6 +382,47 @@ dgi_status_t dgi::layer_forward_rows(const dgi_graph* g, const dgi_layer_t* laye
     if (P.transform_first) DGI_TRY(run_transform(layer, P, h_in, ld_in, ws + f.wt_off, ws + f.z_off, 0, g->N, s));
     return run_batch(g, layer, P, h_in, ld_in, h_out, ld_out, dst_begin, dst_end, ws + f.wt_off, ws + f.z_off, ws + f.temp_off, s, nullptr, false, nullptr,
                      out_base);
+}
+
+dgi_status_t dgi::layer_transform_info(const dgi_graph* g, const dgi_layer_t* layer, TransformInfo* info) {
+    LayerPlan P;
+    DGI_TRY(plan_layer(g, layer, reinterpret_cast<const void*>(16), 0, &P));
+    info->transform_first = P.transform_first;
+    info->z_cols = P.z_cols; info->z_ld = P.z_ld; info->z_dtype = P.z_dtype;
+    info->weight_bytes = P.wt_bytes;
+    return DGI_OK;
+}
+
+dgi_status_t dgi::layer_transform_rows(const dgi_graph* g, const dgi_layer_t* layer, const void* h_in, int64_t ld_in, int64_t rows, void* Z,
+                                       void* weights, hipStream_t s) {
+    LayerPlan P;
+    DGI_TRY(plan_layer(g, layer, reinterpret_cast<const void*>(16), 0, &P));
+    DGI_REQUIRE(P.transform_first, DGI_ERR_INVALID_ARG, "layer_transform_rows: not a transform-first layer");
+    DGI_REQUIRE(weights != nullptr && (uintptr_t)weights % 256 == 0, DGI_ERR_INVALID_ARG, "layer_transform_rows: weight scratch missing or misaligned");
+    if (rows <= 0) return DGI_OK;
+    DGI_TRY(check_matrix(h_in, ld_in, layer->in_dim, "h_in"));
+    DGI_TRY(prepare_weights(layer, P, weights, s));
+    return run_transform(layer, P, h_in, ld_in, weights, Z, 0, rows, s);
+}
+
+uint64_t dgi::layer_aggregate_temp_bytes(const dgi_graph* g, const dgi_layer_t* layer, int64_t b, int64_t e) {
+    LayerPlan P;
+    if (plan_layer(g, layer, reinterpret_cast<const void*>(16), 0, &P) != DGI_OK) return 0;
+    return batch_temp_bytes(g, layer, P, b, e) + 256;
+}
+
+dgi_status_t dgi::layer_aggregate_rows(const dgi_graph* g, const dgi_layer_t* layer, const void* Z, void* h_out, int64_t ld_out, int64_t out_base,
+                                       int64_t b, int64_t e, void* temp, uint64_t temp_bytes, hipStream_t s) {
+    LayerPlan P;
+    DGI_TRY(plan_layer(g, layer, reinterpret_cast<const void*>(16), 0, &P));
+    DGI_REQUIRE(P.transform_first, DGI_ERR_INVALID_ARG, "layer_aggregate_rows: not a transform-first layer");
+    DGI_REQUIRE(b >= 0 && e >= b && e <= g->N, DGI_ERR_INVALID_ARG, "layer_aggregate_rows: bad destination range");
+    if (e == b) return DGI_OK;
+    DGI_REQUIRE(Z != nullptr, DGI_ERR_INVALID_ARG, "layer_aggregate_rows: Z is NULL");
+    DGI_TRY(check_matrix(h_out, ld_out, layer->out_dim, "h_out"));
+    DGI_REQUIRE(temp != nullptr && (uintptr_t)temp % 256 == 0 && temp_bytes >= batch_temp_bytes(g, layer, P, b, e), DGI_ERR_INVALID_ARG,
+                "layer_aggregate_rows: temporary buffer missing, misaligned or too small");
+    return run_batch(g, layer, P, nullptr, 0, h_out, ld_out, b, e, nullptr, Z, temp, s, nullptr, false, nullptr, out_base);
 }
 
 extern "C" dgi_status_t dgi_layer_forward(const dgi_graph_t* g, const dgi_layer_t* layer, const void* h_in, int64_t ld_in,

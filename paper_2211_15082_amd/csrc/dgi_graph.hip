@@ -165,6 +165,7 @@ extern "C" dgi_status_t dgi_graph_free(dgi_graph_t* g) {
     (void)hipFree(g->hs_arena);
     (void)hipHostFree(g->hs_hid[0]);
     (void)hipHostFree(g->hs_hid[1]);
+    (void)hipHostFree(g->hs_z);
     (void)hipFree(g->ss_d_ip);
     (void)hipFree(g->ss_d_ix);
     delete g;

@@ -36,6 +36,7 @@ struct Slot {
     int layer = 0;
     int64_t n_sub = 0, rows = 0, in_bytes = 0, out_bytes = 0;
     uint64_t M_k = 0;
+    bool dense = false;  // a row chunk of a layer's dense pass (no input set, no sub-problem)
     ~Slot() { for (auto e : ev) if (e) (void)hipEventDestroy(e); }
     dgi_status_t create() { for (auto& e : ev) DGI_HIP(hipEventCreate(&e)); return DGI_OK; }
     // wait until the slot's batch has been stored, account for it, release its sub-problem
@@ -48,10 +49,14 @@ struct Slot {
             DGI_HIP(hipEventElapsedTime(&t12, ev[1], ev[2]));
             DGI_HIP(hipEventElapsedTime(&t23, ev[2], ev[3]));
             hs->load_ms[layer] += t01; hs->compute_ms[layer] += t12; hs->store_ms[layer] += t23;
-            hs->batches[layer] += 1;
-            hs->input_rows[layer] += n_sub;
-            hs->input_bytes[layer] += in_bytes;
-            hs->output_bytes[layer] += out_bytes;
+            if (dense) {
+                hs->transform_bytes[layer] += in_bytes + out_bytes;
+            } else {
+                hs->batches[layer] += 1;
+                hs->input_rows[layer] += n_sub;
+                hs->input_bytes[layer] += in_bytes;
+                hs->output_bytes[layer] += out_bytes;
+            }
             hs->peak_batch_bytes = std::max<int64_t>(hs->peak_batch_bytes, (int64_t)M_k);
         }
         sub.reset();
@@ -262,6 +267,55 @@ dgi_status_t infer_host(const dgi_graph* g, const dgi_layer_t* layers, int32_t L
         char* dst_dev = nullptr;
         DGI_HIP(hipHostGetDevicePointer(reinterpret_cast<void**>(&dst_dev), dst_host, 0));
 
+        // Transform-first across the host link.  When the layer's plan multiplies before it aggregates and a
+        // transformed row is clearly narrower than an input row, the rows every batch loads for its input set should
+        // be the narrow ones: a dense pass streams H^{l-1} through the device once in contiguous row chunks and
+        // leaves Z = H^{l-1} W in host memory, and the batches then gather rows of Z and only aggregate.
+        TransformInfo ti{};
+        DGI_TRY(layer_transform_info(g, &Ly, &ti));
+        const int zb = ti.z_dtype == DGI_BF16 ? 2 : 4;
+        const bool two_pass = !all_fits && ti.transform_first && (uint64_t)ti.z_ld * zb * 4 <= (uint64_t)ld_xs * xb * 3;
+        const void* f_src = cur;        // where the batches' input rows come from
+        int64_t f_ld = ld_cur, f_lds = ld_xs;
+        int f_width = Ly.in_dim, f_eb = xb;
+        if (two_pass) {
+            const uint64_t z_bytes = (uint64_t)N * ti.z_ld * zb;
+            if (g->hs_z_bytes < z_bytes) {
+                (void)hipHostFree(g->hs_z); g->hs_z = nullptr; g->hs_z_bytes = 0;
+                DGI_HIP(hipHostMalloc(&g->hs_z, (size_t)z_bytes, hipHostMallocDefault));
+                g->hs_z_bytes = z_bytes;
+            }
+            char* z_host = static_cast<char*>(g->hs_z);
+            char* z_dev = nullptr;
+            DGI_HIP(hipHostGetDevicePointer(reinterpret_cast<void**>(&z_dev), z_host, 0));
+            const uint64_t w_bytes = (uint64_t)round_up((int64_t)ti.weight_bytes, 256);
+            const uint64_t per_row = (uint64_t)ld_xs * xb + (uint64_t)ti.z_ld * zb;
+            DGI_REQUIRE(M > w_bytes + 1024 + per_row, DGI_ERR_OOM, "infer_host: layer %d: the packed weights and one row do not fit %llu bytes", l, (unsigned long long)M);
+            const int64_t rows_c = std::max<int64_t>(1, (int64_t)((M - w_bytes - 1024) / per_row));
+            for (int64_t r0 = 0; r0 < N; r0 += rows_c) {
+                const int64_t n = std::min(rows_c, N - r0);
+                Slot& S = slot[k % n_slots];
+                DGI_TRY(S.retire(hs));
+                char* A = S.mem;
+                const uint64_t o_x = w_bytes, o_z = o_x + (uint64_t)round_up(n * ld_xs * xb, 256);
+                DGI_HIP(hipEventRecord(S.ev[0], sa));
+                DGI_TRY(launch_permute_rows(static_cast<const char*>(cur) + (size_t)r0 * ld_cur * xb, ld_cur, A + o_x, ld_xs, n, Ly.in_dim, xb, nullptr, true, sa));
+                DGI_HIP(hipEventRecord(S.ev[1], sa));
+                DGI_HIP(hipStreamWaitEvent(sb, S.ev[1], 0));
+                DGI_TRY(layer_transform_rows(g, &Ly, A + o_x, ld_xs, n, A + o_z, A, sb));
+                DGI_HIP(hipEventRecord(S.ev[2], sb));
+                DGI_TRY(store_rows(A + o_z, ti.z_ld, z_host + (size_t)r0 * ti.z_ld * zb, z_dev + (size_t)r0 * ti.z_ld * zb, ti.z_ld, n, ti.z_cols, zb, sb));
+                DGI_HIP(hipEventRecord(S.ev[3], sb));
+                S.pending = true; S.dense = true; S.layer = l; S.n_sub = 0; S.rows = n;
+                S.M_k = o_z + (uint64_t)n * ti.z_ld * zb;
+                S.in_bytes = n * (int64_t)Ly.in_dim * xb; S.out_bytes = n * (int64_t)ti.z_cols * zb;
+                ++k;
+            }
+            for (int i = 0; i < n_slots; ++i) DGI_TRY(slot[i].retire(hs));  // the batches read all of Z
+            f_src = z_dev; f_ld = ti.z_ld; f_lds = ti.z_ld; f_eb = zb;
+            f_width = (int)ti.z_ld;  // whole padded rows: 16-byte pieces over the link (the padding columns are never read)
+        }
+
         int64_t n_t = o.batch_size > 0 ? o.batch_size : (all_fits ? N : (o.init_node_threshold > 0 ? o.init_node_threshold : 65536));
         int64_t n_i = (o.batch_size > 0 || all_fits) ? INT64_MAX / 4
                                        : (o.init_edge_threshold > 0 ? o.init_edge_threshold : (int64_t)std::max(1.0, (double)n_t * std::max(avg_deg, 1.0)));
@@ -292,7 +346,7 @@ dgi_status_t infer_host(const dgi_graph* g, const dgi_layer_t* layers, int32_t L
             uint64_t off = 0;
             auto carve = [&](uint64_t bytes) { const uint64_t at = off; off += (uint64_t)round_up((int64_t)std::max<uint64_t>(bytes, 16), 256); return at; };
             const uint64_t o_idx = carve((uint64_t)e_b * 4), o_ptr = carve((uint64_t)(n_sub + 1) * 8), o_deg = carve((uint64_t)(n_sub + 1) * 8);
-            const uint64_t o_U = carve((uint64_t)n_sub * 4), o_x = carve((uint64_t)n_sub * ld_xs * xb), o_y = carve((uint64_t)rows * ld_os * yb);
+            const uint64_t o_U = carve((uint64_t)n_sub * 4), o_x = carve((uint64_t)n_sub * f_lds * f_eb), o_y = carve((uint64_t)rows * ld_os * yb);
             if (off > M) { DGI_TRY(shrink()); continue; }
             char* A = S.mem;
             int64_t e_sub = 0;
@@ -304,30 +358,31 @@ dgi_status_t infer_host(const dgi_graph* g, const dgi_layer_t* layers, int32_t L
             DGI_HIP(hipMemcpyAsync(&lb, sc.loc.as<int32_t>() + b, 4, hipMemcpyDeviceToHost, sa));
             DGI_HIP(hipStreamSynchronize(sa));
             uint64_t ws_bytes = 0;
-            DGI_TRY(dgi_layer_workspace_bytes(S.sub.g, &Ly, lb, lb + rows, &ws_bytes));
+            if (two_pass) ws_bytes = layer_aggregate_temp_bytes(S.sub.g, &Ly, lb, lb + rows);
+            else DGI_TRY(dgi_layer_workspace_bytes(S.sub.g, &Ly, lb, lb + rows, &ws_bytes));
             const uint64_t o_ws = carve(ws_bytes);
             const uint64_t M_k = off + S.sub.g->device_bytes;
             if (M_k > M) { S.sub.reset(); DGI_TRY(shrink()); continue; }
             // ---- (ii) rows of the input set, read from host memory by the device --------------------------------------
-            DGI_TRY(launch_permute_rows(cur, ld_cur, A + o_x, ld_xs, n_sub, Ly.in_dim, xb, (const int32_t*)(A + o_U), true, sa));
+            DGI_TRY(launch_permute_rows(f_src, f_ld, A + o_x, f_lds, n_sub, f_width, f_eb, (const int32_t*)(A + o_U), true, sa));
             DGI_HIP(hipEventRecord(S.ev[1], sa));
             // ---- (iii) the layer on the sub-problem, on the second stream; the output buffer starts at row lb ----------------
             DGI_HIP(hipStreamWaitEvent(sb, S.ev[1], 0));
-            DGI_TRY(layer_forward_rows(S.sub.g, &Ly, A + o_x, ld_xs, A + o_y, ld_os, lb, lb, lb + rows, A + o_ws, ws_bytes, sb));
+            if (two_pass) DGI_TRY(layer_aggregate_rows(S.sub.g, &Ly, A + o_x, A + o_y, ld_os, lb, lb, lb + rows, A + o_ws, ws_bytes, sb));
+            else DGI_TRY(layer_forward_rows(S.sub.g, &Ly, A + o_x, ld_xs, A + o_y, ld_os, lb, lb, lb + rows, A + o_ws, ws_bytes, sb));
             DGI_HIP(hipEventRecord(S.ev[2], sb));
             // ---- (iv) dump the batch's rows ------------------------------------------------------------------------------
             DGI_TRY(store_rows(A + o_y, ld_os, dst_host + (size_t)b * ld_dst * yb, dst_dev + (size_t)b * ld_dst * yb, ld_dst, rows, Ly.out_dim, yb, sb));
             DGI_HIP(hipEventRecord(S.ev[3], sb));
-            S.pending = true; S.layer = l; S.n_sub = n_sub; S.rows = rows; S.M_k = M_k;
-            S.in_bytes = n_sub * (int64_t)Ly.in_dim * xb; S.out_bytes = rows * (int64_t)Ly.out_dim * yb;
+            S.pending = true; S.dense = false; S.layer = l; S.n_sub = n_sub; S.rows = rows; S.M_k = M_k;
+            S.in_bytes = n_sub * (int64_t)f_width * f_eb; S.out_bytes = rows * (int64_t)Ly.out_dim * yb;
             if (o.batch_size == 0 && !all_fits) DGI_TRY(dgi_threshold_update((double)M, (double)M_k, &n_t, &n_i));  // Eq. 2
             b = e;
             ++k;
         }
         // layer l+1 reads what layer l dumped: both slots must have stored their batches.  H^{l-1} is dead from
         // here on: its buffer takes H^{l+1}.
-        DGI_TRY(slot[0].retire(hs));
-        DGI_TRY(slot[1].retire(hs));
+        for (int i = 0; i < n_slots; ++i) DGI_TRY(slot[i].retire(hs));
         cur = dst_dev;
         ld_cur = ld_dst;
     }

@@ -78,6 +78,8 @@ struct dgi_graph {
     mutable uint64_t hs_arena_bytes = 0;
     mutable void* hs_hid[2] = {nullptr, nullptr};
     mutable uint64_t hs_hid_bytes = 0;
+    mutable void* hs_z = nullptr;       // page-locked host buffer of a transform-first layer's transformed rows
+    mutable uint64_t hs_z_bytes = 0;
     // dgi_infer_sampled builds one sampled graph per layer: its host indptr, device indptr and device indices
     // live here between layers and calls (the sampled handle borrows them).  Guarded by hs_mutex as well.
     mutable std::vector<int64_t> ss_ip;
@@ -213,6 +215,25 @@ dgi_status_t graph_adopt(int64_t N, int64_t E, int64_t* d_indptr, int32_t* d_ind
 // dgi_layer_forward with an output buffer whose first row is destination row out_base (0 = the whole matrix)
 dgi_status_t layer_forward_rows(const dgi_graph* g, const dgi_layer_t* layer, const void* h_in, int64_t ld_in, void* h_out, int64_t ld_out,
                                 int64_t out_base, int64_t dst_begin, int64_t dst_end, void* workspace, uint64_t workspace_bytes, hipStream_t s);
+
+// The dense and the sparse half of a transform-first layer as separate calls (dgi_infer_host runs them as two passes
+// when the transformed rows are narrower than the layer's input rows).
+struct TransformInfo {
+    bool transform_first;   // the layer's plan multiplies before it aggregates (always for GAT)
+    int z_cols;             // columns of a transformed row: [z_self |] z_neigh, or [z | e_l | e_r] for GAT
+    int64_t z_ld;
+    int z_dtype;
+    uint64_t weight_bytes;  // device scratch layer_transform_rows needs for the packed weights
+};
+dgi_status_t layer_transform_info(const dgi_graph* g, const dgi_layer_t* layer, TransformInfo* info);
+// Z[0:rows) = H[0:rows) W  (h_in, Z, weights: DEVICE; weights 256-byte aligned, info.weight_bytes long)
+dgi_status_t layer_transform_rows(const dgi_graph* g, const dgi_layer_t* layer, const void* h_in, int64_t ld_in, int64_t rows, void* Z,
+                                  void* weights, hipStream_t s);
+// destination rows [b, e) of g from transformed rows Z (one per node of g, leading dimension info.z_ld); temp as sized
+// by layer_aggregate_temp_bytes; h_out's first row is destination row out_base
+uint64_t layer_aggregate_temp_bytes(const dgi_graph* g, const dgi_layer_t* layer, int64_t b, int64_t e);
+dgi_status_t layer_aggregate_rows(const dgi_graph* g, const dgi_layer_t* layer, const void* Z, void* h_out, int64_t ld_out, int64_t out_base,
+                                  int64_t b, int64_t e, void* temp, uint64_t temp_bytes, hipStream_t s);
 
 // frees dgi_infer's cached arena (takes ws_mutex; dgi_infer_host calls it while holding hs_mutex)
 dgi_status_t release_infer_arena(const dgi_graph* g);

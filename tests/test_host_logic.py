@@ -33,7 +33,7 @@ def test_struct_sizes_match_header_layout():
     assert ctypes.sizeof(B.OptsStruct) == 7 * 8
     assert ctypes.sizeof(B.StatsStruct) == 8 + 8 + 16 * (8 * 8 + 4 * 3) + 16
     assert ctypes.sizeof(B.GraphInfoStruct) == 5 * 8 + 8 + 8
-    assert ctypes.sizeof(B.HostStatsStruct) == 8 + 8 + 16 * 8 * 7 + 4 * 8
+    assert ctypes.sizeof(B.HostStatsStruct) == 8 + 8 + 16 * 8 * 8 + 4 * 8
 
 
 def brute_batch_end(ip, limit, begin, n_t, n_i):
