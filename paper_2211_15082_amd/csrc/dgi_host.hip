@@ -257,6 +257,11 @@ dgi_status_t infer_host(const dgi_graph* g, const dgi_layer_t* layers, int32_t L
     const void* cur = x_dev;
     int64_t ld_cur = ld_x;
     int64_t k = 0;  // batch counter: slot k % n_slots
+    // Thresholds that planned the last batch filling at least half of M, and the bytes of an input row then: the next
+    // layer starts from them (rescaled by the row width) instead of climbing from the initial values again, which
+    // costs a few undersized batches per layer (Eq. 2 under-predicts: an input set grows more slowly than its batch).
+    int64_t carry_nt = 0, carry_ni = 0;
+    double carry_row = 0.0;
     for (int l = 0; l < L; ++l) {
         const dgi_layer_t& Ly = layers[l];
         const int xb = Ly.feat_dtype == DGI_BF16 ? 2 : 4, yb = Ly.out_dtype == DGI_BF16 ? 2 : 4;
@@ -319,6 +324,12 @@ dgi_status_t infer_host(const dgi_graph* g, const dgi_layer_t* layers, int32_t L
         int64_t n_t = o.batch_size > 0 ? o.batch_size : (all_fits ? N : (o.init_node_threshold > 0 ? o.init_node_threshold : 65536));
         int64_t n_i = (o.batch_size > 0 || all_fits) ? INT64_MAX / 4
                                        : (o.init_edge_threshold > 0 ? o.init_edge_threshold : (int64_t)std::max(1.0, (double)n_t * std::max(avg_deg, 1.0)));
+        const double row_now = (double)f_lds * f_eb;
+        if (o.batch_size == 0 && !all_fits && carry_nt > 0) {
+            const double sc_rows = carry_row / row_now;
+            n_t = (int64_t)std::min(4.0e18, std::max(1.0, (double)carry_nt * sc_rows));
+            n_i = (int64_t)std::min(4.0e18, std::max(1.0, (double)carry_ni * sc_rows));
+        }
         int64_t b = 0;
         while (b < N) {
             int64_t e = 0;
@@ -376,7 +387,10 @@ dgi_status_t infer_host(const dgi_graph* g, const dgi_layer_t* layers, int32_t L
             DGI_HIP(hipEventRecord(S.ev[3], sb));
             S.pending = true; S.dense = false; S.layer = l; S.n_sub = n_sub; S.rows = rows; S.M_k = M_k;
             S.in_bytes = n_sub * (int64_t)f_width * f_eb; S.out_bytes = rows * (int64_t)Ly.out_dim * yb;
-            if (o.batch_size == 0 && !all_fits) DGI_TRY(dgi_threshold_update((double)M, (double)M_k, &n_t, &n_i));  // Eq. 2
+            if (o.batch_size == 0 && !all_fits) {
+                if (2 * M_k >= M) { carry_nt = n_t; carry_ni = n_i; carry_row = row_now; }
+                DGI_TRY(dgi_threshold_update((double)M, (double)M_k, &n_t, &n_i));  // Eq. 2
+            }
             b = e;
             ++k;
         }

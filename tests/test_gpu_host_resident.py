@@ -82,7 +82,10 @@ def test_host_resident_inference_matches_the_oracle(kind):
     assert max_rel_err(out2.numpy(), want) <= TOL_F32
     # (launch overheads dominate batches this small, so the library keeps two of them in flight: M is half the budget)
     assert st2["slots"] == 2
-    assert all(nb >= 3 for nb in st2["batches"]) and st2["peak_batch_bytes"] <= st2["budget_bytes"] == 1_200_000 // 256 * 256
+    # (later layers start from the thresholds the previous layer settled on, rescaled by the row width, so a layer
+    # with narrow rows may need fewer batches)
+    assert st2["batches"][0] >= 3 and sum(st2["batches"]) >= 5, st2["batches"]
+    assert st2["peak_batch_bytes"] <= st2["budget_bytes"] == 1_200_000 // 256 * 256
     # a layer that multiplies first and whose transformed rows are clearly narrower than its input rows runs as a dense
     # pass over all rows plus batches that load the transformed rows: GCN 64 -> 16 (Z is 16 wide) and GAT 32 -> 16 with
     # one head (Z = [z | e_l | e_r] is 18 wide); GraphSAGE's [z_self | z_neigh] is as wide as its input, so it stays
