@@ -470,6 +470,41 @@ def test_fused_layer_with_eight_or_more_column_blocks(storage, dims, agg):
     assert max_rel_err(got, want) <= (TOL_BF16 if storage == "bf16" else TOL_F32)
 
 
+@pytest.mark.parametrize("order", ["agg_first_split", "agg_first_fused", "transform_first"])
+def test_graph_without_edges(order):
+    # every neighbourhood is empty: GraphSAGE keeps its own-feature term, GCN and GAT reduce to act(bias); also
+    # through dgi_infer, the sampler and the host-resident path
+    bd = B()
+    n = 300
+    indptr, indices = np.zeros(n + 1, np.int64), np.zeros(0, np.int32)
+    X = rnd((n, 64), 1)
+    g = bd.graph_load(indptr, indices)
+    layers = [dict(agg="mean", act="relu", W_self=rnd((64, 64), 2, 0.2), W_neigh=rnd((64, 64), 3, 0.2), bias=rnd((64,), 4), order=order),
+              dict(agg="gcn", act="none", W_neigh=rnd((64, 32), 5, 0.2), bias=rnd((32,), 6), order=order),
+              dict(agg="gat", act="elu", W_neigh=rnd((32, 32), 7, 0.3), heads=2, attn_src=rnd((2, 16), 8, 0.5), attn_dst=rnd((2, 16), 9, 0.5),
+                   bias=rnd((32,), 10))]
+    H = X
+    for L in layers:
+        want = oracle.layer_forward(indptr, indices, L, H)
+        got = gpu_layer(g, L, H)
+        assert max_rel_err(got, want) <= TOL_F32, L["agg"]
+        H = want.astype(np.float32)
+    want = oracle.infer(indptr, indices, layers, X)
+    assert np.allclose(want[0], want[-1])          # GCN and GAT after it see nothing but their biases
+    structs, keep = zip(*[bd.make_layer(L) for L in layers])
+    out = torch.full((n, 32), 777.0, dtype=torch.float32, device="cuda")
+    bd.infer(g, list(structs), torch.from_numpy(X).cuda(), out)
+    assert max_rel_err(out.cpu().numpy(), want) <= TOL_F32
+    out.fill_(777.0)
+    bd.infer_sampled(g, list(structs), torch.from_numpy(X).cuda(), out, fanout=3, seed=5)
+    assert max_rel_err(out.cpu().numpy(), want) <= TOL_F32
+    xh = torch.empty((n, 64), dtype=torch.float32, pin_memory=True)
+    xh.copy_(torch.from_numpy(X))
+    oh = torch.full((n, 32), 777.0, dtype=torch.float32, pin_memory=True)
+    bd.infer_host(g, list(structs), xh, oh, batch_size=100, stream_always=True)
+    assert max_rel_err(oh.numpy(), want) <= TOL_F32
+
+
 @pytest.mark.parametrize("k,scale", [(2, 0.05), (4, 0.002), (5, 0.02)])
 def test_device_side_input_generation_is_reproducible(k, scale):
     # the seeded generators must give the same graph and features on every run, also when they run on the GPU
