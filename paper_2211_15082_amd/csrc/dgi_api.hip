@@ -584,6 +584,23 @@ extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layer
             int64_t e = 0;
             DGI_TRY(dgi_plan_batch_end(g->h_indptr.data(), DGI_I64, N, b, std::min(std::max<int64_t>(n_t, 1), kMaxRowsPerLaunch * 4),
                                        std::max<int64_t>(n_i, 0), &e));
+            // With everything resident the temporaries of a planned batch are known before it runs, so the first batch
+            // of a layer applies Eq. 2 to its own plan (repeatedly: temporaries grow with the batch, but not in
+            // proportion) instead of running an undersized batch just to learn r.
+            if (o.batch_size == 0 && b == 0) {
+                const int64_t row_cap = kMaxRowsPerLaunch * 4;
+                for (int it = 0; it < 16 && e < N; ++it) {
+                    const uint64_t nd = batch_temp_bytes(g, &L, P, b, e);
+                    if (nd > temp_cap) break;  // the halving below takes over
+                    int64_t t2 = n_t, i2 = n_i, e2 = 0;
+                    if (nd == 0) { t2 = N; i2 = std::max<int64_t>(g->E, 1); }
+                    else DGI_TRY(dgi_threshold_update((double)temp_cap, (double)nd, &t2, &i2));
+                    if (t2 <= n_t && i2 <= n_i) break;
+                    DGI_TRY(dgi_plan_batch_end(g->h_indptr.data(), DGI_I64, N, b, std::min(std::max<int64_t>(t2, 1), row_cap), std::max<int64_t>(i2, 0), &e2));
+                    if (e2 <= e || batch_temp_bytes(g, &L, P, b, e2) > temp_cap) break;  // no growth, or growing overshoots
+                    n_t = t2; n_i = i2; e = e2;
+                }
+            }
             const uint64_t need = batch_temp_bytes(g, &L, P, b, e);
             if (need > temp_cap) {  // the batch would not fit: the out-of-memory reaction of Section 4.1
                 if (o.stats) o.stats->oom_retries += 1;

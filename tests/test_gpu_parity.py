@@ -248,7 +248,14 @@ def test_batch_size_invariance_is_bitwise():
         assert np.array_equal(got, ref), bs
     got, stats = run_infer(cfg, batch_size=0, init_node_threshold=16, mem_budget_bytes=6_000_000)
     assert np.array_equal(got, ref)
-    assert stats["batches"][0] > 1
+    assert stats["batches"] == [1, 1]   # nothing to bound (fused layer, transform-first layer): Eq. 2 on the plan takes all rows at once
+    # dynamic batches that the budget really limits: the unfused path's aggregated tile (2.56 MB for all rows) against
+    # about 1.1 MB left of the budget
+    cfg["layers"][0]["order"] = "agg_first_split"
+    ref2, _ = run_infer(cfg, batch_size=cfg["num_nodes"])
+    got, stats = run_infer(cfg, batch_size=0, init_node_threshold=16, mem_budget_bytes=5_000_000)
+    assert np.array_equal(got, ref2)
+    assert stats["batches"][0] > 1 and stats["fused"] == [0, 0]
 
 
 def test_memory_budget_forces_small_batches_and_oom_is_reported():
