@@ -147,6 +147,12 @@ def test_host_resident_bf16_and_argument_checks():
     st = bd.infer_host(g, list(structs), x, out, batch_size=1000, stream_always=True)
     assert st["batches"] == [3, 3]
     assert max_rel_err(out.numpy(), want) <= TOL_BF16
+    # a budget that forces several batches: the 64 -> 24 layer then runs as a dense pass ([z_self | z_neigh] is 48 wide,
+    # three quarters of its input) plus batches that load rows of Z, stored in bf16 like the device-resident path's Z
+    out_b = torch.empty((n, 24), dtype=torch.float32, pin_memory=True)
+    st_b = bd.infer_host(g, list(structs), x, out_b, mem_budget_bytes=600_000, stream_always=True)
+    assert max_rel_err(out_b.numpy(), want) <= TOL_BF16
+    assert st_b["transform_bytes"] == [0, n * (64 + 48) * 2] and min(st_b["batches"]) >= 2
     # an empty graph is a no-op
     g0 = bd.graph_load(np.zeros(1, np.int64), np.zeros(0, np.int32))
     st0 = bd.infer_host(g0, list(structs), torch.empty((0, 64), dtype=torch.bfloat16, pin_memory=True),
