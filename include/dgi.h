@@ -129,7 +129,9 @@ typedef struct {
     uint64_t mem_budget_bytes;     /* bytes the call may allocate for hidden layers + temporaries;
                                       0 = 90 % of the currently free device memory (Sec. 4.1) */
     dgi_stats_t* stats;            /* HOST, or NULL.  Setting it makes dgi_infer wait for completion. */
-    int64_t init_node_threshold;   /* initial n_t of Eq. 2 for batch_size==0; 0 = 65536 */
+    int64_t init_node_threshold;   /* initial n_t of Eq. 2 for batch_size==0; 0 = 65536.  dgi_infer knows a planned batch's
+                                      temporaries before it runs, so the first batch of a layer is rescaled by Eq. 2 on its
+                                      plan (it is not launched undersized); dgi_infer_host rescales after each batch */
     int64_t init_edge_threshold;   /* initial n_i of Eq. 2; 0 = init_node_threshold * average degree */
     int32_t jk_concat;             /* 1: jumping-knowledge stack (the paper's JKNet): layers 0..L-2 form a chain and the
                                       last layer reads the concatenation of all their outputs, so layers[L-1].in_dim must
