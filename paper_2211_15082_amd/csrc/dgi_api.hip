@@ -58,6 +58,10 @@ struct LayerPlan {
 //   GCN fp32 256->256, degree 52 (ratio 6.5): 18.8 vs 22.0 ms;  GraphSAGE fp32 256->256, degree 20 (ratio 1.25):
 //   125 vs 133 ms;  GraphSAGE bf16 128->128, degree 14 (ratio 1.8): 155 vs 118 ms.
 // The split path's fp32 GEMM is MFMA-bound and expensive, its bf16 GEMM is cheap, hence the two thresholds.
+// The fp32 threshold comes from a 20 M-node graph sampled down to average degrees 2..12 (fused / split, ms per layer):
+//   GraphSAGE 256->256 (threshold ratio 1 = degree 16): degree 2 62/60, 4 63/66, 6 64/74, 8 66/82, 12 77/95;
+//   GCN 256->256 (degree 8): 2 41/41, 4 43/46, 6 45/53, 8 48/61;  GraphSAGE 128->128 (degree 8): 4 26/26, 6 27/28, 8 28/32;
+//   GraphSAGE 128->256 (degree 16): 6 41/40, 8 42/43, 12 44/51.  The crossovers sit at ratios 0.2-0.6: 0.5 it is.
 // DGI_TUNE_FUSED = 0 / 2 forces never / always (tuning aid).
 bool want_fused(const dgi_graph* g, int dtype, int K, int64_t ldw, int N) {
     static const int mode = [] { const char* e = getenv("DGI_TUNE_FUSED"); return e ? atoi(e) : 1; }();
@@ -65,7 +69,7 @@ bool want_fused(const dgi_graph* g, int dtype, int K, int64_t ldw, int N) {
     if (mode == 2) return true;
     const double avg_deg = g && g->N > 0 ? (double)g->E / (double)g->N : 0.0;
     const double ratio = avg_deg * (double)K / ((double)ldw * (double)N / 32.0);
-    return ratio >= (dtype == DGI_BF16 ? 3.0 : 1.0);
+    return ratio >= (dtype == DGI_BF16 ? 3.0 : 0.5);
 }
 
 dgi_status_t validate_layer(const dgi_layer_t* L) {
