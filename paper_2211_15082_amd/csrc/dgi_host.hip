@@ -279,7 +279,7 @@ dgi_status_t infer_host(const dgi_graph* g, const dgi_layer_t* layers, int32_t L
         TransformInfo ti{};
         DGI_TRY(layer_transform_info(g, &Ly, &ti));
         const int zb = ti.z_dtype == DGI_BF16 ? 2 : 4;
-        const bool two_pass = !all_fits && ti.transform_first && (uint64_t)ti.z_ld * zb * 4 <= (uint64_t)ld_xs * xb * 3;
+        bool two_pass = !all_fits && ti.transform_first && (uint64_t)ti.z_ld * zb * 4 <= (uint64_t)ld_xs * xb * 3;
         const void* f_src = cur;        // where the batches' input rows come from
         int64_t f_ld = ld_cur, f_lds = ld_xs;
         int f_width = Ly.in_dim, f_eb = xb;
@@ -287,9 +287,16 @@ dgi_status_t infer_host(const dgi_graph* g, const dgi_layer_t* layers, int32_t L
             const uint64_t z_bytes = (uint64_t)N * ti.z_ld * zb;
             if (g->hs_z_bytes < z_bytes) {
                 (void)hipHostFree(g->hs_z); g->hs_z = nullptr; g->hs_z_bytes = 0;
-                DGI_HIP(hipHostMalloc(&g->hs_z, (size_t)z_bytes, hipHostMallocDefault));
-                g->hs_z_bytes = z_bytes;
+                if (hipHostMalloc(&g->hs_z, (size_t)z_bytes, hipHostMallocDefault) == hipSuccess) {
+                    g->hs_z_bytes = z_bytes;
+                } else {  // no page-locked memory left for Z: the layer runs in one pass over its input rows
+                    (void)hipGetLastError();
+                    g->hs_z = nullptr;
+                    two_pass = false;
+                }
             }
+        }
+        if (two_pass) {
             char* z_host = static_cast<char*>(g->hs_z);
             char* z_dev = nullptr;
             DGI_HIP(hipHostGetDevicePointer(reinterpret_cast<void**>(&z_dev), z_host, 0));
