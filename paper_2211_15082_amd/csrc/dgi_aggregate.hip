@@ -33,6 +33,9 @@ namespace {
 #ifndef DGI_UNROLL_WIDE
 #define DGI_UNROLL_WIDE 8        // row loads in flight per lane when a whole wavefront covers one source row
 #endif
+#ifndef DGI_FUSED_RING_STEPS
+#define DGI_FUSED_RING_STEPS 2   // K steps per batch of weight fragments in the fused kernel's transform phase
+#endif
 constexpr int kWaves = 4;        // wavefronts per workgroup
 constexpr int kRowsPerWg = 16;   // destination rows per workgroup (wide rows)
 // Narrow rows (G <= 16 lanes per source row): every lane group owns its own destination row, so a wavefront
@@ -712,17 +715,35 @@ void fused_layer_kernel(FusedParams fp) {
         // loop over the whole LDS row [h_v | m_v] against columns [0, 2 Kp) (the host checks K1p == Kp)
         const int lsteps = SL ? 2 * ksteps : ksteps;
         const int wks = SL ? 0 : fp.K1p / (2 * VEC);  // first K step of the block in the fragment-order weight
-        for (int ks = resumed ? ksteps : 0; ks < lsteps; ks += U) {
-            uint4 a[U], b[U];
+        // The weight fragments come from L2 with a latency of a microsecond or more while other workgroups gather:
+        // three batches of R steps rotate, two on their way while the third is in the matrix cores (R = 2 keeps the
+        // registers of this phase below those of the gather phase, so the kernel's occupancy does not change).
+        constexpr int R = DGI_FUSED_RING_STEPS;
+        auto load_b = [&](uint4 (&b)[R], int ks) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int k = (ks + u) * 2 * VEC;
-                const bool in = ks + u < lsteps;
-                b[u] = in ? *reinterpret_cast<const uint4*>(w + (int64_t)(wks + ks + u) * 64 * VEC) : make_uint4(0u, 0u, 0u, 0u);
-                a[u] = in ? *reinterpret_cast<const uint4*>(a_lds + k) : make_uint4(0u, 0u, 0u, 0u);
-            }
+            for (int u = 0; u < R; ++u)
+                b[u] = ks + u < lsteps ? *reinterpret_cast<const uint4*>(w + (int64_t)(wks + ks + u) * 64 * VEC) : make_uint4(0u, 0u, 0u, 0u);
+        };
+        auto batch = [&](const uint4 (&b)[R], int ks) {  // R steps from K step ks on (wave-uniform guard)
+            if (ks >= lsteps) return;
+            uint4 a[R];
 #pragma unroll
-            for (int u = 0; u < U; ++u) mma(acc, a[u], b[u]);
+            for (int u = 0; u < R; ++u)
+                a[u] = ks + u < lsteps ? *reinterpret_cast<const uint4*>(a_lds + (ks + u) * 2 * VEC) : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+            for (int u = 0; u < R; ++u) mma(acc, a[u], b[u]);
+        };
+        const int ks0 = resumed ? ksteps : 0;
+        uint4 b0[R], b1[R], b2[R];
+        load_b(b0, ks0);
+        load_b(b1, ks0 + R);
+        for (int ks = ks0; ks < lsteps; ks += 3 * R) {
+            load_b(b2, ks + 2 * R);
+            batch(b0, ks);
+            load_b(b0, ks + 3 * R);
+            batch(b1, ks + R);
+            load_b(b1, ks + 4 * R);
+            batch(b2, ks + 2 * R);
         }
         if (n < fp.N) {
             const float bias = fp.bias ? fp.bias[n] : 0.f;
