@@ -141,7 +141,7 @@ def host_resident(args, cfg, g, structs, B):
     here includes those transfers; it is a separate line, never the headline value."""
     import torch
     n, e = cfg["num_nodes"], int(cfg["indices"].numel())
-    x = torch.empty(cfg["x"].shape, dtype=cfg["x"].dtype, pin_memory=True)
+    x = B.pinned_empty(tuple(cfg["x"].shape), cfg["x"].dtype)   # exactly sized (torch's pinned allocator rounds up to 2^k)
     reorder_seconds = 0.0
     if args.reorder != "none":
         # Section 4.2: renumber the nodes once so that batches of consecutive ids share inputs; x goes in in the new
@@ -156,7 +156,7 @@ def host_resident(args, cfg, g, structs, B):
         del xp
     else:
         x.copy_(cfg["x"])
-    out = torch.empty((n, structs[-1].out_dim), dtype=torch.float32, pin_memory=True)
+    out = B.pinned_empty((n, structs[-1].out_dim), torch.float32)
     budget = int(args.device_budget_gb * 1e9)
     kw = dict(batch_size=args.batch_size, mem_budget_bytes=budget, stream_always=not args.allow_device_resident)
     for _ in range(max(args.warmup, 1)):

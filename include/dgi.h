@@ -320,6 +320,13 @@ dgi_status_t dgi_batch_input_set_size(int64_t num_nodes, const int64_t* indptr, 
 dgi_status_t dgi_reorder_permutation(int64_t num_nodes, const int64_t* indptr, const int32_t* indices,
                                      int32_t method, uint64_t seed, int32_t* perm_new_of_old);
 
+/* Page-locked host memory of exactly `bytes` bytes for dgi_infer_host's x_host / out_host (hipHostMalloc; any other
+ * page-locked allocation serves as well — this pair exists for callers whose framework's pinned allocator rounds
+ * sizes up, which at tens of gigabytes decides whether the matrices of Algorithm 2 fit the lockable memory).
+ * dgi_host_free(NULL) is a no-op. */
+dgi_status_t dgi_host_alloc(uint64_t bytes, void** ptr);
+dgi_status_t dgi_host_free(void* ptr);
+
 const char* dgi_status_string(dgi_status_t s);
 const char* dgi_last_error(void);  /* thread-local, never NULL */
 int32_t     dgi_version(void);     /* major*1000 + minor */

@@ -92,7 +92,7 @@ EXPORTS = [
     "dgi_graph_load", "dgi_graph_free", "dgi_graph_release_workspace", "dgi_graph_info", "dgi_graph_vector", "dgi_graph_csr", "dgi_graph_reorder",
     "dgi_layer_forward", "dgi_layer_workspace_bytes", "dgi_infer", "dgi_infer_partial", "dgi_infer_host", "dgi_graph_sample", "dgi_infer_sampled", "dgi_plan_batch_end", "dgi_threshold_update",
     "dgi_threshold_halve", "dgi_batch_input_set_size", "dgi_reorder_permutation", "dgi_status_string",
-    "dgi_last_error", "dgi_version",
+    "dgi_last_error", "dgi_version", "dgi_host_alloc", "dgi_host_free",
 ]
 
 if not os.path.exists(LIB_PATH):
@@ -341,6 +341,33 @@ def infer_host(graph, layer_structs, x_host, out_host, batch_size=0, mem_budget_
     n = hs.num_layers
     return {k: (list(getattr(hs, k))[:n] if hasattr(getattr(hs, k), "__len__") else getattr(hs, k))
             for k, _ in HostStatsStruct._fields_ if k != "reserved"}
+
+
+class _PinnedBlock:
+    """Owner of one dgi_host_alloc block; frees it when the last tensor viewing it is gone."""
+
+    def __init__(self, nbytes):
+        p = ctypes.c_void_p()
+        _check(_lib.dgi_host_alloc(ctypes.c_uint64(nbytes), ctypes.byref(p)))
+        self.ptr, self.nbytes = p.value, nbytes
+
+    def __del__(self):
+        if getattr(self, "ptr", None):
+            _lib.dgi_host_free(ctypes.c_void_p(self.ptr))
+            self.ptr = None
+
+
+def pinned_empty(shape, dtype):
+    """A page-locked host tensor of exactly the requested size (torch's pinned allocator rounds sizes up to a power
+    of two; at tens of gigabytes that is what runs the box out of lockable memory)."""
+    import torch
+    n = 1
+    for d in shape:
+        n *= int(d)
+    block = _PinnedBlock(n * torch.empty((), dtype=dtype).element_size())
+    buf = (ctypes.c_ubyte * max(block.nbytes, 1)).from_address(block.ptr)
+    buf._dgi_block = block  # the tensor's storage holds `buf`, and `buf` holds the block: freed with the last view
+    return torch.frombuffer(buf, dtype=dtype, count=n).reshape(*shape)
 
 
 # ---- host-side planning helpers (no device access) ------------------------------------------------------

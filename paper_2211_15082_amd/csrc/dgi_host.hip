@@ -416,6 +416,24 @@ dgi_status_t infer_host(const dgi_graph* g, const dgi_layer_t* layers, int32_t L
 
 using namespace dgi;
 
+extern "C" dgi_status_t dgi_host_alloc(uint64_t bytes, void** ptr) {
+    DGI_REQUIRE(ptr != nullptr, DGI_ERR_INVALID_ARG, "host_alloc: NULL argument");
+    *ptr = nullptr;
+    const hipError_t e = hipHostMalloc(ptr, (size_t)std::max<uint64_t>(bytes, 16), hipHostMallocDefault);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        *ptr = nullptr;
+        set_error("host_alloc: %llu bytes of page-locked memory: %s", (unsigned long long)bytes, hipGetErrorString(e));
+        return DGI_ERR_OOM;
+    }
+    return DGI_OK;
+}
+
+extern "C" dgi_status_t dgi_host_free(void* ptr) {
+    if (ptr) DGI_HIP(hipHostFree(ptr));
+    return DGI_OK;
+}
+
 extern "C" dgi_status_t dgi_infer_host(const dgi_graph_t* g, const dgi_layer_t* layers, int32_t num_layers, const void* x_host,
                                        int64_t ld_x, void* out_host, int64_t ld_out, const dgi_infer_opts_t* opts,
                                        dgi_host_stats_t* hstats, void* hip_stream) {

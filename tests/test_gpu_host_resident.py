@@ -189,3 +189,29 @@ def test_reordering_shrinks_the_input_sets_of_fixed_batches():
     st2 = bd.infer_host(g2, list(structs), pinned(X2), out2, batch_size=2000, stream_always=True)
     assert max_rel_err(out2.numpy()[p], out.numpy()) <= TOL_F32          # the same model output, row for row
     assert st2["input_rows"][0] < 0.85 * st["input_rows"][0], (st["input_rows"], st2["input_rows"])
+
+
+def test_exactly_sized_page_locked_buffers_from_the_library():
+    # dgi_host_alloc / dgi_host_free behind binding.pinned_empty: accepted by dgi_infer_host like torch's pinned tensors
+    import gc
+    bd = B()
+    n = 2000
+    indptr, indices = random_csr(n, 5.0, seed=41)
+    X = rnd((n, 48), 1)
+    layers = [dict(agg="mean", act="relu", W_self=rnd((48, 32), 2, 0.2), W_neigh=rnd((48, 32), 3, 0.2), bias=rnd((32,), 4)),
+              dict(agg="gcn", act="none", W_neigh=rnd((32, 8), 5, 0.2), bias=None)]
+    want = oracle.infer(indptr, indices, layers, X)
+    g = bd.graph_load(indptr, indices)
+    structs, keep = zip(*[bd.make_layer(L) for L in layers])
+    x = bd.pinned_empty((n, 48), torch.float32)
+    x.copy_(torch.from_numpy(X))
+    out = bd.pinned_empty((n, 8), torch.float32)
+    out.fill_(777.0)
+    st = bd.infer_host(g, list(structs), x, out, mem_budget_bytes=700_000, stream_always=True)
+    assert st["device_resident"] == 0 and max_rel_err(out.numpy(), want) <= TOL_F32
+    view = out[:10]          # a view keeps the block alive after the first tensor object is gone
+    del out
+    gc.collect()
+    assert max_rel_err(view.numpy(), want[:10]) <= TOL_F32
+    del view, x
+    gc.collect()

@@ -190,6 +190,8 @@ def test_argument_validation_fails_before_any_device_work():
     assert lib.dgi_layer_forward(None, None, None, 0, None, 0, 0, 0, None, 0, None) == B.ERR_INVALID_ARG
     assert lib.dgi_infer_partial(None, None, 1, None, 0, None, 0, None, 0, None, None, None) == B.ERR_INVALID_ARG
     assert lib.dgi_infer_host(None, None, 1, None, 0, None, 0, None, None, None) == B.ERR_INVALID_ARG
+    assert lib.dgi_host_alloc(ctypes.c_uint64(64), None) == B.ERR_INVALID_ARG
+    assert lib.dgi_host_free(None) == B.OK
     assert lib.dgi_graph_sample(None, 10, ctypes.c_uint64(1), 0, None, None) == B.ERR_INVALID_ARG
     assert lib.dgi_infer_sampled(None, None, 1, None, 0, None, 0, 10, ctypes.c_uint64(1), None, None) == B.ERR_INVALID_ARG
     with pytest.raises(B.DgiError) as ei:
