@@ -252,7 +252,8 @@ dgi_status_t dgi_infer_partial(const dgi_graph_t* g, const dgi_layer_t* layers, 
  * three quarters as wide as its input rows runs as two passes when it needs more than one batch: H^{l-1} streams
  * through the device once in contiguous row chunks and Z = H^{l-1} W goes to a page-locked buffer, then the
  * batches load rows of Z for their input sets and only aggregate (input_bytes counts rows of Z, transform_bytes
- * the dense pass).
+ * the dense pass).  For GraphSAGE the batches load only the z_neigh block of those rows (that block's width is what
+ * the three-quarters rule compares) plus the z_self block of their own destination rows, a contiguous run.
  * When the whole graph fits M, every layer is one batch; when x, the output and dgi_infer's own buffers all fit
  * the budget, the call is one copy in, dgi_infer, one copy out (hstats->device_resident = 1) and the hidden
  * layers never leave the device (opts->host_stream_always = 1 switches that off).  opts->batch_size > 0 fixes

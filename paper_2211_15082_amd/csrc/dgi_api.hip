@@ -394,6 +394,8 @@ dgi_status_t dgi::layer_transform_info(const dgi_graph* g, const dgi_layer_t* la
     info->transform_first = P.transform_first;
     info->z_cols = P.z_cols; info->z_ld = P.z_ld; info->z_dtype = P.z_dtype;
     info->weight_bytes = P.wt_bytes;
+    info->has_self = P.has_self && !P.gat;
+    info->z_neigh_col = P.z_neigh_col;
     return DGI_OK;
 }
 
@@ -427,6 +429,33 @@ dgi_status_t dgi::layer_aggregate_rows(const dgi_graph* g, const dgi_layer_t* la
     DGI_REQUIRE(temp != nullptr && (uintptr_t)temp % 256 == 0 && temp_bytes >= batch_temp_bytes(g, layer, P, b, e), DGI_ERR_INVALID_ARG,
                 "layer_aggregate_rows: temporary buffer missing, misaligned or too small");
     return run_batch(g, layer, P, nullptr, 0, h_out, ld_out, b, e, nullptr, Z, temp, s, nullptr, false, nullptr, out_base);
+}
+
+dgi_status_t dgi::layer_aggregate_rows_split(const dgi_graph* g, const dgi_layer_t* layer, const void* Zn, int64_t ld_n, const void* Zs, int64_t ld_s,
+                                             void* h_out, int64_t ld_out, int64_t out_base, int64_t b, int64_t e, void* temp, uint64_t temp_bytes,
+                                             hipStream_t s) {
+    LayerPlan P;
+    DGI_TRY(plan_layer(g, layer, reinterpret_cast<const void*>(16), 0, &P));
+    DGI_REQUIRE(P.transform_first && !P.gat && P.has_self, DGI_ERR_INVALID_ARG, "layer_aggregate_rows_split: not a transform-first GraphSAGE layer");
+    DGI_REQUIRE(b >= 0 && e >= b && e <= g->N, DGI_ERR_INVALID_ARG, "layer_aggregate_rows_split: bad destination range");
+    if (e == b) return DGI_OK;
+    DGI_REQUIRE(Zn != nullptr && Zs != nullptr && ld_n >= layer->out_dim && ld_s >= layer->out_dim, DGI_ERR_INVALID_ARG,
+                "layer_aggregate_rows_split: NULL matrix or leading dimension too small");
+    DGI_TRY(check_matrix(h_out, ld_out, layer->out_dim, "h_out"));
+    const uint64_t part_bytes = round_up((int64_t)agg_hub_partial_bytes(g, b, e, layer->out_dim), 256);
+    DGI_REQUIRE(part_bytes == 0 || (temp != nullptr && (uintptr_t)temp % 256 == 0 && temp_bytes >= part_bytes), DGI_ERR_INVALID_ARG,
+                "layer_aggregate_rows_split: temporary buffer missing, misaligned or too small");
+    const int zb = elem_bytes(P.z_dtype), ob = elem_bytes(layer->out_dtype);
+    AggArgs a;
+    a.g = g; a.mode = P.mode; a.row_begin = b; a.row_end = e;
+    a.hub_partials = part_bytes ? (float*)temp : nullptr;
+    a.S = Zn; a.ld_s = ld_n; a.s_dtype = P.z_dtype; a.width = layer->out_dim;
+    // the kernels address the own-feature addend by destination row: row v of `self` is row v - b of Zs
+    a.self = (const char*)Zs - b * ld_s * zb; a.ld_self = ld_s;
+    a.out = (char*)h_out + (b - out_base) * ld_out * ob; a.ld_out = ld_out; a.out_row0 = b; a.out_dtype = layer->out_dtype;
+    a.bias = layer->bias; a.act = layer->act; a.act_slope = layer->act_slope; a.out_scale = nullptr;
+    DGI_TRY(launch_aggregate(a, 0, s));
+    return launch_aggregate(a, 1, s);
 }
 
 extern "C" dgi_status_t dgi_layer_forward(const dgi_graph_t* g, const dgi_layer_t* layer, const void* h_in, int64_t ld_in,

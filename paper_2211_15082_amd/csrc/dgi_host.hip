@@ -279,7 +279,12 @@ dgi_status_t infer_host(const dgi_graph* g, const dgi_layer_t* layers, int32_t L
         TransformInfo ti{};
         DGI_TRY(layer_transform_info(g, &Ly, &ti));
         const int zb = ti.z_dtype == DGI_BF16 ? 2 : 4;
-        bool two_pass = !all_fits && ti.transform_first && (uint64_t)ti.z_ld * zb * 4 <= (uint64_t)ld_xs * xb * 3;
+        // (GraphSAGE: the batches gather only the z_neigh block of a transformed row; z_self is needed for the batch's own
+        // rows alone, which are one contiguous run of Z)
+        const int64_t ld_zn = round_up(Ly.out_dim, 16 / zb);
+        const uint64_t gathered_row = ti.has_self ? (uint64_t)ld_zn * zb : (uint64_t)ti.z_ld * zb;
+        bool two_pass = !all_fits && ti.transform_first && gathered_row * 4 <= (uint64_t)ld_xs * xb * 3;
+        const char* z_rows = nullptr;   // device view of Z in host memory (two passes)
         const void* f_src = cur;        // where the batches' input rows come from
         int64_t f_ld = ld_cur, f_lds = ld_xs;
         int f_width = Ly.in_dim, f_eb = xb;
@@ -324,8 +329,10 @@ dgi_status_t infer_host(const dgi_graph* g, const dgi_layer_t* layers, int32_t L
                 ++k;
             }
             for (int i = 0; i < n_slots; ++i) DGI_TRY(slot[i].retire(hs));  // the batches read all of Z
+            z_rows = z_dev;
             f_src = z_dev; f_ld = ti.z_ld; f_lds = ti.z_ld; f_eb = zb;
             f_width = (int)ti.z_ld;  // whole padded rows: 16-byte pieces over the link (the padding columns are never read)
+            if (ti.has_self) { f_src = z_dev + (size_t)ti.z_neigh_col * zb; f_lds = ld_zn; f_width = (int)ld_zn; }
         }
 
         int64_t n_t = o.batch_size > 0 ? o.batch_size : (all_fits ? N : (o.init_node_threshold > 0 ? o.init_node_threshold : 65536));
@@ -365,6 +372,8 @@ dgi_status_t infer_host(const dgi_graph* g, const dgi_layer_t* layers, int32_t L
             auto carve = [&](uint64_t bytes) { const uint64_t at = off; off += (uint64_t)round_up((int64_t)std::max<uint64_t>(bytes, 16), 256); return at; };
             const uint64_t o_idx = carve((uint64_t)e_b * 4), o_ptr = carve((uint64_t)(n_sub + 1) * 8), o_deg = carve((uint64_t)(n_sub + 1) * 8);
             const uint64_t o_U = carve((uint64_t)n_sub * 4), o_x = carve((uint64_t)n_sub * f_lds * f_eb), o_y = carve((uint64_t)rows * ld_os * yb);
+            const bool split_z = two_pass && ti.has_self;
+            const uint64_t o_zs = carve(split_z ? (uint64_t)rows * ld_zn * zb : 0);  // z_self of the batch's own rows
             if (off > M) { DGI_TRY(shrink()); continue; }
             char* A = S.mem;
             int64_t e_sub = 0;
@@ -383,17 +392,22 @@ dgi_status_t infer_host(const dgi_graph* g, const dgi_layer_t* layers, int32_t L
             if (M_k > M) { S.sub.reset(); DGI_TRY(shrink()); continue; }
             // ---- (ii) rows of the input set, read from host memory by the device --------------------------------------
             DGI_TRY(launch_permute_rows(f_src, f_ld, A + o_x, f_lds, n_sub, f_width, f_eb, (const int32_t*)(A + o_U), true, sa));
+            if (split_z)
+                DGI_TRY(launch_permute_rows(z_rows + (size_t)b * ti.z_ld * zb, ti.z_ld, A + o_zs, ld_zn, rows, (int)ld_zn, zb,
+                                            nullptr, true, sa));
             DGI_HIP(hipEventRecord(S.ev[1], sa));
             // ---- (iii) the layer on the sub-problem, on the second stream; the output buffer starts at row lb ----------------
             DGI_HIP(hipStreamWaitEvent(sb, S.ev[1], 0));
-            if (two_pass) DGI_TRY(layer_aggregate_rows(S.sub.g, &Ly, A + o_x, A + o_y, ld_os, lb, lb, lb + rows, A + o_ws, ws_bytes, sb));
+            if (split_z)
+                DGI_TRY(layer_aggregate_rows_split(S.sub.g, &Ly, A + o_x, ld_zn, A + o_zs, ld_zn, A + o_y, ld_os, lb, lb, lb + rows, A + o_ws, ws_bytes, sb));
+            else if (two_pass) DGI_TRY(layer_aggregate_rows(S.sub.g, &Ly, A + o_x, A + o_y, ld_os, lb, lb, lb + rows, A + o_ws, ws_bytes, sb));
             else DGI_TRY(layer_forward_rows(S.sub.g, &Ly, A + o_x, ld_xs, A + o_y, ld_os, lb, lb, lb + rows, A + o_ws, ws_bytes, sb));
             DGI_HIP(hipEventRecord(S.ev[2], sb));
             // ---- (iv) dump the batch's rows ------------------------------------------------------------------------------
             DGI_TRY(store_rows(A + o_y, ld_os, dst_host + (size_t)b * ld_dst * yb, dst_dev + (size_t)b * ld_dst * yb, ld_dst, rows, Ly.out_dim, yb, sb));
             DGI_HIP(hipEventRecord(S.ev[3], sb));
             S.pending = true; S.dense = false; S.layer = l; S.n_sub = n_sub; S.rows = rows; S.M_k = M_k;
-            S.in_bytes = n_sub * (int64_t)f_width * f_eb; S.out_bytes = rows * (int64_t)Ly.out_dim * yb;
+            S.in_bytes = n_sub * (int64_t)f_width * f_eb + (split_z ? rows * ld_zn * zb : 0); S.out_bytes = rows * (int64_t)Ly.out_dim * yb;
             if (o.batch_size == 0 && !all_fits) {
                 if (2 * M_k >= M) { carry_nt = n_t; carry_ni = n_i; carry_row = row_now; }
                 DGI_TRY(dgi_threshold_update((double)M, (double)M_k, &n_t, &n_i));  // Eq. 2

@@ -224,6 +224,8 @@ struct TransformInfo {
     int64_t z_ld;
     int z_dtype;
     uint64_t weight_bytes;  // device scratch layer_transform_rows needs for the packed weights
+    bool has_self;          // GraphSAGE: columns [0, z_neigh_col) hold z_self, the rest z_neigh
+    int z_neigh_col;
 };
 dgi_status_t layer_transform_info(const dgi_graph* g, const dgi_layer_t* layer, TransformInfo* info);
 // Z[0:rows) = H[0:rows) W  (h_in, Z, weights: DEVICE; weights 256-byte aligned, info.weight_bytes long)
@@ -232,6 +234,11 @@ dgi_status_t layer_transform_rows(const dgi_graph* g, const dgi_layer_t* layer, 
 // destination rows [b, e) of g from transformed rows Z (one per node of g, leading dimension info.z_ld); temp as sized
 // by layer_aggregate_temp_bytes; h_out's first row is destination row out_base
 uint64_t layer_aggregate_temp_bytes(const dgi_graph* g, const dgi_layer_t* layer, int64_t b, int64_t e);
+// The same for a GraphSAGE layer with the two blocks of Z in separate matrices: Zn holds z_neigh of every node of g
+// (leading dimension ld_n), Zs holds z_self of the destination rows only, its first row being row b (ld_s).
+dgi_status_t layer_aggregate_rows_split(const dgi_graph* g, const dgi_layer_t* layer, const void* Zn, int64_t ld_n, const void* Zs, int64_t ld_s,
+                                        void* h_out, int64_t ld_out, int64_t out_base, int64_t b, int64_t e, void* temp, uint64_t temp_bytes,
+                                        hipStream_t s);
 dgi_status_t layer_aggregate_rows(const dgi_graph* g, const dgi_layer_t* layer, const void* Z, void* h_out, int64_t ld_out, int64_t out_base,
                                   int64_t b, int64_t e, void* temp, uint64_t temp_bytes, hipStream_t s);
 

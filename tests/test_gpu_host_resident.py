@@ -88,11 +88,14 @@ def test_host_resident_inference_matches_the_oracle(kind):
     assert st2["peak_batch_bytes"] <= st2["budget_bytes"] == 1_200_000 // 256 * 256
     # a layer that multiplies first and whose transformed rows are clearly narrower than its input rows runs as a dense
     # pass over all rows plus batches that load the transformed rows: GCN 64 -> 16 (Z is 16 wide) and GAT 32 -> 16 with
-    # one head (Z = [z | e_l | e_r] is 18 wide); GraphSAGE's [z_self | z_neigh] is as wide as its input, so it stays
-    dense = {"sage": [0, 0, 0], "gcn": [0, n * (64 + 16) * 4], "gat": [0, n * (32 + 18) * 4]}[kind]
+    # one head (Z = [z | e_l | e_r] is 18 wide); GraphSAGE 48 -> 24 and 24 -> 16, whose batches gather the z_neigh block
+    # only (24 and 16 wide) and read z_self for their own rows
+    dense = {"sage": [0, n * (48 + 48) * 4, n * (24 + 32) * 4], "gcn": [0, n * (64 + 16) * 4], "gat": [0, n * (32 + 18) * 4]}[kind]
     assert st2["transform_bytes"] == dense and st["transform_bytes"] == [0] * len(layers)
     if kind == "gcn":
         assert st2["input_bytes"][1] == st2["input_rows"][1] * 16 * 4
+    if kind == "sage":   # z_neigh rows of the input sets + z_self rows of the destination rows
+        assert st2["input_bytes"][1] == (st2["input_rows"][1] + n) * 24 * 4
     # hidden layers kept in host memory although a whole layer fits a slot: one batch per layer
     out3 = torch.full((n, 16), 777.0, dtype=torch.float32, pin_memory=True)
     st3 = bd.infer_host(g, list(structs), x, out3, stream_always=True)
