@@ -489,12 +489,17 @@ extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layer
         DGI_REQUIRE(layers[num_layers - 1].in_dim == ld_cat && layers[num_layers - 1].feat_dtype == hd, DGI_ERR_INVALID_ARG,
                     "infer: the last jumping-knowledge layer must read the concatenation of all earlier outputs");
     }
+    // A first GCN layer gathers rows that already carry d_out(u)^-1/2 from a scaled copy of x (one pass over x:
+    // 2 N ld bytes) instead of fetching the factor per edge (a 128-byte line for 4 bytes on most edges).  With few
+    // edges per node (a sampled graph) the copy costs more than the per-edge fetches; then the layer keeps them.
+    const bool scale_x = layers[0].agg == DGI_AGG_GCN && !jk &&
+                         (double)g->E * 128.0 >= 2.0 * (double)g->N * (double)round_up(layers[0].in_dim, 16 / elem_bytes(layers[0].feat_dtype)) *
+                                                     elem_bytes(layers[0].feat_dtype);
     std::vector<LayerPlan> plans((size_t)num_layers);
     for (int l = 0; l < num_layers; ++l) {
         // layer 0 reads the caller's x; later layers read the library's own 16-byte aligned hidden buffers.  With a
         // permutation, layer 0 reads the library's permuted copy of x instead.
-        const bool scaled_x = layers[0].agg == DGI_AGG_GCN && !jk;
-        const bool own_input = l > 0 || o.perm_new_of_old || scaled_x;
+        const bool own_input = l > 0 || o.perm_new_of_old || scale_x;
         const int64_t own_ld = (jk && l > 0) ? ld_cat : round_up(layers[l].in_dim, 16 / elem_bytes(layers[l].feat_dtype));
         DGI_TRY(plan_layer(g, &layers[l], own_input ? reinterpret_cast<const void*>(256) : x, own_input ? own_ld : ld_x, &plans[l]));
         if (l > 0 && !(jk && l == num_layers - 1)) {
@@ -535,7 +540,7 @@ extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layer
     const int64_t ld_xp = round_up(L0.in_dim, 16 / xb), ld_yp = round_up(LL.out_dim, 16 / yb);
     // GCN layers gather rows already multiplied by d_out(u)^-1/2: every layer folds the next layer's factor into
     // its epilogue, and the input of a first GCN layer is scaled once into a library-owned copy.
-    const bool scale_x = L0.agg == DGI_AGG_GCN && !jk;  // (a jumping-knowledge output has several consumers: no folding)
+    // (a jumping-knowledge output has several consumers: no folding of the factor, and no scaled copy of x)
     const uint64_t xp_bytes = (permuted || scale_x) ? (uint64_t)round_up(N * ld_xp * xb, 256) : 0;
     const uint64_t yp_bytes = permuted ? (uint64_t)round_up(N * ld_yp * yb, 256) : 0;
     uint64_t fixed_max = 0, temp_full_max = 0;
@@ -596,7 +601,7 @@ extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layer
         else if (jk) { dst = hid[0] + cat_off[l] * elem_bytes(L.out_dtype); ld_dst = ld_cat; }
         else { dst = hid[l % 2]; ld_dst = round_up(L.out_dim, 16 / elem_bytes(L.out_dtype)); }
         if (jk && last) { cur = hid[0]; ld_cur = ld_cat; }  // the whole concatenation
-        const bool in_prescaled = !jk && L.agg == DGI_AGG_GCN && (l == 0 || layers[l - 1].agg != DGI_AGG_GAT);
+        const bool in_prescaled = !jk && L.agg == DGI_AGG_GCN && (l == 0 ? scale_x : layers[l - 1].agg != DGI_AGG_GAT);
         const float* out_scale = (!jk && !last && layers[l + 1].agg == DGI_AGG_GCN && L.agg != DGI_AGG_GAT) ? g->d_rs_out : nullptr;
         if (tm) { tm->layer = l; DGI_TRY(tm->begin(SPAN_LAYER)); }
         const size_t layer_span = tm ? tm->spans.size() - 1 : 0;
