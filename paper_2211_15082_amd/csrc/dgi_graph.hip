@@ -69,8 +69,8 @@ void find_hubs(dgi_graph* g) {
 // Shared tail of load / reorder: the handle already has N, E, itype, device CSR and h_indptr.
 // Without count_out (library-built graphs only: their indices are known to be valid) the out-degrees are not counted
 // and the handle refuses GCN layers.
-dgi_status_t finish_graph(dgi_graph* g, hipStream_t stream, bool no_hubs = false, bool count_out = true) {
-    g->has_out_degrees = count_out;
+dgi_status_t finish_graph(dgi_graph* g, hipStream_t stream, bool no_hubs = false, bool count_out = true, const int32_t* counted = nullptr) {
+    g->has_out_degrees = count_out || counted != nullptr;
     DGI_TRY(dev_alloc(&g->d_deg_out, g->N, g));
     DGI_TRY(dev_alloc(&g->d_rs_in, g->N, g));
     DGI_TRY(dev_alloc(&g->d_rs_out, g->N, g));
@@ -81,7 +81,10 @@ dgi_status_t finish_graph(dgi_graph* g, hipStream_t stream, bool no_hubs = false
     do {
         if ((st = launch_fill_zero(d_bad, sizeof(int), stream)) != DGI_OK) break;
         if (g->N > 0 && (st = launch_fill_zero(g->d_deg_out, (uint64_t)g->N * 4, stream)) != DGI_OK) break;
-        if (g->E > 0 && count_out) {
+        if (counted && g->N > 0) {
+            const hipError_t ce = hipMemcpyAsync(g->d_deg_out, counted, (size_t)g->N * 4, hipMemcpyDeviceToDevice, stream);
+            if (ce != hipSuccess) { set_error("graph setup failed: %s", hipGetErrorString(ce)); st = DGI_ERR_DEVICE; break; }
+        } else if (g->E > 0 && count_out) {
             const int64_t blocks = std::min<int64_t>((g->E + 255) / 256, 65536);
             hipLaunchKernelGGL(check_and_count_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, g->d_indices, g->E, g->N,
                                g->d_deg_out, d_bad);
@@ -130,7 +133,7 @@ dgi_status_t validate_indptr(const dgi_graph* g) {
 // possible the host scan for hubs is skipped as well; without count_out_degrees the count of out-degrees (one integer
 // atomic per edge) is skipped too, and the handle then serves every aggregation but GCN.  On failure nothing is adopted: the caller still owns the arrays.
 dgi_status_t graph_adopt(int64_t N, int64_t E, int64_t* d_indptr, int32_t* d_indices, std::vector<int64_t>&& h_indptr, int64_t max_degree,
-                         bool own_arrays, bool count_out_degrees, hipStream_t stream, dgi_graph_t** out) {
+                         bool own_arrays, bool count_out_degrees, hipStream_t stream, dgi_graph_t** out, const int32_t* counted_out_degrees) {
     dgi_graph* g = new dgi_graph();
     g->N = N; g->E = E; g->itype = DGI_I64;
     (void)hipGetDevice(&g->device);
@@ -138,7 +141,7 @@ dgi_status_t graph_adopt(int64_t N, int64_t E, int64_t* d_indptr, int32_t* d_ind
     g->device_bytes = (uint64_t)(N + 1) * 8 + (uint64_t)E * 4;
     g->h_indptr = std::move(h_indptr);
     const bool skip_hub_scan = max_degree >= 0 && max_degree <= kHubDegree;
-    dgi_status_t st = finish_graph(g, stream, skip_hub_scan, count_out_degrees);
+    dgi_status_t st = finish_graph(g, stream, skip_hub_scan, count_out_degrees, counted_out_degrees);
     if (st != DGI_OK) { h_indptr = std::move(g->h_indptr); dgi_graph_free(g); return st; }
     if (skip_hub_scan) g->max_in_degree = max_degree;
     g->own_csr = own_arrays;

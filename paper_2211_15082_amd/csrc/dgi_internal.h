@@ -210,7 +210,8 @@ dgi_status_t reorder_permutation(int64_t N, const int64_t* indptr, const int32_t
 
 // handle over device CSR arrays built by the library (int64 indptr); takes ownership of the arrays and of h_indptr
 dgi_status_t graph_adopt(int64_t N, int64_t E, int64_t* d_indptr, int32_t* d_indices, std::vector<int64_t>&& h_indptr, int64_t max_degree,
-                         bool own_arrays, bool count_out_degrees, hipStream_t stream, dgi_graph_t** out);
+                         bool own_arrays, bool count_out_degrees, hipStream_t stream, dgi_graph_t** out,
+                         const int32_t* counted_out_degrees = nullptr /* DEVICE, N entries: used instead of counting */);
 
 // dgi_layer_forward with an output buffer whose first row is destination row out_base (0 = the whole matrix)
 dgi_status_t layer_forward_rows(const dgi_graph* g, const dgi_layer_t* layer, const void* h_in, int64_t ld_in, void* h_out, int64_t ld_out,

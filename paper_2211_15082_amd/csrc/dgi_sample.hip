@@ -33,13 +33,18 @@ __device__ __forceinline__ uint64_t splitmix64_output(uint64_t seed, uint64_t k)
 // LDS per pass), then keeps the pairs up to that threshold with an order-preserving wave compaction.
 template <typename IdxT>
 __global__ __launch_bounds__(64) void sample_rows_kernel(const IdxT* indptr, const int32_t* indices, int64_t N, int fanout, uint64_t seed,
-                                                         uint64_t key_base /* l*E + 1 */, const int64_t* new_indptr, int32_t* new_indices) {
+                                                         uint64_t key_base /* l*E + 1 */, const int64_t* new_indptr, int32_t* new_indices,
+                                                         int32_t* deg_out /* NULL, or zeroed: out-degrees of the sample are counted here */) {
     __shared__ uint32_t hist[256];
     const int lane = threadIdx.x;
     for (int64_t v = blockIdx.x; v < N; v += gridDim.x) {
         const int64_t a = (int64_t)indptr[v], d = (int64_t)indptr[v + 1] - a, o = new_indptr[v];
         if (d <= fanout) {
-            for (int64_t j = lane; j < d; j += 64) new_indices[o + j] = indices[a + j];
+            for (int64_t j = lane; j < d; j += 64) {
+                const int32_t u = indices[a + j];
+                new_indices[o + j] = u;
+                if (deg_out) atomicAdd(&deg_out[u], 1);  // integer atomics: order-independent result
+            }
             continue;
         }
         auto value = [&](int64_t j) { return (splitmix64_output(seed, key_base + (uint64_t)(a + j)) & 0xFFFFFFFF00000000ull) | (uint64_t)j; };
@@ -52,7 +57,11 @@ __global__ __launch_bounds__(64) void sample_rows_kernel(const IdxT* indptr, con
             }
             const bool keep = lane < d && rank < fanout;
             const unsigned long long m = __ballot(keep);
-            if (keep) new_indices[o + __popcll(m & ((1ull << lane) - 1ull))] = indices[a + lane];
+            if (keep) {
+                const int32_t u = indices[a + lane];
+                new_indices[o + __popcll(m & ((1ull << lane) - 1ull))] = u;
+                if (deg_out) atomicAdd(&deg_out[u], 1);
+            }
             continue;
         }
         uint64_t prefix = 0;  // the bytes of the threshold found so far (the high ones)
@@ -99,7 +108,11 @@ __global__ __launch_bounds__(64) void sample_rows_kernel(const IdxT* indptr, con
             const bool keep = j < d && value(j) <= prefix;
             const unsigned long long m = __ballot(keep);
             const int64_t at = base + __popcll(m & ((1ull << lane) - 1ull));
-            if (keep && at < o + fanout) new_indices[at] = indices[a + j];  // (exactly fanout values pass; the bound keeps a row inside its slots regardless)
+            if (keep && at < o + fanout) {  // (exactly fanout values pass; the bound keeps a row inside its slots regardless)
+                const int32_t u = indices[a + j];
+                new_indices[at] = u;
+                if (deg_out) atomicAdd(&deg_out[u], 1);
+            }
             base += __popcll(m);
         }
     }
@@ -154,8 +167,12 @@ dgi_status_t sample_graph(const dgi_graph* g, int fanout, uint64_t seed, int lay
     int64_t* d_ip = cached ? g->ss_d_ip : nullptr;
     int32_t* d_ix = cached ? g->ss_d_ix : nullptr;
     void* d_tmp = nullptr;
+    // GCN reads the sample's out-degrees: the sampling kernel counts them while it writes the kept edges (the
+    // atomics hide behind its own latency-bound work; a separate pass over the sampled edges took as long as the sampling)
+    int32_t* d_deg = nullptr;
     auto fail = [&](dgi_status_t st) {
         (void)hipFree(d_tmp);
+        (void)hipFree(d_deg);
         if (!cached) { (void)hipFree(d_ip); (void)hipFree(d_ix); }
         give_back();
         return st;
@@ -173,7 +190,12 @@ dgi_status_t sample_graph(const dgi_graph* g, int fanout, uint64_t seed, int lay
     size_t tmp_bytes = 0;
     if (err == hipSuccess) err = hipcub::DeviceScan::InclusiveSum(nullptr, tmp_bytes, d_ip, d_ip, (int)(N + 1), s);
     if (err == hipSuccess) err = hipMalloc(&d_tmp, std::max<size_t>(tmp_bytes, 16));
+    if (err == hipSuccess && count_out_degrees) err = hipMalloc(reinterpret_cast<void**>(&d_deg), std::max<size_t>((size_t)N * 4, 16));
     if (err != hipSuccess) { set_error("graph_sample: %s", hipGetErrorString(err)); return fail(err == hipErrorOutOfMemory ? DGI_ERR_OOM : DGI_ERR_DEVICE); }
+    if (d_deg && N > 0) {
+        const dgi_status_t zs = launch_fill_zero(d_deg, (uint64_t)N * 4, s);
+        if (zs != DGI_OK) return fail(zs);
+    }
     {
         const unsigned grid1 = (unsigned)std::min<int64_t>((N + 256) / 256, (int64_t)1 << 20);
         const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(N, (int64_t)1 << 22));
@@ -183,13 +205,13 @@ dgi_status_t sample_graph(const dgi_graph* g, int fanout, uint64_t seed, int lay
             err = hipcub::DeviceScan::InclusiveSum(d_tmp, tmp_bytes, d_ip, d_ip, (int)(N + 1), s);
             if (err == hipSuccess && N > 0)
                 hipLaunchKernelGGL(sample_rows_kernel<int64_t>, dim3(grid), dim3(64), 0, s, (const int64_t*)g->d_indptr, g->d_indices, N, fanout, seed, key_base,
-                                   d_ip, d_ix);
+                                   d_ip, d_ix, d_deg);
         } else {
             hipLaunchKernelGGL(min_degree_kernel<int32_t>, dim3(grid1), dim3(256), 0, s, (const int32_t*)g->d_indptr, N, fanout, d_ip);
             err = hipcub::DeviceScan::InclusiveSum(d_tmp, tmp_bytes, d_ip, d_ip, (int)(N + 1), s);
             if (err == hipSuccess && N > 0)
                 hipLaunchKernelGGL(sample_rows_kernel<int32_t>, dim3(grid), dim3(64), 0, s, (const int32_t*)g->d_indptr, g->d_indices, N, fanout, seed, key_base,
-                                   d_ip, d_ix);
+                                   d_ip, d_ix, d_deg);
         }
         if (err == hipSuccess) err = hipGetLastError();
     }
@@ -197,8 +219,9 @@ dgi_status_t sample_graph(const dgi_graph* g, int fanout, uint64_t seed, int lay
     if (err != hipSuccess) { set_error("graph_sample: %s", hipGetErrorString(err)); return fail(DGI_ERR_DEVICE); }
     (void)hipFree(d_tmp);
     d_tmp = nullptr;
-    const dgi_status_t st = graph_adopt(N, Es, d_ip, d_ix, std::move(ip), std::min<int64_t>(g->max_in_degree, fanout), !cached, count_out_degrees, s, g_out);
+    const dgi_status_t st = graph_adopt(N, Es, d_ip, d_ix, std::move(ip), std::min<int64_t>(g->max_in_degree, fanout), !cached, false, s, g_out, d_deg);
     if (st != DGI_OK) return fail(st);  // graph_adopt handed `ip` back
+    (void)hipFree(d_deg);  // copied into the new handle
     return DGI_OK;
 }
 
