@@ -338,7 +338,7 @@ extern "C" dgi_status_t dgi_graph_release_workspace(dgi_graph_t* g) {
     if (!g) return DGI_OK;
     DGI_TRY(release_infer_arena(g));
     std::lock_guard<std::mutex> hs_lock(g->hs_mutex);
-    if (g->hs_arena || g->hs_hid[0] || g->hs_hid[1] || g->hs_z || g->ss_d_ip || g->ss_d_ix) {
+    if (g->hs_arena || g->hs_hid[0] || g->hs_hid[1] || g->hs_z || g->ss_d_ip || g->ss_d_ix || g->ss_d_tmp || g->ss_d_deg || g->ss_d_vec) {
         DGI_HIP(hipDeviceSynchronize());
         (void)hipFree(g->hs_arena);
         (void)hipHostFree(g->hs_hid[0]);
@@ -347,11 +347,17 @@ extern "C" dgi_status_t dgi_graph_release_workspace(dgi_graph_t* g) {
         g->hs_z = nullptr; g->hs_z_bytes = 0;
         (void)hipFree(g->ss_d_ip);
         (void)hipFree(g->ss_d_ix);
+        (void)hipFree(g->ss_d_tmp);
+        (void)hipFree(g->ss_d_deg);
+        g->ss_d_tmp = nullptr; g->ss_tmp_cap = 0; g->ss_d_deg = nullptr;
+        (void)hipFree(g->ss_d_vec);
+        g->ss_d_vec = nullptr; g->ss_ip_fanout = -1;
         g->hs_arena = nullptr; g->hs_arena_bytes = 0;
         g->hs_hid[0] = g->hs_hid[1] = nullptr; g->hs_hid_bytes = 0;
         g->ss_d_ip = nullptr; g->ss_d_ix = nullptr; g->ss_ix_cap = 0;
     }
     std::vector<int64_t>().swap(g->ss_ip);
+    g->ss_ip_fanout = -1;
     return DGI_OK;
 }
 

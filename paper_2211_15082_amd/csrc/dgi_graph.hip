@@ -69,11 +69,21 @@ void find_hubs(dgi_graph* g) {
 // Shared tail of load / reorder: the handle already has N, E, itype, device CSR and h_indptr.
 // Without count_out (library-built graphs only: their indices are known to be valid) the out-degrees are not counted
 // and the handle refuses GCN layers.
-dgi_status_t finish_graph(dgi_graph* g, hipStream_t stream, bool no_hubs = false, bool count_out = true, const int32_t* counted = nullptr) {
+dgi_status_t finish_graph(dgi_graph* g, hipStream_t stream, bool no_hubs = false, bool count_out = true, const int32_t* counted = nullptr,
+                          void* node_vectors = nullptr) {
     g->has_out_degrees = count_out || counted != nullptr;
-    DGI_TRY(dev_alloc(&g->d_deg_out, g->N, g));
-    DGI_TRY(dev_alloc(&g->d_rs_in, g->N, g));
-    DGI_TRY(dev_alloc(&g->d_rs_out, g->N, g));
+    if (node_vectors) {  // lent by the caller (a sampled graph lives for one layer: no allocation per layer)
+        const uint64_t stride = (uint64_t)round_up(g->N * 4, 256);
+        char* base = static_cast<char*>(node_vectors);
+        g->d_deg_out = reinterpret_cast<int32_t*>(base);
+        g->d_rs_in = reinterpret_cast<float*>(base + stride);
+        g->d_rs_out = reinterpret_cast<float*>(base + 2 * stride);
+        g->own_vectors = false;
+    } else {
+        DGI_TRY(dev_alloc(&g->d_deg_out, g->N, g));
+        DGI_TRY(dev_alloc(&g->d_rs_in, g->N, g));
+        DGI_TRY(dev_alloc(&g->d_rs_out, g->N, g));
+    }
     int* d_bad = nullptr;
     DGI_HIP(hipMalloc(reinterpret_cast<void**>(&d_bad), sizeof(int)));
     dgi_status_t st = DGI_OK;
@@ -133,7 +143,7 @@ dgi_status_t validate_indptr(const dgi_graph* g) {
 // possible the host scan for hubs is skipped as well; without count_out_degrees the count of out-degrees (one integer
 // atomic per edge) is skipped too, and the handle then serves every aggregation but GCN.  On failure nothing is adopted: the caller still owns the arrays.
 dgi_status_t graph_adopt(int64_t N, int64_t E, int64_t* d_indptr, int32_t* d_indices, std::vector<int64_t>&& h_indptr, int64_t max_degree,
-                         bool own_arrays, bool count_out_degrees, hipStream_t stream, dgi_graph_t** out, const int32_t* counted_out_degrees) {
+                         bool own_arrays, bool count_out_degrees, hipStream_t stream, dgi_graph_t** out, const int32_t* counted_out_degrees, void* node_vectors) {
     dgi_graph* g = new dgi_graph();
     g->N = N; g->E = E; g->itype = DGI_I64;
     (void)hipGetDevice(&g->device);
@@ -141,7 +151,7 @@ dgi_status_t graph_adopt(int64_t N, int64_t E, int64_t* d_indptr, int32_t* d_ind
     g->device_bytes = (uint64_t)(N + 1) * 8 + (uint64_t)E * 4;
     g->h_indptr = std::move(h_indptr);
     const bool skip_hub_scan = max_degree >= 0 && max_degree <= kHubDegree;
-    dgi_status_t st = finish_graph(g, stream, skip_hub_scan, count_out_degrees, counted_out_degrees);
+    dgi_status_t st = finish_graph(g, stream, skip_hub_scan, count_out_degrees, counted_out_degrees, node_vectors);
     if (st != DGI_OK) { h_indptr = std::move(g->h_indptr); dgi_graph_free(g); return st; }
     if (skip_hub_scan) g->max_in_degree = max_degree;
     g->own_csr = own_arrays;
@@ -159,9 +169,11 @@ extern "C" dgi_status_t dgi_graph_free(dgi_graph_t* g) {
         (void)hipFree(const_cast<void*>(g->d_indptr));
         (void)hipFree(const_cast<int32_t*>(g->d_indices));
     }
-    (void)hipFree(g->d_deg_out);
-    (void)hipFree(g->d_rs_in);
-    (void)hipFree(g->d_rs_out);
+    if (g->own_vectors) {
+        (void)hipFree(g->d_deg_out);
+        (void)hipFree(g->d_rs_in);
+        (void)hipFree(g->d_rs_out);
+    }
     (void)hipFree(g->d_hub_rows);
     (void)hipFree(g->d_hub_chunk_ptr);
     (void)hipFree(g->ws_ptr);
@@ -171,6 +183,9 @@ extern "C" dgi_status_t dgi_graph_free(dgi_graph_t* g) {
     (void)hipHostFree(g->hs_z);
     (void)hipFree(g->ss_d_ip);
     (void)hipFree(g->ss_d_ix);
+    (void)hipFree(g->ss_d_tmp);
+    (void)hipFree(g->ss_d_deg);
+    (void)hipFree(g->ss_d_vec);
     delete g;
     return DGI_OK;
 }

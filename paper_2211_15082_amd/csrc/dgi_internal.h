@@ -52,6 +52,7 @@ struct dgi_graph {
     const void* d_indptr = nullptr;     // device, itype entries
     const int32_t* d_indices = nullptr; // device
     bool own_csr = false;               // device CSR allocated by the handle
+    bool own_vectors = true;            // d_deg_out / d_rs_in / d_rs_out allocated by the handle (else borrowed)
     bool has_out_degrees = true;        // d_deg_out / d_rs_out are filled (a sampled graph for a layer without GCN skips the count)
     int32_t* d_deg_out = nullptr;
     float* d_rs_in = nullptr;           // in-degree^-1/2, degree clamped to >= 1
@@ -86,6 +87,11 @@ struct dgi_graph {
     mutable int64_t* ss_d_ip = nullptr;
     mutable int32_t* ss_d_ix = nullptr;
     mutable uint64_t ss_ix_cap = 0;  // entries
+    mutable void* ss_d_tmp = nullptr;   // the sampler's scan workspace and out-degree counters, kept between calls
+    mutable uint64_t ss_tmp_cap = 0;    // bytes
+    mutable int32_t* ss_d_deg = nullptr;
+    mutable char* ss_d_vec = nullptr;   // 3 N-vectors lent to the sampled graph of a layer (degrees and normalisers)
+    mutable int64_t ss_ip_fanout = -1;  // fan-out ss_ip (and ss_d_ip) were computed for: the sample's indptr depends on nothing else
 };
 
 namespace dgi {
@@ -211,7 +217,8 @@ dgi_status_t reorder_permutation(int64_t N, const int64_t* indptr, const int32_t
 // handle over device CSR arrays built by the library (int64 indptr); takes ownership of the arrays and of h_indptr
 dgi_status_t graph_adopt(int64_t N, int64_t E, int64_t* d_indptr, int32_t* d_indices, std::vector<int64_t>&& h_indptr, int64_t max_degree,
                          bool own_arrays, bool count_out_degrees, hipStream_t stream, dgi_graph_t** out,
-                         const int32_t* counted_out_degrees = nullptr /* DEVICE, N entries: used instead of counting */);
+                         const int32_t* counted_out_degrees = nullptr /* DEVICE, N entries: used instead of counting */,
+                         void* node_vectors = nullptr /* DEVICE, 3 x round_up(4 N, 256) bytes lent for the handle's N-vectors */);
 
 // dgi_layer_forward with an output buffer whose first row is destination row out_base (0 = the whole matrix)
 dgi_status_t layer_forward_rows(const dgi_graph* g, const dgi_layer_t* layer, const void* h_in, int64_t ld_in, void* h_out, int64_t ld_out,
