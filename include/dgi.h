@@ -291,8 +291,9 @@ dgi_status_t dgi_infer_host(const dgi_graph_t* g, const dgi_layer_t* layers, int
  * dgi_infer_sampled: layer l of the model runs on dgi_graph_sample(g, fanout, seed, l) with the ordinary
  * layer-wise schedule (dgi_infer on one layer; opts as there, perm_new_of_old / jk_concat / stats unsupported);
  * the mean and GCN normalisers use the degrees of the sampled graph.  x, out: DEVICE, as for dgi_infer.  The
- * hidden layers and the schedule's arena are kept in g's handle between calls (dgi_graph_release_workspace returns
- * them); calls on one handle are serialised.  Waits for completion. */
+ * hidden layers, the schedule's arena, the sample's indptr (it depends on the degrees and the fan-out only, so it is
+ * computed once per fan-out) and the sampler's buffers are kept in g's handle between calls
+ * (dgi_graph_release_workspace returns them); calls on one handle are serialised.  Waits for completion. */
 dgi_status_t dgi_graph_sample(const dgi_graph_t* g, int32_t fanout, uint64_t seed, int32_t layer, void* hip_stream,
                               dgi_graph_t** g_out);
 dgi_status_t dgi_infer_sampled(const dgi_graph_t* g, const dgi_layer_t* layers, int32_t num_layers, const void* x,
