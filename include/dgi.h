@@ -198,6 +198,20 @@ dgi_status_t dgi_layer_forward(const dgi_graph_t* g, const dgi_layer_t* layer, c
 dgi_status_t dgi_layer_workspace_bytes(const dgi_graph_t* g, const dgi_layer_t* layer, int64_t dst_begin,
                                        int64_t dst_end, uint64_t* bytes /*HOST*/);
 
+/* dgi_layer_forward for callers that can neither allocate device memory nor pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and kernels as
+ * dgi_layer_forward, but the workspace is a static device array of DGI_STATIC_WORKSPACE_BYTES bytes that is part of
+ * the library's code object (every GPU the library runs on holds one copy until the process ends).  The call
+ * allocates and frees nothing, on the device or through any library.  A layer / row range whose
+ * dgi_layer_workspace_bytes exceeds DGI_STATIC_WORKSPACE_BYTES is refused with DGI_ERR_UNSUPPORTED (a transform-first
+ * layer needs the transformed rows of all N nodes in the workspace, so this bounds N for those).  The calling thread's
+ * current device must be the graph's.  All calls on one GPU share the one array and it keeps the previous call's
+ * contents (every region is rewritten before it is read): calls that overlap in time on one GPU, on any streams,
+ * race; order them on one stream or with events. */
+#define DGI_STATIC_WORKSPACE_BYTES (32u << 20)
+dgi_status_t dgi_layer_forward_static(const dgi_graph_t* g, const dgi_layer_t* layer, const void* h_in, int64_t ld_in,
+                                      void* h_out, int64_t ld_out, int64_t dst_begin, int64_t dst_end, void* hip_stream);
+
 /* Whole-model layer-wise inference (Algorithm 2): for l = 1..L, for every batch of destination rows,
  * compute H^l[batch]; H^{l-1} is released when layer l is done (two ping-pong buffers).
  *   x   : DEVICE [N x layers[0].in_dim], dtype layers[0].feat_dtype, leading dimension ld_x.

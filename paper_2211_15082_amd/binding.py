@@ -90,7 +90,7 @@ class GraphInfoStruct(ctypes.Structure):
 
 EXPORTS = [
     "dgi_graph_load", "dgi_graph_free", "dgi_graph_release_workspace", "dgi_graph_info", "dgi_graph_vector", "dgi_graph_csr", "dgi_graph_reorder",
-    "dgi_layer_forward", "dgi_layer_workspace_bytes", "dgi_infer", "dgi_infer_partial", "dgi_infer_host", "dgi_graph_sample", "dgi_infer_sampled", "dgi_plan_batch_end", "dgi_threshold_update",
+    "dgi_layer_forward", "dgi_layer_forward_static", "dgi_layer_workspace_bytes", "dgi_infer", "dgi_infer_partial", "dgi_infer_host", "dgi_graph_sample", "dgi_infer_sampled", "dgi_plan_batch_end", "dgi_threshold_update",
     "dgi_threshold_halve", "dgi_batch_input_set_size", "dgi_reorder_permutation", "dgi_status_string",
     "dgi_last_error", "dgi_version", "dgi_host_alloc", "dgi_host_free",
 ]
@@ -266,6 +266,18 @@ def layer_forward(graph, layer_struct, h_in, h_out, dst_begin, dst_end, workspac
     _check(_lib.dgi_layer_forward(graph.handle, ctypes.byref(layer_struct), _dptr(h_in), ctypes.c_int64(ld_in), _dptr(h_out),
                                   ctypes.c_int64(ld_out), ctypes.c_int64(dst_begin), ctypes.c_int64(dst_end),
                                   ctypes.c_void_p(workspace.data_ptr() + off), ctypes.c_uint64(workspace.numel() - off), _stream()))
+    return h_out
+
+
+STATIC_WORKSPACE_BYTES = 32 << 20  # DGI_STATIC_WORKSPACE_BYTES
+
+
+def layer_forward_static(graph, layer_struct, h_in, h_out, dst_begin, dst_end, ld_in=None, ld_out=None):
+    """dgi_layer_forward_static: the same layer call on the library's static device workspace (nothing is allocated)."""
+    ld_in = int(h_in.stride(0)) if ld_in is None else ld_in
+    ld_out = int(h_out.stride(0)) if ld_out is None else ld_out
+    _check(_lib.dgi_layer_forward_static(graph.handle, ctypes.byref(layer_struct), _dptr(h_in), ctypes.c_int64(ld_in), _dptr(h_out),
+                                         ctypes.c_int64(ld_out), ctypes.c_int64(dst_begin), ctypes.c_int64(dst_end), _stream()))
     return h_out
 
 

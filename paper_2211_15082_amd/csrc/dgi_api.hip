@@ -470,6 +470,54 @@ extern "C" dgi_status_t dgi_layer_forward(const dgi_graph_t* g, const dgi_layer_
     return layer_forward_rows(g, layer, h_in, ld_in, h_out, ld_out, 0, dst_begin, dst_end, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
+// ---- dgi_layer_forward without any allocation: the workspace is a static device array -----------------------
+// One array per GPU (every device that loads the library's code object holds its own copy).  In host code the
+// array's name is only a handle for hipGetSymbolAddress; kernels and fills get the address that call returns.
+static __device__ __align__(256) unsigned char scratch[DGI_STATIC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on device i, looked up on first use there
+
+// the calling thread's current device must be the one the lookup is for
+dgi_status_t static_scratch(void** out) {
+    int dev = -1;
+    DGI_HIP(hipGetDevice(&dev));
+    DGI_REQUIRE(dev >= 0 && dev < kMaxDevices, DGI_ERR_UNSUPPORTED, "static workspace: device ordinal %d out of range", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        DGI_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        DGI_REQUIRE(p != nullptr && (uintptr_t)p % 256 == 0, DGI_ERR_DEVICE, "static workspace: symbol address missing or misaligned");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return DGI_OK;
+}
+}  // namespace
+
+extern "C" dgi_status_t dgi_layer_forward_static(const dgi_graph_t* g, const dgi_layer_t* layer, const void* h_in, int64_t ld_in,
+                                                 void* h_out, int64_t ld_out, int64_t dst_begin, int64_t dst_end, void* hip_stream) {
+    DGI_REQUIRE(g != nullptr, DGI_ERR_INVALID_ARG, "graph is NULL");
+    int dev = -1;
+    DGI_HIP(hipGetDevice(&dev));
+    DGI_REQUIRE(dev == g->device, DGI_ERR_INVALID_ARG, "layer_forward_static: current device %d is not the graph's device %d", dev, g->device);
+    uint64_t need = 0;
+    DGI_TRY(dgi_layer_workspace_bytes(g, layer, dst_begin, dst_end, &need));
+    DGI_REQUIRE(need <= (uint64_t)DGI_STATIC_WORKSPACE_BYTES, DGI_ERR_UNSUPPORTED,
+                "layer_forward_static: this layer and row range need %llu bytes of workspace, the static workspace holds %llu; "
+                "use dgi_layer_forward with a caller-provided workspace",
+                (unsigned long long)need, (unsigned long long)DGI_STATIC_WORKSPACE_BYTES);
+    void* ws = nullptr;
+    DGI_TRY(static_scratch(&ws));
+    // every region of the workspace the kernels read is written first in the same call (packed weights are zero-filled
+    // by a kernel, Z / partials / the aggregated tile are produced before they are consumed), so what the previous
+    // call left behind is never observed
+    return layer_forward_rows(g, layer, h_in, ld_in, h_out, ld_out, 0, dst_begin, dst_end, ws, DGI_STATIC_WORKSPACE_BYTES,
+                              static_cast<hipStream_t>(hip_stream));
+}
+
 extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layers, int32_t num_layers, const void* x,
                                   int64_t ld_x, void* out, int64_t ld_out, const dgi_infer_opts_t* opts, void* hip_stream) {
     DGI_REQUIRE(g != nullptr && layers != nullptr, DGI_ERR_INVALID_ARG, "infer: NULL argument");
