@@ -26,13 +26,6 @@ def splitmix64_output(seed, k):
         return z ^ (z >> np.uint64(31))
 
 
-def edge_keys(num_edges, seed, layer):
-    e = np.arange(num_edges, dtype=np.uint64)
-    with np.errstate(over="ignore"):
-        k = np.uint64(layer) * np.uint64(num_edges) + e + np.uint64(1)
-    return (splitmix64_output(seed, k) >> np.uint64(32)).astype(np.uint32)
-
-
 def sample_csr(indptr, indices, fanout, seed, layer, edge_base=0, total_edges=None):
     """The sampled graph of one layer: (indptr int64, indices int32).  For a slice of consecutive rows of a larger
     graph (indptr rebased to 0, its share of indices), pass the position of the slice's first edge in the full

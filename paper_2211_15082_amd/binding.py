@@ -11,7 +11,7 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("DGI_LIB_PATH") or os.path.join(_HERE, "libdgi.so")  # override: A/B builds when tuning
+LIB_PATH = os.path.join(_HERE, "libdgi.so")
 
 OK, ERR_INVALID_ARG, ERR_BAD_GRAPH, ERR_UNSUPPORTED, ERR_OOM, ERR_DEVICE = range(6)
 I32, I64 = 0, 1

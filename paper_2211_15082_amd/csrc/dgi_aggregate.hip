@@ -55,6 +55,7 @@ struct AggParams {
     int64_t ld_s;
     int width;
     void* out;
+    void* out_lo;          // bf16 output only: receives the part of each value its bf16 rounding dropped (or null)
     int64_t ld_out;
     int64_t out_row0;
     int out_bf16;
@@ -253,8 +254,13 @@ __device__ __forceinline__ void finish_store(const AggParams& p, int64_t v, int6
     val = activate(val, p.act, p.act_slope);
     if (p.out_scale) val *= p.out_scale[v];
     const int64_t o = out_row * p.ld_out + c;
-    if (p.out_bf16) static_cast<uint16_t*>(p.out)[o] = float_to_bf16(val);
-    else static_cast<float*>(p.out)[o] = val;
+    if (p.out_bf16) {
+        const uint16_t hi = float_to_bf16(val);
+        static_cast<uint16_t*>(p.out)[o] = hi;
+        if (p.out_lo) static_cast<uint16_t*>(p.out_lo)[o] = float_to_bf16(val - bf16_to_float(hi));
+    } else {
+        static_cast<float*>(p.out)[o] = val;
+    }
 }
 
 // The same epilogue for the VEC consecutive elements a lane owns (columns col .. col+VEC-1 of row v), stored as one
@@ -302,6 +308,16 @@ __device__ __forceinline__ void store_chunk(const AggParams& p, int64_t v, int64
         // VEC bf16 values are 8 bytes (fp32 sources) or 16 bytes (bf16 sources)
         if constexpr (VEC == 4) *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + o) = make_uint2(w[0], w[1]);
         else *reinterpret_cast<uint4*>(static_cast<uint16_t*>(p.out) + o) = make_uint4(w[0], w[1], w[(VEC > 4) ? 2 : 0], w[(VEC > 4) ? 3 : 0]);
+        if (p.out_lo) {  // what the rounding above dropped, as a second bf16 value per element
+            uint32_t l[(VEC + 1) / 2];
+#pragma unroll
+            for (int i = 0; i < VEC / 2; ++i) {
+                const float r0 = val[2 * i] - __uint_as_float(w[i] << 16), r1 = val[2 * i + 1] - __uint_as_float(w[i] & 0xffff0000u);
+                l[i] = (uint32_t)float_to_bf16(r0) | ((uint32_t)float_to_bf16(r1) << 16);
+            }
+            if constexpr (VEC == 4) *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out_lo) + o) = make_uint2(l[0], l[1]);
+            else *reinterpret_cast<uint4*>(static_cast<uint16_t*>(p.out_lo) + o) = make_uint4(l[0], l[1], l[(VEC > 4) ? 2 : 0], l[(VEC > 4) ? 3 : 0]);
+        }
     } else {
 #pragma unroll
         for (int i = 0; i < VEC; i += 4) *reinterpret_cast<float4*>(static_cast<float*>(p.out) + o + i) = make_float4(val[i], val[i + 1], val[i + 2], val[i + 3]);
@@ -520,6 +536,14 @@ __device__ __forceinline__ uint4 pack_row_chunk(const float* f) {  // VEC floats
                       (uint32_t)float_to_bf16(f[6 % Row<T>::VEC]) | ((uint32_t)float_to_bf16(f[7 % Row<T>::VEC]) << 16));
 }
 
+// The part of a row chunk that its bf16 rounding dropped (bf16 tiles only): f - float(bf16(f)), again as bf16.
+__device__ __forceinline__ uint4 pack_row_chunk_lo(const float* f) {
+    float r[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) r[i] = f[i] - bf16_to_float(float_to_bf16(f[i]));
+    return pack_row_chunk<uint16_t>(r);
+}
+
 // Aggregation fused with the layer's dense transform (aggregate-first layers).  A workgroup of W wavefronts
 // owns 32 destination rows.  Phase 1: the wavefronts gather and aggregate 32/W rows each exactly as the
 // stand-alone kernel does, but deposit the scaled result in an LDS tile (32 x K).  Phase 2: the tile is the
@@ -530,6 +554,9 @@ __device__ __forceinline__ uint4 pack_row_chunk(const float* f) {  // VEC floats
 // (LDS row = [h_v | m_v]) by coalesced loads before the gather starts, so phase 2 reads both blocks from
 // LDS; without SL they are read from global memory straight into fragment layout (smaller tile, but every
 // column block re-reads them with 32 cache lines per load instruction).
+// bf16 tiles hold m_v as two bf16 values per element, the rounded value and what the rounding dropped (LDS row =
+// [h_v |] m_hi | m_lo), and both blocks are multiplied with the neighbour weights: the fp32 accumulation of the
+// gather is not cut to 8 bits before the transform (two bf16 MFMAs cost a tenth of one fp32 MFMA pass).
 template <typename T, typename IdxT, int G, int MODE, int W, bool SL>
 __global__ __launch_bounds__(W * 64) __attribute__((amdgpu_waves_per_eu(W == 8 ? 4 : 1)))  // 8-wavefront form: two workgroups per CU
 void fused_layer_kernel(FusedParams fp) {
@@ -550,6 +577,7 @@ void fused_layer_kernel(FusedParams fp) {
     const int Kp = (K + 2 * VEC - 1) / (2 * VEC) * (2 * VEC);
     const int chunks = Kp / VEC;
     const int acol = SL ? Kp : 0;  // column of the aggregated block inside an LDS row
+    constexpr bool HL = sizeof(T) == 2;  // a second block of Kp columns right after it holds the rounding remainders
 
     if (SL) {  // the rows' own features: [0, Kp) of every LDS row, zero past K and past the row range
 #pragma unroll
@@ -637,7 +665,7 @@ void fused_layer_kernel(FusedParams fp) {
         const int cur = nxt;
         if (r + 1 < RPW) nxt = (int64_t)lane < (int64_t)(bound[r + 2 <= RPW ? r + 2 : RPW] - ee) ? p.indices[(int64_t)ee + lane] : 0;
         if (v >= p.row_end) {  // rows past the range: an all-zero A row
-            for (int ch = lane; ch < chunks; ch += 64) *reinterpret_cast<uint4*>(trow + ch * VEC) = make_uint4(0u, 0u, 0u, 0u);
+            for (int ch = lane; ch < (HL ? 2 : 1) * chunks; ch += 64) *reinterpret_cast<uint4*>(trow + ch * VEC) = make_uint4(0u, 0u, 0u, 0u);
             continue;
         }
         T* arow = trow;
@@ -653,6 +681,7 @@ void fused_layer_kernel(FusedParams fp) {
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) f[i] = ch * VEC + i < K ? src[ch * VEC + i] : 0.f;
                 *reinterpret_cast<uint4*>(arow + ch * VEC) = pack_row_chunk<T>(f);
+                if constexpr (HL) *reinterpret_cast<uint4*>(arow + Kp + ch * VEC) = pack_row_chunk_lo(f);
             }
             continue;
         }
@@ -669,6 +698,7 @@ void fused_layer_kernel(FusedParams fp) {
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) acc[i] *= scale;
                 *reinterpret_cast<uint4*>(arow + c) = pack_row_chunk<T>(acc);
+                if constexpr (HL) *reinterpret_cast<uint4*>(arow + Kp + c) = pack_row_chunk_lo(acc);
             }
         }
     }
@@ -744,6 +774,21 @@ void fused_layer_kernel(FusedParams fp) {
             batch(b1, ks + R);
             load_b(b1, ks + 4 * R);
             batch(b2, ks + 2 * R);
+        }
+        if constexpr (HL) {  // the rounding remainders of m_v against the neighbour weights once more
+            const T* a_lo = a_lds + acol + Kp;
+            const int wn = fp.K1p / (2 * VEC);
+            for (int ks = 0; ks < ksteps; ks += R) {
+                uint4 a[R], b[R];
+#pragma unroll
+                for (int u = 0; u < R; ++u) {
+                    const bool in = ks + u < ksteps;
+                    b[u] = in ? *reinterpret_cast<const uint4*>(w + (int64_t)(wn + ks + u) * 64 * VEC) : make_uint4(0u, 0u, 0u, 0u);
+                    a[u] = in ? *reinterpret_cast<const uint4*>(a_lo + (ks + u) * 2 * VEC) : make_uint4(0u, 0u, 0u, 0u);
+                }
+#pragma unroll
+                for (int u = 0; u < R; ++u) mma(acc, a[u], b[u]);
+            }
         }
         if (n < fp.N) {
             const float bias = fp.bias ? fp.bias[n] : 0.f;
@@ -968,7 +1013,8 @@ bool fused_supported(const FusedArgs& a) {
     if ((uintptr_t)a.H % 16 || (a.ld_h * eb) % 16 || a.K % E || a.K / E <= 8) return false;
     if (a.ldw % (2 * E) || a.K1p % (2 * E)) return false;
     if (a.ldw != a.K1p + round_up(a.K, 2 * E)) return false;
-    return (size_t)kFusedRows * (size_t)(round_up(a.K, 2 * E) + E) * eb <= kFusedMaxLds;
+    const int blocks = a.dtype == DGI_BF16 ? 2 : 1;  // bf16 tiles carry m_v as two blocks (value, rounding remainder)
+    return (size_t)kFusedRows * (size_t)(blocks * round_up(a.K, 2 * E) + E) * eb <= kFusedMaxLds;
 }
 
 uint64_t fused_temp_bytes(const dgi_graph* g, int64_t row_begin, int64_t row_end, int K) {
@@ -997,22 +1043,27 @@ dgi_status_t launch_fused(const FusedArgs& a, int stage, hipStream_t stream) {
     fp.Wf = a.Wf; fp.ldw = a.ldw; fp.K1p = a.K1p; fp.has_self = a.has_self ? 1 : 0; fp.N = a.N;
     fp.bias = a.bias; fp.act = a.act; fp.act_slope = a.act_slope; fp.out_scale = a.out_scale;
     fp.out = a.out; fp.ld_out = a.ld_out; fp.out_row0 = a.out_row0; fp.out_bf16 = a.out_dtype == DGI_BF16;
-    fp.lds_ld = (int)(round_up(a.K, 2 * E) + E);
+    const int mblocks = a.dtype == DGI_BF16 ? 2 : 1;
+    fp.lds_ld = (int)(mblocks * round_up(a.K, 2 * E) + E);
     {
         // Variant 2 (self rows in the tile, 8 wavefronts) when every wavefront gets a column block: phase 2 then
         // reads nothing but the weight from outside the workgroup, and half of it runs inside the gather (measured on
         // 256 -> 256 fp32 GraphSAGE, 20 M nodes, degree 20: 104 ms with variant 0, 121 with 1, 99 with 2).  Narrow
         // outputs would leave wavefronts idle there.  With 4 wavefronts the staged tile (variant 1) measured within
         // the run-to-run spread of variant 0 for K <= 128 and clearly slower beyond (256 -> 128: 74 vs 92-97 ms), so
-        // it is only reachable through DGI_TUNE_FUSED_SELF.
+        // it is only reachable by compiling with -DDGI_FUSED_SELF_VARIANT=1.
         const int Kp = (int)round_up(a.K, 2 * E);
-        static const int forced = [] { const char* e = getenv("DGI_TUNE_FUSED_SELF"); return e ? atoi(e) : -1; }();
+#ifdef DGI_FUSED_SELF_VARIANT
+        const int forced = DGI_FUSED_SELF_VARIANT;
+#else
+        const int forced = -1;
+#endif
         const bool can = a.has_self && a.K1p == Kp && (a.mode == MODE_SUM || a.mode == MODE_MEAN) &&
-                         (size_t)kFusedRows * (size_t)(2 * Kp + E) * eb <= 80 * 1024;
+                         (size_t)kFusedRows * (size_t)((1 + mblocks) * Kp + E) * eb <= 80 * 1024;
         int variant = 0;
         if (can) variant = forced >= 0 ? forced : ((a.N + 31) / 32 >= 8 ? 2 : 0);
         fp.self_lds = variant;
-        if (variant) fp.lds_ld = 2 * Kp + E;
+        if (variant) fp.lds_ld = (1 + mblocks) * Kp + E;
     }
     float* partials = static_cast<float*>(a.temp);
     float* hub_agg = a.temp ? reinterpret_cast<float*>(static_cast<char*>(a.temp) + round_up((int64_t)agg_hub_partial_bytes(g, a.row_begin, a.row_end, a.K), 256)) : nullptr;
@@ -1046,6 +1097,9 @@ dgi_status_t launch_aggregate(const AggArgs& a, int stage, hipStream_t stream) {
     p.S = a.S; p.ld_s = a.ld_s; p.width = a.width;
     p.out = a.out; p.ld_out = a.ld_out; p.out_row0 = a.out_row0;
     p.out_bf16 = a.out_dtype == DGI_BF16;
+    DGI_REQUIRE(a.out_lo == nullptr || (p.out_bf16 && (uintptr_t)a.out_lo % 16 == (uintptr_t)a.out % 16), DGI_ERR_INVALID_ARG,
+                "aggregate: a low-order output needs a bf16 output of the same alignment");
+    p.out_lo = a.out_lo;
     p.self = a.self; p.ld_self = a.ld_self;
     p.bias = a.bias; p.act = a.act; p.act_slope = a.act_slope; p.out_scale = a.out_scale;
     p.row_begin = a.row_begin; p.row_end = a.row_end;

@@ -49,6 +49,8 @@ struct LayerPlan {
     // aggregate-first: AGG tile of the batch (unfused path only)
     int64_t agg_ld = 0;
     bool fused = false;   // aggregate-first with the transform fused into the gather kernel
+    bool wide_agg = false;  // bf16 features: the aggregated tile is a pair of bf16 values per element
+    bool wide_sum = false;  // bf16 features under SUM: transformed rows (transform-first) stay fp32
 };
 
 // Fusing the transform into the gather kernel removes the aggregated matrix's HBM round trip and hides the MFMA
@@ -62,11 +64,8 @@ struct LayerPlan {
 //   GraphSAGE 256->256 (threshold ratio 1 = degree 16): degree 2 62/60, 4 63/66, 6 64/74, 8 66/82, 12 77/95;
 //   GCN 256->256 (degree 8): 2 41/41, 4 43/46, 6 45/53, 8 48/61;  GraphSAGE 128->128 (degree 8): 4 26/26, 6 27/28, 8 28/32;
 //   GraphSAGE 128->256 (degree 16): 6 41/40, 8 42/43, 12 44/51.  The crossovers sit at ratios 0.2-0.6: 0.5 it is.
-// DGI_TUNE_FUSED = 0 / 2 forces never / always (tuning aid).
+// dgi_layer_t.order = AGG_FIRST_FUSED / AGG_FIRST_SPLIT overrides this choice per layer.
 bool want_fused(const dgi_graph* g, int dtype, int K, int64_t ldw, int N) {
-    static const int mode = [] { const char* e = getenv("DGI_TUNE_FUSED"); return e ? atoi(e) : 1; }();
-    if (mode == 0) return false;
-    if (mode == 2) return true;
     const double avg_deg = g && g->N > 0 ? (double)g->E / (double)g->N : 0.0;
     const double ratio = avg_deg * (double)K / ((double)ldw * (double)N / 32.0);
     return ratio >= (dtype == DGI_BF16 ? 3.0 : 0.5);
@@ -103,6 +102,15 @@ dgi_status_t plan_layer(const dgi_graph* g, const dgi_layer_t* L, const void* h_
     p.mode = L->agg == DGI_AGG_MEAN ? MODE_MEAN : L->agg == DGI_AGG_GCN ? MODE_GCN : MODE_SUM;
     p.transform_first = p.gat || L->order == DGI_ORDER_TRANSFORM_FIRST ||
                         (L->order == DGI_ORDER_AUTO && L->out_dim < L->in_dim);
+    // bf16 storage means: inputs, weights and stored layers are bf16, everything in between is accumulated in fp32.
+    // An aggregated vector cut to 8 bits before the transform would be a second rounding per layer that the stored
+    // data does not have (measured on a 1.7 M-node down-scale of the 111 M-node bf16 benchmark: 2.3e-2 against the
+    // oracle instead of 1.1e-2), and under SUM, whose aggregate over a long neighbour list is far larger than its
+    // terms, an absolute error that is large next to the other rows of the output.  So the aggregated tile is a pair
+    // of bf16 values per element (the rounded value and the rounding remainder, together 16 mantissa bits) and both go
+    // through the matrix cores; and a transform-first SUM layer keeps its transformed rows in fp32.
+    p.wide_agg = L->feat_dtype == DGI_BF16 && !p.gat;
+    p.wide_sum = L->feat_dtype == DGI_BF16 && L->agg == DGI_AGG_SUM;
     const int in_p = (int)round_up(L->in_dim, p.E);
     if (p.gat) {
         p.K1p = in_p; p.ldw = in_p;
@@ -112,7 +120,7 @@ dgi_status_t plan_layer(const dgi_graph* g, const dgi_layer_t* L, const void* h_
         p.K1p = in_p; p.ldw = in_p;
         p.z_neigh_col = p.has_self ? (int)round_up(L->out_dim, p.E) : 0;
         p.w_rows = p.z_neigh_col + L->out_dim;
-        p.z_cols = p.w_rows; p.z_ld = round_up(p.z_cols, p.E); p.z_dtype = L->feat_dtype;
+        p.z_cols = p.w_rows; p.z_ld = round_up(p.z_cols, p.E); p.z_dtype = p.wide_sum ? (int)DGI_F32 : L->feat_dtype;
     } else {
         const int in_p2 = (int)round_up(L->in_dim, 2 * p.E);  // MFMA k-step granularity of the fused kernel
         p.K1p = p.has_self ? in_p2 : 0;
@@ -175,7 +183,7 @@ uint64_t batch_temp_bytes(const dgi_graph* g, const dgi_layer_t* L, const LayerP
     if (P.fused) return fused_temp_bytes(g, b, e, L->in_dim);
     uint64_t bytes = 0;
     if (!P.gat) bytes += round_up((int64_t)agg_hub_partial_bytes(g, b, e, P.transform_first ? L->out_dim : L->in_dim), 256);
-    if (!P.transform_first) bytes += (uint64_t)round_up((e - b) * P.agg_ld * P.eb, 256);
+    if (!P.transform_first) bytes += (uint64_t)round_up((e - b) * P.agg_ld * P.eb, 256) * (P.wide_agg ? 2 : 1);
     return bytes;
 }
 
@@ -261,8 +269,9 @@ dgi_status_t run_batch(const dgi_graph* g, const dgi_layer_t* L, const LayerPlan
         return DGI_OK;
     }
     void* agg = (char*)temp + part_bytes;
+    void* agg_lo = P.wide_agg ? (char*)agg + round_up((e - b) * P.agg_ld * P.eb, 256) : nullptr;
     a.S = h_in; a.ld_s = ld_in; a.s_dtype = L->feat_dtype; a.width = L->in_dim;
-    a.out = agg; a.ld_out = P.agg_ld; a.out_row0 = b; a.out_dtype = L->feat_dtype;
+    a.out = agg; a.out_lo = agg_lo; a.ld_out = P.agg_ld; a.out_row0 = b; a.out_dtype = L->feat_dtype;
     if (timer) DGI_TRY(timer->begin(SPAN_AGG));
     DGI_TRY(launch_aggregate(a, 0, s));
     if (timer) DGI_TRY(timer->end());
@@ -272,8 +281,10 @@ dgi_status_t run_batch(const dgi_graph* g, const dgi_layer_t* L, const LayerPlan
     if (P.has_self) {
         ga.A1 = (const char*)h_in + b * ld_in * P.eb; ga.ld_a1 = ld_in; ga.K1 = L->in_dim;
         ga.A2 = agg; ga.ld_a2 = P.agg_ld; ga.K2 = L->in_dim;
+        ga.A3 = agg_lo;
     } else {
         ga.A1 = agg; ga.ld_a1 = P.agg_ld; ga.K1 = L->in_dim;
+        if (agg_lo) { ga.A2 = agg_lo; ga.ld_a2 = P.agg_ld; ga.K2 = L->in_dim; }  // K1p is 0: the same weight block again
     }
     ga.Wt = Wt; ga.ldw = P.ldw; ga.K1p = P.K1p;
     ga.bias = L->bias; ga.act = L->act; ga.act_slope = L->act_slope;

@@ -1,9 +1,10 @@
 // Dense transform of a layer (the w^l part of Eq. 1) on the MFMA matrix cores, with the bias and the
 // activation fused into the epilogue so they run once per node in the producing layer.
 //
-//   Y[r, n] = act( sum_k A1[r,k] Wt[n,k] + sum_k A2[r,k] Wt[n,K1p+k] + bias[n] )
+//   Y[r, n] = act( sum_k A1[r,k] Wt[n,k] + sum_k (A2[r,k] + A3[r,k]) Wt[n,K1p+k] + bias[n] )
 //
-// A1|A2 is the row-wise concatenation [h_v | m_v] of GraphSAGE (A2 may be absent); Wt is the weight
+// A1|A2 is the row-wise concatenation [h_v | m_v] of GraphSAGE (A2 may be absent); A3, when present, is the
+// low-order part of an m_v that is stored as a pair of bf16 values (it multiplies the same weight block); Wt is the weight
 // packed transposed, [Nout x ldw] with K contiguous, so both MFMA operands are read from LDS rows of
 // the same shape.  fp32 data uses v_mfma_f32_32x32x2_f32, bf16 data v_mfma_f32_32x32x16_bf16, both with
 // fp32 accumulators.  A workgroup of 4 wavefronts owns a BM x BN output tile; each k-step stages a
@@ -24,6 +25,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 struct GemmParams {
     const void* A1; int64_t ld_a1; int K1; int a1_vec;
     const void* A2; int64_t ld_a2; int K2; int a2_vec;
+    const void* A3;  // optional third block: same shape, leading dimension and weight columns as A2
     const void* Wt; int64_t ldw; int K1p;
     const float* bias;
     int act; float act_slope;
@@ -83,16 +85,17 @@ void gemm_kernel(GemmParams p) {
 
     const int S1 = (p.K1 + BK - 1) / BK;
     const int S2 = p.A2 ? (p.K2 + BK - 1) / BK : 0;
-    const int S = S1 + S2;
+    const int S = S1 + S2 + (p.A3 ? S2 : 0);
     uint4 ra[A_CHUNKS], rb[B_CHUNKS];
 
     auto load_step = [&](int s) {
         const bool second = s >= S1;
-        const T* A = static_cast<const T*>(second ? p.A2 : p.A1);
+        const bool third = s >= S1 + S2;
+        const T* A = static_cast<const T*>(third ? p.A3 : second ? p.A2 : p.A1);
         const int64_t lda = second ? p.ld_a2 : p.ld_a1;
         const int K = second ? p.K2 : p.K1;
         const bool vec = second ? p.a2_vec : p.a1_vec;
-        const int k0 = (second ? s - S1 : s) * BK;
+        const int k0 = (third ? s - S1 - S2 : second ? s - S1 : s) * BK;
         const int wcol = second ? p.K1p : 0;
 #pragma unroll
         for (int i = 0; i < A_CHUNKS; ++i) {
@@ -349,7 +352,8 @@ dgi_status_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
     p.A1 = a.A1; p.ld_a1 = a.ld_a1; p.K1 = a.K1;
     p.a1_vec = ((uintptr_t)a.A1 % 16 == 0) && (a.ld_a1 % E == 0);
     p.A2 = a.K2 > 0 ? a.A2 : nullptr; p.ld_a2 = a.ld_a2; p.K2 = a.K2;
-    p.a2_vec = p.A2 && ((uintptr_t)a.A2 % 16 == 0) && (a.ld_a2 % E == 0);
+    p.A3 = p.A2 ? a.A3 : nullptr;
+    p.a2_vec = p.A2 && ((uintptr_t)a.A2 % 16 == 0) && (a.ld_a2 % E == 0) && ((uintptr_t)p.A3 % 16 == 0);
     p.Wt = a.Wt; p.ldw = a.ldw; p.K1p = a.K1p;
     p.bias = a.bias; p.act = a.act; p.act_slope = a.act_slope;
     p.Y = a.Y; p.ld_y = a.ld_y; p.out_bf16 = a.out_dtype == DGI_BF16;

@@ -205,8 +205,10 @@ dgi_status_t infer_host(const dgi_graph* g, const dgi_layer_t* layers, int32_t L
     // unless compute + dump exceed 0.38 of the load, the point where 1.6x the traffic costs as much as the lost
     // overlap.
     auto choose_slots = [&]() -> dgi_status_t {
-        const char* const env = getenv("DGI_TUNE_HOST_SLOTS");  // measurements only
-        if (env && *env) { n_slots = atoi(env) == 1 ? 1 : 2; return DGI_OK; }
+#ifdef DGI_HOST_SLOTS  // measurement builds pin the number of batches in flight
+        n_slots = DGI_HOST_SLOTS == 1 ? 1 : 2;
+        return DGI_OK;
+#endif
         if (whole <= budget) { n_slots = 1; return DGI_OK; }  // a whole layer at once: every row crosses the link once
         const int64_t n_t = o.batch_size > 0 ? o.batch_size : (o.init_node_threshold > 0 ? o.init_node_threshold : 65536);
         const int64_t n_i = o.batch_size > 0 ? INT64_MAX / 4

@@ -112,6 +112,8 @@ struct AggArgs {
     int s_dtype = DGI_F32;
     int width = 0;            // columns gathered
     void* out = nullptr;      // element (v, c) at out[(v - out_row0) * ld_out + c]
+    void* out_lo = nullptr;   // bf16 output only, optional: a second matrix of the same layout that receives
+                              // bf16(value - float(bf16(value))), so that out + out_lo carries 16 mantissa bits
     int64_t ld_out = 0;
     int64_t out_row0 = 0;
     int out_dtype = DGI_F32;
@@ -168,12 +170,15 @@ struct GatArgs {
 };
 dgi_status_t launch_gat(const GatArgs& a, hipStream_t stream);
 
-// Y[r, n] = act( sum_k A1[r,k] Wt[n,k] + sum_k A2[r,k] Wt[n,K1p+k] + bias[n] ),  r in [0,M), n in [0,Nout).
-// Wt is the packed transposed weight [Nout x ldw] (K contiguous); the A2 block starts at column K1p.
+// Y[r, n] = act( sum_k A1[r,k] Wt[n,k] + sum_k (A2[r,k] + A3[r,k]) Wt[n,K1p+k] + bias[n] ),  r in [0,M), n in [0,Nout).
+// Wt is the packed transposed weight [Nout x ldw] (K contiguous); the A2 block starts at column K1p.  A3 (optional,
+// needs A2; same shape and leading dimension) multiplies the same weight columns as A2: the low-order halves of an
+// A2 that is kept as a pair of bf16 values.
 struct GemmArgs {
     int dtype = DGI_F32;        // dtype of A1, A2 and Wt
     const void* A1 = nullptr; int64_t ld_a1 = 0; int K1 = 0;
     const void* A2 = nullptr; int64_t ld_a2 = 0; int K2 = 0;
+    const void* A3 = nullptr;
     const void* Wt = nullptr; int64_t ldw = 0; int K1p = 0;
     const float* bias = nullptr;
     int act = DGI_ACT_NONE; float act_slope = 0.f;
