@@ -226,6 +226,8 @@ def main():
     ap.add_argument("--config", type=int, default=4)
     ap.add_argument("--scale", type=float, default=1.0)
     ap.add_argument("--batch-size", type=int, default=0, help="destination rows per batch; 0 = dynamic")
+    ap.add_argument("--order", choices=["auto", "agg_first", "transform_first", "agg_first_fused", "agg_first_split"], default="auto",
+                    help="force every layer's execution order (dgi_layer_t.order); auto = the library's choice")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-configs", dest="other_configs", action="store_false",
                     help="skip the short runs of the other full-size workloads that the headline line carries as context")
@@ -266,7 +268,7 @@ def main():
     structs, keep = [], []
     for i, L in enumerate(cfg["layers"]):
         fs = storage if i == 0 else cfg["layers"][i - 1].get("out_storage", "f32")
-        s, k = B.make_layer(L, device=dev, feat_dtype=fs)
+        s, k = B.make_layer(dict(L, order=args.order), device=dev, feat_dtype=fs)
         structs.append(s)
         keep.append(k)
     x = cfg["x"].contiguous()

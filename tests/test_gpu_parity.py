@@ -480,6 +480,44 @@ def test_fused_layer_with_eight_or_more_column_blocks(storage, dims, agg):
     assert max_rel_err(got, want) <= (TOL_BF16 if storage == "bf16" else TOL_F32)
 
 
+def _graph_with_medium_and_hub_rows(n, seed):
+    """Poisson rows plus rows of 65..1000 in-edges (gathered by a whole wavefront), two hub rows (chunked pre-pass),
+    one of them in the last tile, and empty rows."""
+    rng = np.random.default_rng(seed)
+    deg = rng.poisson(5.0, n)
+    deg[rng.random(n) < 0.2] = 0
+    for v, d in zip(rng.choice(n - 2, 12, replace=False), (65, 66, 100, 127, 128, 129, 300, 511, 512, 700, 1000, 1024)):
+        deg[v] = d
+    deg[n // 3] = 3000
+    deg[n - 1] = 1500
+    indptr = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(deg, out=indptr[1:])
+    return indptr, rng.integers(0, n, indptr[-1]).astype(np.int32)
+
+
+@pytest.mark.parametrize("agg", ["mean", "sum", "gcn"])
+@pytest.mark.parametrize("dims", [(128, 128), (128, 172), (96, 64), (72, 33), (128, 192), (120, 40)])
+def test_fused_layer_on_narrow_bf16_rows(agg, dims):
+    # the fused kernel on bf16 rows of at most 128 elements (16 lanes per source row, the aggregate kept in LDS as bf16
+    # value + rounding remainder): rows of 65..1024 in-edges, hub rows through the pre-pass, a ragged last tile, both
+    # indptr types, with and without own features, bf16 and fp32 outputs, destination sub-ranges
+    n = 5000
+    d_in, d_out = dims
+    indptr, indices = _graph_with_medium_and_hub_rows(n, seed=d_in + d_out)
+    X, Ws, Wn = [torch.from_numpy(a).to(torch.bfloat16).float().numpy() for a in (rnd((n, d_in), 1), rnd((d_in, d_out), 2, 0.1), rnd((d_in, d_out), 3, 0.1))]
+    for itype, with_self, out_storage, rng_ in ((torch.int64, True, "bf16", (0, n)), (torch.int32, False, "f32", (0, n)), (torch.int32, True, "f32", (37, n - 1))):
+        g = B().graph_load(torch.from_numpy(indptr).to("cuda").to(itype), torch.from_numpy(indices).to("cuda"))
+        layer = dict(agg=agg, act="relu", W_self=Ws if (with_self and agg != "gcn") else None, W_neigh=Wn, bias=rnd((d_out,), 4),
+                     order="agg_first_fused", out_storage=out_storage)
+        b, e = rng_
+        got = gpu_layer(g, layer, X, b, e, storage="bf16")
+        want = oracle.layer_forward(indptr, indices, layer, X)
+        assert max_rel_err(got[b:e], want[b:e]) <= TOL_BF16, (itype, with_self, out_storage)
+        if out_storage == "f32":
+            assert max_rel_err(got[b:e], want[b:e]) <= 2e-3      # nothing rounded to bf16 after the inputs
+        assert (got[:b] == 777.0).all() and (got[e:] == 777.0).all()
+
+
 @pytest.mark.parametrize("order", ["agg_first_split", "agg_first_fused", "transform_first", "auto"])
 @pytest.mark.parametrize("dims,with_self", [((128, 128), True), ((64, 256), False), ((256, 48), True)])
 def test_bf16_sum_over_long_rows_keeps_fp32_accumulation(order, dims, with_self):
