@@ -248,7 +248,8 @@ dgi_status_t dgi_infer_partial(const dgi_graph_t* g, const dgi_layer_t* layers, 
  * the graph structure is on the device, the feature matrices H^0 .. H^L live in host memory, and every batch
  * loads its input set, computes one layer for its destination rows and dumps them back).
  *   x_host   : HOST, page-locked (hipHostMalloc / a pinned tensor), [N x layers[0].in_dim], leading dimension ld_x.
- *   out_host : HOST, page-locked, [N x layers[L-1].out_dim], leading dimension ld_out.
+ *   out_host : HOST, page-locked, [N x layers[L-1].out_dim], leading dimension ld_out; only columns [0, out_dim) of
+ *              its rows are written.
  * Hidden layers H^1 .. H^{L-1} are kept in two page-locked host buffers used alternately (H^{l-1}'s buffer is
  * reused when layer l is done); they and the device memory of the batches stay in the graph handle between
  * calls (dgi_graph_release_workspace or dgi_graph_free returns them), and calls on one handle are serialised.

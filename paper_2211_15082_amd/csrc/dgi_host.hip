@@ -85,14 +85,15 @@ dgi_status_t device_view(const void* host, const char* what, void** dev) {
     return DGI_OK;
 }
 
-// Device rows to host memory.  Equal leading dimensions: one contiguous copy by the DMA engine.  Otherwise a
-// kernel writes the rows through the mapped host address: a pitched DMA copy of sub-kilobyte rows ran at
-// 14 GB/s here, a third of the link.
+// Device rows to host memory; only columns [0, width) of the destination rows are written.  Dense rows on both sides
+// (width == both leading dimensions): one contiguous copy by the DMA engine.  Otherwise a kernel writes the rows
+// through the mapped host address: a pitched DMA copy of sub-kilobyte rows ran at 14 GB/s here, a third of the
+// link (and a contiguous copy of padded rows would write the device buffer's padding columns into the caller's).
 dgi_status_t store_rows(const void* src_dev, int64_t ld_src, void* dst_host, void* dst_host_dev, int64_t ld_dst, int64_t rows, int width, int eb,
                         hipStream_t s) {
     if (rows == 0) return DGI_OK;
-    if (ld_src == ld_dst) {
-        DGI_HIP(hipMemcpyAsync(dst_host, src_dev, (size_t)((rows - 1) * ld_dst + width) * eb, hipMemcpyDeviceToHost, s));
+    if (ld_src == ld_dst && width == ld_dst) {
+        DGI_HIP(hipMemcpyAsync(dst_host, src_dev, (size_t)rows * width * eb, hipMemcpyDeviceToHost, s));
         return DGI_OK;
     }
     return launch_permute_rows(src_dev, ld_src, dst_host_dev, ld_dst, rows, width, eb, nullptr, true, s);

@@ -109,6 +109,26 @@ def test_host_resident_inference_matches_the_oracle(kind):
     assert st3["device_resident"] == 0 and st["device_resident"] == 0
 
 
+def test_host_output_columns_beyond_the_layer_width_are_left_alone():
+    # out_host as the first 47 columns of a 48-column pinned matrix (the library's device buffers pad 47 to 48 as well):
+    # column 47 belongs to the caller and must keep its contents, in the device-resident shortcut and when streaming
+    bd = B()
+    n = 3000
+    indptr, indices = random_csr(n, 4.0, seed=29)
+    X = rnd((n, 32), 1)
+    layers = [dict(agg="mean", act="relu", W_self=rnd((32, 64), 2, 0.2), W_neigh=rnd((32, 64), 3, 0.2), bias=rnd((64,), 4)),
+              dict(agg="mean", act="none", W_self=rnd((64, 47), 5, 0.2), W_neigh=rnd((64, 47), 6, 0.2), bias=None)]
+    want = oracle.infer(indptr, indices, layers, X)
+    g = bd.graph_load(indptr, indices)
+    structs, keep = zip(*[bd.make_layer(L) for L in layers])
+    x = pinned(X)
+    for kw in (dict(), dict(stream_always=True), dict(stream_always=True, batch_size=500)):
+        wide = torch.full((n, 48), 777.0, dtype=torch.float32, pin_memory=True)
+        bd.infer_host(g, list(structs), x, wide[:, :47], **kw)
+        assert max_rel_err(wide[:, :47].numpy(), want) <= TOL_F32, kw
+        assert bool((wide[:, 47] == 777.0).all()), kw
+
+
 def test_host_resident_thresholds_are_halved_when_a_batch_does_not_fit():
     bd = B()
     n = 4000
