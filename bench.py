@@ -116,7 +116,7 @@ def ablation(args, cfg, g, structs, x, out, B):
     import torch
     n = cfg["num_nodes"]
     variants = [("shuffled ids", g, None, 0.0)]
-    for method in ("bfs_rcm", "degree"):
+    for method in ("bfs_rcm", "community", "degree"):
         t0 = time.perf_counter()
         g2, perm = B.graph_reorder(g, method)
         torch.cuda.synchronize()
@@ -235,7 +235,7 @@ def main():
     ap.add_argument("--fanout", type=int, default=0, help="sampling inference with this fan-out per layer (prints its own JSON line)")
     ap.add_argument("--host-resident", action="store_true",
                     help="embeddings in pinned host memory, batches streamed in (dgi_infer_host); prints its own JSON line")
-    ap.add_argument("--reorder", choices=["none", "degree", "bfs_rcm"], default="none",
+    ap.add_argument("--reorder", choices=["none", "degree", "bfs_rcm", "community"], default="none",
                     help="--host-resident: renumber the nodes with the library's reordering first (Section 4.2)")
     ap.add_argument("--allow-device-resident", action="store_true",
                     help="--host-resident: let the library keep the hidden layers on the device when everything fits the budget")

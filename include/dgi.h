@@ -72,8 +72,16 @@ typedef enum {
 /* Node renumbering used to form batches of consecutive ids that share in-neighbours (Section 4.2).
  *   DEGREE : descending in-degree, ties by old id ("Degree Sorting" of Section 5.3)
  *   BFS_RCM: reverse Cuthill-McKee style BFS enumeration on the undirected structure (the paper's RCMK)
- *   RANDOM : seeded shuffle (the "Random" comparison point)                                             */
-typedef enum { DGI_REORDER_NONE = 0, DGI_REORDER_DEGREE = 1, DGI_REORDER_BFS_RCM = 2, DGI_REORDER_RANDOM = 3 } dgi_reorder_t;
+ *   RANDOM : seeded shuffle (the "Random" comparison point)
+ *   COMMUNITY: ids grouped by the label that DGI_COMMUNITY_ROUNDS rounds of label propagation on the undirected
+ *            structure leave on every node (each node repeatedly takes the most frequent label among its in- and
+ *            out-neighbours), ties inside a group by old id.  A BFS frontier mixes the communities of a graph after a
+ *            few levels; this keeps each one contiguous, which is what makes a batch of consecutive ids share its
+ *            in-neighbours when the graph has communities.  Not one of the paper's orderings (Section 4.2 compares
+ *            RCMK with Random, Degree Sorting and Rabbit Order): a cheap stand-in for the community-based class. */
+typedef enum { DGI_REORDER_NONE = 0, DGI_REORDER_DEGREE = 1, DGI_REORDER_BFS_RCM = 2, DGI_REORDER_RANDOM = 3,
+               DGI_REORDER_COMMUNITY = 4 } dgi_reorder_t;
+#define DGI_COMMUNITY_ROUNDS 10
 
 typedef struct dgi_graph dgi_graph_t; /* opaque; owns device copies of the CSR and degree vectors */
 
@@ -177,8 +185,9 @@ dgi_status_t dgi_graph_csr(const dgi_graph_t* g, int64_t* indptr, int32_t* indic
 /* Node reordering (Section 4.2).  Builds a renumbered copy of `g` (rows permuted, sources relabelled,
  * each row sorted by new source id) and writes perm_new_of_old[old] = new into a buffer of N int32 at
  * `perm_where` (HOST or DEVICE).  Any bijection leaves the inference result unchanged up to rounding;
- * only locality differs.  The permutation is computed on the host from the handle's CSR; relabelling
- * runs on the device.  `seed` is used by RANDOM only. */
+ * only locality differs.  DEGREE, BFS_RCM and COMMUNITY permutations are computed on the device (on the
+ * host, by the same rule, for graphs beyond the device routines' 2^30-edge limit); relabelling runs on the device.
+ * `seed` is used by RANDOM only. */
 dgi_status_t dgi_graph_reorder(const dgi_graph_t* g, int32_t method, uint64_t seed, void* hip_stream,
                                dgi_graph_t** g_out, int32_t* perm_new_of_old, int32_t perm_where);
 

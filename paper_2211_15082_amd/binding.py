@@ -20,7 +20,7 @@ F32, BF16 = 0, 1
 AGG = {"sum": 0, "mean": 1, "gcn": 2, "gat": 3}
 ACT = {"none": 0, "relu": 1, "elu": 2, "leaky_relu": 3}
 ORDER = {"auto": 0, "agg_first": 1, "transform_first": 2, "agg_first_fused": 3, "agg_first_split": 4}
-REORDER = {"none": 0, "degree": 1, "bfs_rcm": 2, "random": 3}
+REORDER = {"none": 0, "degree": 1, "bfs_rcm": 2, "random": 3, "community": 4}
 MAX_LAYERS = 16
 
 

@@ -282,7 +282,8 @@ extern "C" dgi_status_t dgi_graph_reorder(const dgi_graph_t* g, int32_t method, 
     struct FreeOnExit { int32_t*& p; ~FreeOnExit() { (void)hipFree(p); p = nullptr; } } perm_guard{d_perm};
     // the permutation: on the device for DEGREE / BFS_RCM, on the host otherwise (and beyond the device limits)
     dgi_status_t pst = DGI_ERR_UNSUPPORTED;
-    if (method == DGI_REORDER_DEGREE || method == DGI_REORDER_BFS_RCM) pst = reorder_permutation_device(g, method, d_perm, stream);
+    if (method == DGI_REORDER_DEGREE || method == DGI_REORDER_BFS_RCM || method == DGI_REORDER_COMMUNITY)
+        pst = reorder_permutation_device(g, method, d_perm, stream);
     if (pst == DGI_OK) {
         if (N) DGI_HIP(hipMemcpy(perm.data(), d_perm, (size_t)N * 4, hipMemcpyDeviceToHost));
     } else if (pst == DGI_ERR_UNSUPPORTED) {

@@ -9,6 +9,13 @@
 //           unvisited neighbours of a dequeued node are appended in ascending (degree, old id) order.  After
 //           kMaxBfsComponents components the remaining nodes are appended in (degree, id) order.
 //  RANDOM : seeded Fisher-Yates shuffle.
+//  COMMUNITY: synchronous label propagation on the undirected structure, then ids by (label, old id).  The rule, which
+//           the device kernels follow to the letter: labels start as the node ids; in round r the nodes whose id has
+//           the parity of r take a new label, the others keep theirs (two half-steps never flip-flop); a node's
+//           neighbour list is its in-neighbours in stored order followed by its out-neighbours in ascending id, with
+//           multiplicity; the list is read in chunks of 64, a chunk's winner is its most frequent label (ties: the
+//           smallest label), and chunk winners are merged in order: the same label as the running winner adds its
+//           count, a different one replaces it only with a strictly larger count.
 #include <algorithm>
 #include <numeric>
 #include <vector>
@@ -98,6 +105,49 @@ void rcm_order(int64_t N, const int64_t* indptr, const int32_t* indices, int32_t
     for (int64_t r = 0; r < N; ++r) perm[order[r]] = (int32_t)(N - 1 - r);  // reversed enumeration
 }
 
+void community_order(int64_t N, const int64_t* indptr, const int32_t* indices, int32_t* perm) {
+    // out-neighbour lists in ascending destination id (edges are visited by ascending destination row)
+    std::vector<int64_t> optr((size_t)N + 1, 0);
+    for (int64_t e = 0; e < indptr[N]; ++e) optr[(int64_t)indices[e] + 1] += 1;
+    for (int64_t v = 0; v < N; ++v) optr[v + 1] += optr[v];
+    std::vector<int32_t> oidx((size_t)indptr[N]);
+    {
+        std::vector<int64_t> cur(optr.begin(), optr.end() - 1);
+        for (int64_t v = 0; v < N; ++v)
+            for (int64_t e = indptr[v]; e < indptr[v + 1]; ++e) oidx[cur[indices[e]]++] = (int32_t)v;
+    }
+    std::vector<int32_t> lab((size_t)N), nxt((size_t)N), chunk;
+    std::iota(lab.begin(), lab.end(), 0);
+    for (int r = 0; r < DGI_COMMUNITY_ROUNDS; ++r) {
+        for (int64_t v = 0; v < N; ++v) {
+            nxt[v] = lab[v];
+            if (((v ^ r) & 1) != 0) continue;
+            const int64_t din = indptr[v + 1] - indptr[v], total = din + (optr[v + 1] - optr[v]);
+            int32_t best = -1;
+            int64_t cnt = 0;
+            for (int64_t base = 0; base < total; base += 64) {
+                chunk.clear();
+                for (int64_t j = base; j < std::min(total, base + 64); ++j)
+                    chunk.push_back(lab[j < din ? indices[indptr[v] + j] : oidx[optr[v] + (j - din)]]);
+                int32_t w = -1;
+                int64_t c = 0;
+                for (int32_t a : chunk) {
+                    const int64_t ca = std::count(chunk.begin(), chunk.end(), a);
+                    if (ca > c || (ca == c && a < w)) { w = a; c = ca; }
+                }
+                if (w == best) cnt += c;
+                else if (c > cnt) { best = w; cnt = c; }
+            }
+            if (total > 0) nxt[v] = best;
+        }
+        lab.swap(nxt);
+    }
+    std::vector<int32_t> order((size_t)N);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return lab[a] < lab[b]; });
+    for (int64_t r = 0; r < N; ++r) perm[order[r]] = (int32_t)r;
+}
+
 }  // namespace
 
 dgi_status_t reorder_permutation(int64_t N, const int64_t* indptr, const int32_t* indices, int method, uint64_t seed,
@@ -111,6 +161,10 @@ dgi_status_t reorder_permutation(int64_t N, const int64_t* indptr, const int32_t
         case DGI_REORDER_BFS_RCM:
             DGI_REQUIRE(indices || indptr[N] == 0, DGI_ERR_INVALID_ARG, "reorder: indices is NULL");
             rcm_order(N, indptr, indices, perm);
+            return DGI_OK;
+        case DGI_REORDER_COMMUNITY:
+            DGI_REQUIRE(indices || indptr[N] == 0, DGI_ERR_INVALID_ARG, "reorder: indices is NULL");
+            community_order(N, indptr, indices, perm);
             return DGI_OK;
     }
     set_error("reorder: unknown method %d", method);

@@ -8,6 +8,10 @@
 //           radix sorts, and every component starts at the unvisited node of smallest (degree, id).  After
 //           kMaxBfsComponents components the remaining nodes are appended in (degree, id) order, as on the host.
 //
+//  COMMUNITY: label propagation (one wavefront per node: the labels of up to 64 neighbours at a time are counted
+//           against each other with lane broadcasts), then a stable radix sort of the ids by label.  Follows the rule
+//           stated in dgi_reorder.cpp exactly.
+//
 // Out-neighbour lists come from a radix sort of the edges by source (the CSR only stores in-neighbours).
 #include <hipcub/hipcub.hpp>
 
@@ -266,6 +270,95 @@ dgi_status_t rcm_perm(const dgi_graph* g, int32_t* d_perm, hipStream_t s) {
     return DGI_OK;
 }
 
+__global__ void iota_i32_kernel(int32_t* p, int64_t n) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = (int32_t)i;
+}
+
+// One round of label propagation, one wavefront per node.  Nodes whose id has the parity of `round` take the most
+// frequent label among their in- and out-neighbours (64 at a time, see dgi_reorder.cpp for the exact rule).
+template <typename IdxT>
+__global__ __launch_bounds__(256) void label_round_kernel(const IdxT* indptr, const int32_t* indices, const int64_t* out_ptr,
+                                                          const int32_t* out_idx, int64_t N, const int32_t* lab, int32_t* nxt, int round) {
+    const int lane = threadIdx.x & 63;
+    const int64_t waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    for (int64_t v = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; v < N; v += waves) {
+        if (((v ^ round) & 1) != 0) {
+            if (lane == 0) nxt[v] = lab[v];
+            continue;
+        }
+        const int64_t ia = (int64_t)indptr[v], din = (int64_t)indptr[v + 1] - ia;
+        const int64_t oa = out_ptr[v], total = din + (out_ptr[v + 1] - oa);
+        int32_t best = -1;
+        int64_t cnt = 0;
+        for (int64_t base = 0; base < total; base += 64) {
+            const int64_t j = base + lane;
+            const bool has = j < total;
+            int32_t l = -1;
+            if (has) l = lab[j < din ? indices[ia + j] : out_idx[oa + (j - din)]];
+            int c = 0;
+#pragma unroll
+            for (int k = 0; k < 64; ++k) c += (__builtin_amdgcn_readlane(l, k) == l) ? 1 : 0;
+            // largest count wins, ties go to the smallest label: maximise (count, 0x7fffffff - label)
+            unsigned long long key = has ? (((unsigned long long)c << 32) | (unsigned)(0x7fffffff - l)) : 0ull;
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                const unsigned lo = (unsigned)__shfl_xor((int)(unsigned)key, off, 64), hi = (unsigned)__shfl_xor((int)(unsigned)(key >> 32), off, 64);
+                const unsigned long long other = ((unsigned long long)hi << 32) | lo;
+                key = other > key ? other : key;
+            }
+            const int32_t w = (int32_t)(0x7fffffff - (unsigned)key);
+            const int64_t cw = (int64_t)(key >> 32);
+            if (w == best) cnt += cw;
+            else if (cw > cnt) { best = w; cnt = cw; }
+        }
+        if (lane == 0) nxt[v] = total > 0 ? best : lab[v];
+    }
+}
+
+template <typename IdxT>
+dgi_status_t community_perm(const dgi_graph* g, int32_t* d_perm, hipStream_t s) {
+    const int64_t N = g->N, E = g->E;
+    DGI_REQUIRE(E + 1 < (int64_t)INT_MAX && N < (int64_t)INT_MAX, DGI_ERR_UNSUPPORTED,
+                "device community reordering handles up to 2^31 edges (32-bit item counts of the sort/scan primitives)");
+    const IdxT* indptr = (const IdxT*)g->d_indptr;
+    DevBuf dst, src_sorted, out_idx, out_cnt, out_ptr, lab, nxt, ids, ids2, tmp;
+    DGI_TRY(dst.alloc(E * 4)); DGI_TRY(src_sorted.alloc(E * 4)); DGI_TRY(out_idx.alloc(E * 4));
+    DGI_TRY(out_cnt.alloc((N + 1) * 8)); DGI_TRY(out_ptr.alloc((N + 1) * 8));
+    DGI_TRY(lab.alloc(N * 4)); DGI_TRY(nxt.alloc(N * 4)); DGI_TRY(ids.alloc(N * 4)); DGI_TRY(ids2.alloc(N * 4));
+    // out-neighbour lists: a stable sort of the edges by source keeps each list in ascending destination id
+    hipLaunchKernelGGL(edge_rows_kernel<IdxT>, dim3(blocks_for(N * 64)), dim3(kBlock), 0, s, indptr, N, dst.as<int32_t>());
+    hipLaunchKernelGGL(undirected_degree_kernel<IdxT>, dim3(blocks_for(N)), dim3(kBlock), 0, s, indptr, g->d_deg_out, N,
+                       nxt.as<uint32_t>(), ids.as<int32_t>(), out_cnt.as<int64_t>());
+    size_t tb = 0, t2 = 0;
+    int bits = 1;
+    while (((int64_t)1 << bits) < N) ++bits;
+    DGI_CUB(hipcub::DeviceRadixSort::SortPairs(nullptr, tb, g->d_indices, src_sorted.as<int32_t>(), dst.as<int32_t>(), out_idx.as<int32_t>(), (int)E, 0, bits, s));
+    DGI_CUB(hipcub::DeviceScan::ExclusiveSum(nullptr, t2, out_cnt.as<int64_t>(), out_ptr.as<int64_t>(), (int)(N + 1), s));
+    tb = std::max(tb, t2);
+    DGI_CUB(hipcub::DeviceRadixSort::SortPairs(nullptr, t2, lab.as<int32_t>(), nxt.as<int32_t>(), ids.as<int32_t>(), ids2.as<int32_t>(), (int)N, 0, bits, s));
+    tb = std::max(tb, t2);
+    DGI_TRY(tmp.alloc(tb));
+    if (E) DGI_CUB(hipcub::DeviceRadixSort::SortPairs(tmp.p, tb, g->d_indices, src_sorted.as<int32_t>(), dst.as<int32_t>(), out_idx.as<int32_t>(), (int)E, 0, bits, s));
+    DGI_CUB(hipcub::DeviceScan::ExclusiveSum(tmp.p, tb, out_cnt.as<int64_t>(), out_ptr.as<int64_t>(), (int)(N + 1), s));
+    (void)hipFree(dst.p); dst.p = nullptr;
+    (void)hipFree(src_sorted.p); src_sorted.p = nullptr;
+    hipLaunchKernelGGL(iota_i32_kernel, dim3(blocks_for(N)), dim3(kBlock), 0, s, lab.as<int32_t>(), N);
+    int32_t *a = lab.as<int32_t>(), *b = nxt.as<int32_t>();
+    for (int r = 0; r < DGI_COMMUNITY_ROUNDS; ++r) {
+        hipLaunchKernelGGL(label_round_kernel<IdxT>, dim3(blocks_for(N * 64)), dim3(kBlock), 0, s, indptr, g->d_indices, out_ptr.as<int64_t>(),
+                           out_idx.as<int32_t>(), N, a, b, r);
+        std::swap(a, b);
+    }
+    DGI_HIP(hipGetLastError());
+    // ids by (label, old id): stable sort of 0..N-1 by label
+    hipLaunchKernelGGL(iota_i32_kernel, dim3(blocks_for(N)), dim3(kBlock), 0, s, ids.as<int32_t>(), N);
+    DGI_CUB(hipcub::DeviceRadixSort::SortPairs(tmp.p, tb, a, b, ids.as<int32_t>(), ids2.as<int32_t>(), (int)N, 0, bits, s));
+    hipLaunchKernelGGL(invert_order_kernel, dim3(blocks_for(N)), dim3(kBlock), 0, s, ids2.as<int32_t>(), N, d_perm, 0);
+    DGI_HIP(hipGetLastError());
+    DGI_HIP(hipStreamSynchronize(s));
+    return DGI_OK;
+}
+
 }  // namespace
 
 dgi_status_t reorder_permutation_device(const dgi_graph* g, int method, int32_t* d_perm, hipStream_t stream) {
@@ -273,7 +366,8 @@ dgi_status_t reorder_permutation_device(const dgi_graph* g, int method, int32_t*
     const bool i64 = g->itype == DGI_I64;
     if (method == DGI_REORDER_DEGREE) return i64 ? degree_perm<int64_t>(g, d_perm, stream) : degree_perm<int32_t>(g, d_perm, stream);
     if (method == DGI_REORDER_BFS_RCM) return i64 ? rcm_perm<int64_t>(g, d_perm, stream) : rcm_perm<int32_t>(g, d_perm, stream);
-    set_error("device reordering implements DEGREE and BFS_RCM only");
+    if (method == DGI_REORDER_COMMUNITY) return i64 ? community_perm<int64_t>(g, d_perm, stream) : community_perm<int32_t>(g, d_perm, stream);
+    set_error("device reordering implements DEGREE, BFS_RCM and COMMUNITY only");
     return DGI_ERR_UNSUPPORTED;
 }
 

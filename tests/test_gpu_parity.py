@@ -279,7 +279,7 @@ def test_memory_budget_forces_small_batches_and_oom_is_reported():
     assert ei.value.status == bd.ERR_OOM
 
 
-@pytest.mark.parametrize("method", ["degree", "bfs_rcm", "random"])
+@pytest.mark.parametrize("method", ["degree", "bfs_rcm", "random", "community"])
 def test_reordered_graph_gives_the_same_output(method):
     bd = B()
     cfg = configs.make_config(1)
@@ -326,7 +326,7 @@ def test_graph_vectors_and_validation():
     assert g0.info()["num_nodes"] == 0
 
 
-@pytest.mark.parametrize("method", ["degree", "bfs_rcm"])
+@pytest.mark.parametrize("method", ["degree", "bfs_rcm", "community"])
 def test_device_reordering_equals_the_sequential_algorithm(method):
     # the permutation is computed by kernels in dgi_graph_reorder and by a plain sequential routine in
     # dgi_reorder_permutation; both follow the same rule, so they agree exactly

@@ -111,7 +111,7 @@ def test_input_set_of_the_papers_toy_batches():
     assert B.batch_input_set_size(indptr, indices, 3, 6) == 0
 
 
-@pytest.mark.parametrize("method", ["degree", "bfs_rcm", "random", "none"])
+@pytest.mark.parametrize("method", ["degree", "bfs_rcm", "random", "none", "community"])
 def test_reorder_permutation_is_a_bijection(method):
     indptr, indices = random_csr(300, 4.0, seed=3)
     perm = B.reorder_permutation(indptr, indices, method, seed=7)
@@ -155,6 +155,40 @@ def test_bfs_order_shares_inputs_on_a_community_graph():
     ident = np.arange(n, dtype=np.int32)
     rcm = B.reorder_permutation(indptr, indices, "bfs_rcm")
     assert _total_inputs(indptr, indices, rcm, 50) < 0.5 * _total_inputs(indptr, indices, ident, 50)
+
+
+def test_community_order_keeps_planted_communities_contiguous():
+    # 30 planted communities of 40..100 nodes, 12 in-edges per node, one in eight of them leaving the community, ids
+    # shuffled: label propagation leaves one label per community (a stray node with mostly outside neighbours aside), so
+    # a community occupies a contiguous id range and batches of consecutive ids read far fewer distinct inputs than
+    # with the shuffled ids or the BFS order
+    rng = np.random.default_rng(11)
+    sizes = rng.integers(40, 101, 30)
+    start = np.concatenate([[0], np.cumsum(sizes)])
+    n = int(start[-1])
+    comm = np.repeat(np.arange(30), sizes)
+    shuffle = rng.permutation(n)          # shuffled id of original node i
+    rows = [None] * n
+    for i in range(n):
+        c = comm[i]
+        nb = rng.choice(np.arange(start[c], start[c + 1]), size=12, replace=False)
+        out = rng.random(12) < 0.125
+        nb[out] = rng.integers(0, n, int(out.sum()))
+        rows[shuffle[i]] = np.sort(shuffle[nb])
+    indptr = np.arange(0, 12 * n + 1, 12, dtype=np.int64)
+    indices = np.concatenate(rows).astype(np.int32)
+    perm = B.reorder_permutation(indptr, indices, "community")
+    assert sorted(perm.tolist()) == list(range(n))
+    new_of_orig = perm[shuffle]
+    runs = []
+    for c in range(30):
+        ids = np.sort(new_of_orig[start[c]:start[c + 1]])
+        runs.append(1 + int((np.diff(ids) > 1).sum()))   # contiguous id ranges the community falls into
+    assert sum(r == 1 for r in runs) >= 27 and max(runs) <= 3, runs
+    ident = np.arange(n, dtype=np.int32)
+    rcm = B.reorder_permutation(indptr, indices, "bfs_rcm")
+    t_comm, t_rcm, t_id = (_total_inputs(indptr, indices, p_, 64) for p_ in (perm, rcm, ident))
+    assert t_comm < 0.5 * t_id and t_comm < t_rcm
 
 
 def test_rcm_on_a_path_is_the_path():
