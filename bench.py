@@ -218,6 +218,46 @@ def sampling(args, cfg, g, structs, x, out, B):
                       "sample_one_layer_ms": t_sample * 1e3, "sampled_edges_per_second": len(structs) * kept / sec}))
 
 
+def partial(args, cfg, g, structs, x, B):
+    """Partial inference (Section 3.3; the paper's figure of time against the number of targets): random target sets of
+    growing size, the per-layer sets the library annotates, the rows each layer computes, and the time next to that of
+    full inference.  Separate line, never the headline value."""
+    import torch
+    n, e = cfg["num_nodes"], int(cfg["indices"].numel())
+    out_dim = structs[-1].out_dim
+    full = torch.empty(n, out_dim, dtype=torch.float32, device="cuda")
+    B.infer(g, structs, x, full)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        B.infer(g, structs, x, full)
+    torch.cuda.synchronize()
+    full_ms = (time.perf_counter() - t0) / args.steps * 1e3
+    del full
+    runs = []
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(77)
+    for count in [int(c) for c in args.partial.split(",")]:
+        count = min(count, n)
+        targets = torch.randperm(n, device="cuda", generator=gen)[:count].to(torch.int32)
+        out = torch.empty(count, out_dim, dtype=torch.float32, device="cuda")
+        st = B.infer_partial(g, structs, x, targets, out)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            st = B.infer_partial(g, structs, x, targets, out)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / args.steps * 1e3
+        runs.append({"targets": count, "ms": round(ms, 3), "set_size": st["set_size"], "rows_computed": st["rows_computed"],
+                     "shortcut_all_nodes_up_to_layer": st["all_nodes_from_layer"], "sub_nodes": st["sub_nodes"], "sub_edges": st["sub_edges"]})
+        print("[bench] %s" % json.dumps(runs[-1]), file=sys.stderr, flush=True)
+        del out, targets
+    print(json.dumps({"metric": "partial inference: milliseconds per call against the number of targets", "unit": "ms", "higher_is_better": False,
+                      "n_gpus": 1, "steps": args.steps, "data": "synthetic",
+                      "config": {"workload": cfg["name"] + " [partial inference]", "num_nodes": n, "num_edges": e},
+                      "full_inference_ms": round(full_ms, 3), "runs": runs}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -232,6 +272,8 @@ def main():
     ap.add_argument("--no-other-configs", dest="other_configs", action="store_false",
                     help="skip the short runs of the other full-size workloads that the headline line carries as context")
     ap.add_argument("--ablation", action="store_true", help="reordering x batch-size ablation instead of the timed run")
+    ap.add_argument("--partial", default="", metavar="COUNTS",
+                    help="partial inference of random target sets of these sizes, e.g. 100,1000,10000,100000,1000000 (prints its own JSON line)")
     ap.add_argument("--fanout", type=int, default=0, help="sampling inference with this fan-out per layer (prints its own JSON line)")
     ap.add_argument("--host-resident", action="store_true",
                     help="embeddings in pinned host memory, batches streamed in (dgi_infer_host); prints its own JSON line")
@@ -279,6 +321,10 @@ def main():
         return
     if args.fanout > 0:
         sampling(args, cfg, g, structs, x, out, B)
+        return
+    if args.partial:
+        del out
+        partial(args, cfg, g, structs, x, B)
         return
     if args.host_resident:
         del out

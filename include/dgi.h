@@ -237,17 +237,21 @@ dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layers, int32_t 
 
 /* Partial inference (Sections 2 and 3.3): output embeddings of `num_targets` target nodes only.
  *   targets : DEVICE, int32 node ids (duplicates allowed);  out: DEVICE [num_targets x out_dim], row i = target i.
- * The per-layer target sets V^L = targets, V^{l-1} = V^l + in-neighbours(V^l) are marked on the device; when
- * |V^l| * average degree >= num_nodes the annotation stops and all nodes are used from that layer down (the
- * paper's shortcut), which here means: run dgi_infer on the whole graph and pick the target rows.  Otherwise
- * V^1 with its complete in-neighbour lists and the inputs V^0 are extracted into a relabelled sub-problem on
- * which the ordinary layer-wise schedule runs (degrees in the GCN normaliser remain those of the full graph).
+ * The per-layer target sets V^L = targets, V^{l-1} = V^l + in-neighbours(V^l) are marked on the device, and layer l
+ * computes the rows of V^l only.  When |V^l| * average degree >= num_nodes the sets below V^l are taken to be all
+ * nodes (the paper's shortcut): layers 1 .. l-1 run on the whole graph with dgi_infer, and only the inputs of layer l
+ * are marked exactly.  The remaining layers run on a relabelled sub-problem (the rows of the first of them with their
+ * complete in-neighbour lists, its inputs, nodes numbered by descending depth so that every V^l is a range of ids)
+ * with the ordinary layer-wise schedule; degrees in the GCN normaliser remain those of the full graph.  When the
+ * sub-problem would hold half of the graph's nodes or more, all layers run on the whole graph instead.
  * opts->perm_new_of_old must be NULL.  Waits for completion.  pstats (HOST, may be NULL) reports the set sizes. */
 typedef struct {
     int32_t num_layers;
-    int32_t all_nodes_from_layer;            /* l: layers <= l ran on all nodes (shortcut); -1: never triggered */
+    int32_t all_nodes_from_layer;            /* l >= 1: layers 1 .. l ran on all nodes (shortcut; l = num_layers when the marked
+                                                input set was half of the graph or more and nothing was extracted); -1: none */
     int64_t set_size[DGI_MAX_LAYERS + 1];    /* |V^l| for the annotated layers, index l in [0, num_layers] */
-    int64_t sub_nodes, sub_edges;            /* size of the problem that was actually run */
+    int64_t sub_nodes, sub_edges;            /* size of the sub-problem that was extracted */
+    int64_t rows_computed[DGI_MAX_LAYERS];   /* destination rows layer l (0-based) computed: |V^{l+1}|, or N under the shortcut */
 } dgi_partial_stats_t;
 dgi_status_t dgi_infer_partial(const dgi_graph_t* g, const dgi_layer_t* layers, int32_t num_layers, const void* x,
                                int64_t ld_x, const int32_t* targets, int64_t num_targets, void* out, int64_t ld_out,

@@ -67,6 +67,7 @@ class PartialStatsStruct(ctypes.Structure):
     _fields_ = [
         ("num_layers", ctypes.c_int32), ("all_nodes_from_layer", ctypes.c_int32),
         ("set_size", ctypes.c_int64 * (MAX_LAYERS + 1)), ("sub_nodes", ctypes.c_int64), ("sub_edges", ctypes.c_int64),
+        ("rows_computed", ctypes.c_int64 * MAX_LAYERS),
     ]
 
 
@@ -316,7 +317,7 @@ def infer_partial(graph, layer_structs, x, targets, out, batch_size=0, mem_budge
                                   ctypes.byref(opts), ctypes.byref(ps), _stream()))
     n = ps.num_layers
     return {"set_size": list(ps.set_size)[:n + 1], "all_nodes_from_layer": ps.all_nodes_from_layer,
-            "sub_nodes": ps.sub_nodes, "sub_edges": ps.sub_edges}
+            "sub_nodes": ps.sub_nodes, "sub_edges": ps.sub_edges, "rows_computed": list(ps.rows_computed)[:n]}
 
 
 def graph_sample(graph, fanout, seed, layer):

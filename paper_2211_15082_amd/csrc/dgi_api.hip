@@ -531,6 +531,14 @@ extern "C" dgi_status_t dgi_layer_forward_static(const dgi_graph_t* g, const dgi
 
 extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layers, int32_t num_layers, const void* x,
                                   int64_t ld_x, void* out, int64_t ld_out, const dgi_infer_opts_t* opts, void* hip_stream) {
+    return infer_rows(g, layers, num_layers, x, ld_x, out, ld_out, opts, nullptr, hip_stream);
+}
+
+// dgi_infer with an optional per-layer row limit: layer l computes destination rows [0, row_limit[l]) only and reads
+// source rows [0, row_limit[l-1]) (all N rows of x for l = 0).  Partial inference numbers its sub-problem so that the
+// per-layer target sets of Section 3.3 are such prefixes.  Rows beyond a limit are neither read nor written.
+dgi_status_t dgi::infer_rows(const dgi_graph* g, const dgi_layer_t* layers, int32_t num_layers, const void* x, int64_t ld_x, void* out,
+                             int64_t ld_out, const dgi_infer_opts_t* opts, const int64_t* row_limit, void* hip_stream) {
     DGI_REQUIRE(g != nullptr && layers != nullptr, DGI_ERR_INVALID_ARG, "infer: NULL argument");
     DGI_REQUIRE(num_layers >= 1 && num_layers <= DGI_MAX_LAYERS, DGI_ERR_INVALID_ARG, "infer: 1..%d layers supported", DGI_MAX_LAYERS);
     dgi_infer_opts_t o{};
@@ -614,7 +622,7 @@ extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layer
         uint64_t fixed = P.wt_bytes;
         if (P.transform_first) fixed += (uint64_t)round_up(N * P.z_ld * elem_bytes(P.z_dtype), 256);
         fixed_max = std::max(fixed_max, fixed);
-        temp_full_max = std::max(temp_full_max, batch_temp_bytes(g, &layers[l], P, 0, N));
+        temp_full_max = std::max(temp_full_max, batch_temp_bytes(g, &layers[l], P, 0, row_limit ? std::min(N, row_limit[l]) : N));
     }
     const uint64_t persistent = hidden_bytes * n_hidden + xp_bytes + yp_bytes + fixed_max;
     DGI_REQUIRE(budget > persistent + 4096, DGI_ERR_OOM,
@@ -675,7 +683,7 @@ extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layer
         DGI_TRY(prepare_weights(&L, P, Wt, s));
         if (P.transform_first) {
             if (tm) DGI_TRY(tm->begin(SPAN_GEMM));
-            DGI_TRY(run_transform(&L, P, cur, ld_cur, Wt, Z, 0, N, s));
+            DGI_TRY(run_transform(&L, P, cur, ld_cur, Wt, Z, 0, (row_limit && l > 0) ? std::min(N, row_limit[l - 1]) : N, s));
             if (tm) DGI_TRY(tm->end());
         }
         // ---- batches of destination rows (Section 4.1) ----------------------------------------------
@@ -683,6 +691,8 @@ extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layer
         int64_t n_i = o.batch_size > 0 ? INT64_MAX / 4
                                        : (o.init_edge_threshold > 0 ? o.init_edge_threshold : (int64_t)std::max(1.0, (double)n_t * std::max(avg_deg, 1.0)));
         int64_t b = 0, batches = 0;
+        const int64_t N_full = g->N;
+        const int64_t N = row_limit ? std::min(N_full, row_limit[l]) : N_full;   // rows this layer computes
         while (b < N) {
             int64_t e = 0;
             DGI_TRY(dgi_plan_batch_end(g->h_indptr.data(), DGI_I64, N, b, std::min(std::max<int64_t>(n_t, 1), kMaxRowsPerLaunch * 4),
@@ -727,7 +737,7 @@ extern "C" dgi_status_t dgi_infer(const dgi_graph_t* g, const dgi_layer_t* layer
         if (tm) { DGI_HIP(hipEventRecord(tm->spans[layer_span].b, s)); }
         if (o.stats) {
             o.stats->batches[l] = batches;
-            o.stats->edges[l] = g->E;
+            o.stats->edges[l] = g->h_indptr[(size_t)N] - g->h_indptr[0];
             o.stats->transform_first[l] = P.transform_first ? 1 : 0;
             o.stats->fused[l] = P.fused ? 1 : 0;
             o.stats->gather_width[l] = P.gat ? (int)P.z_ld : (P.transform_first ? L.out_dim : L.in_dim);

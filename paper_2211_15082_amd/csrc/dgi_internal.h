@@ -255,6 +255,10 @@ dgi_status_t layer_aggregate_rows_split(const dgi_graph* g, const dgi_layer_t* l
 dgi_status_t layer_aggregate_rows(const dgi_graph* g, const dgi_layer_t* layer, const void* Z, void* h_out, int64_t ld_out, int64_t out_base,
                                   int64_t b, int64_t e, void* temp, uint64_t temp_bytes, hipStream_t s);
 
+// dgi_infer with an optional per-layer limit on the rows computed (row_limit[l] rows of layer l, NULL = all)
+dgi_status_t infer_rows(const dgi_graph* g, const dgi_layer_t* layers, int32_t num_layers, const void* x, int64_t ld_x, void* out,
+                        int64_t ld_out, const dgi_infer_opts_t* opts, const int64_t* row_limit, void* hip_stream);
+
 // frees dgi_infer's cached arena (takes ws_mutex; dgi_infer_host calls it while holding hs_mutex)
 dgi_status_t release_infer_arena(const dgi_graph* g);
 

@@ -48,12 +48,13 @@ static __global__ void level_flags_kernel(const int32_t* depth, int64_t N, int32
         flag[i] = depth[i] >= l ? 1 : 0;
 }
 
-// per kept node (local id i, global id U[i]): its in-degree if the row keeps its list (depth >= 1), else 0
+// per kept node (local id i, global id U[i]): its in-degree if the row keeps its list (depth >= keep_depth), else 0
 template <typename IdxT>
-static __global__ void sub_rows_kernel(const int32_t* U, int64_t n_sub, const IdxT* indptr, const int32_t* depth, int64_t* sub_deg) {
+static __global__ void sub_rows_kernel(const int32_t* U, int64_t n_sub, const IdxT* indptr, const int32_t* depth, int32_t keep_depth,
+                                       int64_t* sub_deg) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_sub; i += (int64_t)gridDim.x * blockDim.x) {
         const int64_t v = U[i];
-        sub_deg[i] = depth[v] >= 1 ? (int64_t)(indptr[v + 1] - indptr[v]) : 0;
+        sub_deg[i] = depth[v] >= keep_depth ? (int64_t)(indptr[v + 1] - indptr[v]) : 0;
     }
 }
 
@@ -112,7 +113,7 @@ dgi_status_t sub_rows(const dgi_graph* g, const int32_t* depth, Scratch& sc, int
     const int64_t N = g->N;
     DGI_CUB(hipcub::DeviceScan::ExclusiveSum(sc.tmp.p, sc.tb, sc.flag.as<int32_t>(), sc.loc.as<int32_t>(), (int)N, s));
     DGI_CUB(hipcub::DeviceSelect::Flagged(sc.tmp.p, sc.tb, hipcub::CountingInputIterator<int32_t>(0), sc.flag.as<int32_t>(), U, sc.cnt.as<int32_t>(), (int)N, s));
-    hipLaunchKernelGGL(sub_rows_kernel<IdxT>, dim3(grid_for(n_sub)), dim3(kBlock), 0, s, U, n_sub, (const IdxT*)g->d_indptr, depth, sub_deg);
+    hipLaunchKernelGGL(sub_rows_kernel<IdxT>, dim3(grid_for(n_sub)), dim3(kBlock), 0, s, U, n_sub, (const IdxT*)g->d_indptr, depth, 1, sub_deg);
     DGI_TRY(launch_fill_zero(sub_indptr, 8, s));
     DGI_CUB(hipcub::DeviceScan::InclusiveSum(sc.tmp.p, sc.tb, sub_deg, sub_indptr + 1, (int)n_sub, s));
     DGI_HIP(hipMemcpyAsync(e_sub, sub_indptr + n_sub, 8, hipMemcpyDeviceToHost, s));

@@ -404,14 +404,62 @@ def test_partial_inference_matches_the_oracle_rows(kind):
         assert max_rel_err(out.cpu().numpy(), want[t]) <= TOL_F32, (kind, count)
         L = len(layers)
         assert st["set_size"][L] == np.unique(t).size
+        sizes = st["set_size"]
         if count <= 17:
             assert st["all_nodes_from_layer"] == -1 and st["sub_nodes"] < n     # a small sub-problem was extracted
-            sizes = st["set_size"]
             assert all(sizes[l - 1] >= sizes[l] for l in range(1, L + 1))
+            # Section 3.3: layer l computes the rows of V^l only, and far fewer at the top than at the bottom
+            assert st["rows_computed"] == sizes[1:] and st["sub_nodes"] == sizes[0]
+            assert st["rows_computed"][-1] == np.unique(t).size < st["rows_computed"][0]
+        if count == 400:
+            # |V^L| d_avg < n <= |V^{L-1}| d_avg for the 3-layer model, |V^L| d_avg < n only just for the others
+            nb = np.unique(np.concatenate([indices[indptr[v]:indptr[v + 1]] for v in np.unique(t)] + [np.unique(t)]))
+            assert sizes[L - 1] == nb.size
+            if st["all_nodes_from_layer"] == L - 2 and L == 3:   # layer 1 on all nodes, layers 2-3 on V^2 and V^3
+                assert st["rows_computed"] == [n, sizes[2], sizes[3]] and st["sub_nodes"] == sizes[1]
         if count == 5000:
-            assert st["all_nodes_from_layer"] == L - 1 and st["sub_nodes"] == n  # |V^L| d_avg >= n: shortcut
+            # |V^L| d_avg >= n: the shortcut, and the marked inputs V^{L-1} = targets + their in-neighbours are more
+            # than half of the graph: nothing is extracted, every layer runs on all nodes
+            nb = np.unique(np.concatenate([indices[indptr[v]:indptr[v + 1]] for v in np.unique(t)] + [np.unique(t)]))
+            assert sizes[L - 1] == nb.size >= n // 2
+            assert st["all_nodes_from_layer"] == L and st["rows_computed"] == [n] * L and st["sub_nodes"] == n
     with pytest.raises(bd.DgiError):
         bd.infer_partial(g, list(structs), x, torch.tensor([n], dtype=torch.int32, device="cuda"), out)
+
+
+def test_partial_inference_shortcut_in_the_middle_of_a_deep_model():
+    # 4 GraphSAGE layers.  Graph A (average degree 8, one 3000-edge hub): the sets of 60 low-degree targets grow until
+    # |V^l| d >= n somewhere in the middle; whatever layer that is, the layers below it run on all nodes.  Graph B: every
+    # node draws its 8 in-neighbours from the same 64 nodes, so 1000 targets trip the shortcut at once (|V^4| d >= n) while
+    # their inputs V^3 = targets + those 64 nodes stay small: layers 1-3 on all nodes, layer 4 on a 1064-node sub-problem.
+    bd = B()
+    n = 4000
+    dims = [24, 32, 32, 24, 8]
+    layers = [dict(agg="mean", act="relu" if l < 3 else "none", W_self=rnd((dims[l], dims[l + 1]), 2 + l, 0.2),
+                   W_neigh=rnd((dims[l], dims[l + 1]), 12 + l, 0.2), bias=rnd((dims[l + 1],), 22 + l)) for l in range(4)]
+    X = rnd((n, 24), 1)
+    x = torch.from_numpy(X).cuda()
+    rng = np.random.default_rng(5)
+    ipA, ixA = random_csr(n, 8.0, seed=92, empty_frac=0.0, hub=(7, 3000))
+    ipB = np.arange(0, 8 * n + 1, 8, dtype=np.int64)
+    ixB = rng.integers(0, 64, 8 * n).astype(np.int32)
+    lowA = np.nonzero(np.diff(ipA) <= 9)[0][:60].astype(np.int32)
+    tB = rng.choice(np.arange(64, n), 1000, replace=False).astype(np.int32)
+    for indptr, indices, t, expect in ((ipA, ixA, lowA, None), (ipA, ixA, np.array([7, 11, 12], dtype=np.int32), 4), (ipB, ixB, tB, 3)):
+        want = oracle.infer(indptr, indices, layers, X)
+        g = bd.graph_load(indptr, indices)
+        structs, keep = zip(*[bd.make_layer(L) for L in layers])
+        out = torch.full((t.size, 8), 777.0, dtype=torch.float32, device="cuda")
+        st = bd.infer_partial(g, list(structs), x, torch.from_numpy(t).cuda(), out)
+        assert max_rel_err(out.cpu().numpy(), want[t]) <= TOL_F32
+        l0 = st["all_nodes_from_layer"]
+        assert 1 <= l0 <= 4 and (expect is None or l0 == expect), st
+        assert st["rows_computed"][:l0] == [n] * l0
+        if l0 < 4:
+            assert st["rows_computed"][-1] == t.size and st["sub_nodes"] < n // 2
+            assert all(a >= b for a, b in zip(st["rows_computed"][l0:], st["rows_computed"][l0 + 1:]))
+        if expect == 3:
+            assert st["sub_nodes"] == 1000 + np.unique(ixB[(tB[:, None] * 8 + np.arange(8)).ravel()]).size
 
 
 @pytest.mark.parametrize("last", ["gcn", "mean"])
