@@ -258,6 +258,26 @@ def partial(args, cfg, g, structs, x, B):
                       "full_inference_ms": round(full_ms, 3), "runs": runs}))
 
 
+def hot_sources(cfg):
+    """How much of a gather the popular source rows account for: the share of all edges whose source is among the K
+    nodes of largest out-degree, for K rows that fit a workgroup's LDS, one XCD's L2 and the memory-side cache."""
+    import torch
+    n, e = cfg["num_nodes"], int(cfg["indices"].numel())
+    out_deg = torch.zeros(n, dtype=torch.int64, device=cfg["indices"].device)
+    step = 1 << 28
+    for a in range(0, e, step):   # bincount in pieces: a 1.6 G-edge index array would need 13 GB as int64
+        out_deg += torch.bincount(cfg["indices"][a:a + step].long(), minlength=n)
+    top = torch.sort(out_deg, descending=True).values
+    cum = torch.cumsum(top, 0)
+    row_bytes = int(cfg["x"].shape[1]) * cfg["x"].element_size()
+    res = {"workload": cfg["name"], "num_nodes": n, "num_edges": e, "input_row_bytes": row_bytes, "max_out_degree": int(top[0]), "top_sources": []}
+    for what, cap in (("64 KB of LDS", 64 << 10), ("4 MB L2 of one XCD", 4 << 20), ("256 MB memory-side cache", 256 << 20)):
+        for rb in sorted({row_bytes, 256, 1024}):
+            k = max(1, min(n, cap // rb))
+            res["top_sources"].append({"fits": what, "row_bytes": rb, "rows": k, "edge_share": round(float(cum[k - 1]) / e, 5)})
+    print(json.dumps(res))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -274,6 +294,8 @@ def main():
     ap.add_argument("--ablation", action="store_true", help="reordering x batch-size ablation instead of the timed run")
     ap.add_argument("--partial", default="", metavar="COUNTS",
                     help="partial inference of random target sets of these sizes, e.g. 100,1000,10000,100000,1000000 (prints its own JSON line)")
+    ap.add_argument("--hot-sources", action="store_true",
+                    help="print the share of edges whose source is among the top-K out-degree nodes, K sized to LDS / L2 / the memory-side cache")
     ap.add_argument("--fanout", type=int, default=0, help="sampling inference with this fan-out per layer (prints its own JSON line)")
     ap.add_argument("--host-resident", action="store_true",
                     help="embeddings in pinned host memory, batches streamed in (dgi_infer_host); prints its own JSON line")
@@ -302,6 +324,9 @@ def main():
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
     torch.cuda.empty_cache()  # hand the generator's scratch back so the library sees the free memory
+    if args.hot_sources:
+        hot_sources(cfg)
+        return
     n = cfg["num_nodes"]
     e = int(cfg["indices"].numel())
     g = B.graph_load(cfg["indptr"], cfg["indices"])
