@@ -406,26 +406,28 @@ def main():
             if k == args.config:
                 continue
             result["other_configs"]["cfg%d" % k] = other_config(B, configs, k, dev)
+        if args.config != 5:  # the block-model graph once more, renumbered by the library (Section 4.2)
+            result["other_configs"]["cfg5_reordered"] = other_config(B, configs, 5, dev, reorder="community")
     print(json.dumps(result))
 
 
-def timed_steps(B, g, structs, x, out, warmup, steps, batch_size):
+def timed_steps(B, g, structs, x, out, warmup, steps, batch_size, perm=None):
     """(first call in ms: it allocates the library's arena; seconds per step over `steps` timed calls; their stats)."""
     import torch
     first_call_ms = None
     if warmup >= 1:  # the first of the untimed warm-up calls, timed on its own
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        B.infer(g, structs, x, out, batch_size=batch_size)
+        B.infer(g, structs, x, out, batch_size=batch_size, perm_new_of_old=perm)
         torch.cuda.synchronize()
         first_call_ms = (time.perf_counter() - t0) * 1e3
     for _ in range(max(warmup - 1, 0)):
-        B.infer(g, structs, x, out, batch_size=batch_size)
+        B.infer(g, structs, x, out, batch_size=batch_size, perm_new_of_old=perm)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     stats = []
     for _ in range(steps):
-        stats.append(B.infer(g, structs, x, out, batch_size=batch_size, want_stats=True))
+        stats.append(B.infer(g, structs, x, out, batch_size=batch_size, want_stats=True, perm_new_of_old=perm))
     torch.cuda.synchronize()
     return first_call_ms, (time.perf_counter() - t0) / steps, stats
 
@@ -443,7 +445,9 @@ def roofline(cfg, info, stats, steps, storage):
     n_layers = len(cfg["layers"])
     agg_ms = [sum(s["agg_ms"][l] for s in stats) for l in range(n_layers)]
     agg_launches = [sum(s["agg_launches"][l] for s in stats) for l in range(n_layers)]
-    dom = max(range(n_layers), key=lambda l: agg_ms[l])
+    # (layers that run the same kernel on the same graph differ by noise only: the last of those within 3 % of the
+    # slowest is taken, so that the choice, and the offline traffic figure looked up for it, do not flip between runs)
+    dom = max(l for l in range(n_layers) if agg_ms[l] >= 0.97 * max(agg_ms))
     width = stats[0]["gather_width"][dom]
     L = cfg["layers"][dom]
     is_gat = L["agg"] == "gat"
@@ -474,20 +478,31 @@ def roofline(cfg, info, stats, steps, storage):
                     "offline with rocprofv3 --pmc, see profiles/), which that cache can serve as well."}
 
 
-def other_config(B, configs, k, dev, steps=5, warmup=2):
+def other_config(B, configs, k, dev, steps=5, warmup=2, reorder=None):
     import torch
     cfg = configs.make_config(k, device=dev)
     torch.cuda.empty_cache()
     g = B.graph_load(cfg["indptr"], cfg["indices"])
+    perm, reorder_s = None, 0.0
+    if reorder:
+        t0 = time.perf_counter()
+        g2, perm = B.graph_reorder(g, reorder)
+        torch.cuda.synchronize()
+        reorder_s = time.perf_counter() - t0
+        g.free()
+        g = g2
     info = g.info()
     structs, keep = zip(*[B.make_layer(L, device=dev) for L in cfg["layers"]])
     structs = list(structs)
     x = cfg["x"].contiguous()
     out = torch.empty(cfg["num_nodes"], structs[-1].out_dim, dtype=torch.float32, device=dev)
-    first_ms, sec, stats = timed_steps(B, g, structs, x, out, warmup, steps, 0)
+    first_ms, sec, stats = timed_steps(B, g, structs, x, out, warmup, steps, 0, perm)
     e = int(cfg["indices"].numel())
     r = roofline(cfg, info, stats, steps, "f32")
-    res = {"workload": cfg["name"], "num_nodes": cfg["num_nodes"], "num_edges": e, "steps": steps, "warmup": warmup,
+    if reorder:
+        r["traffic"] = None   # the offline counter figure belongs to the graph as generated
+    res = {"workload": cfg["name"] + (" [ids renumbered by dgi_graph_reorder(%s), %.2f s once per graph; x and the output stay in the caller's order]" % (reorder, reorder_s) if reorder else ""),
+           "num_nodes": cfg["num_nodes"], "num_edges": e, "steps": steps, "warmup": warmup,
            "ms_per_step": sec * 1e3, "first_call_ms": first_ms, "edges_per_s": len(structs) * e / sec,
            "per_layer_ms": per_layer_ms(stats, steps),
            "dominant_kernel": {k2: r[k2] for k2 in ("kernel", "achieved", "frac", "avg_launch_ms", "traffic")}}
