@@ -6,8 +6,11 @@
 // A1|A2 is the row-wise concatenation [h_v | m_v] of GraphSAGE (A2 may be absent); A3, when present, is the
 // low-order part of an m_v that is stored as a pair of bf16 values (it multiplies the same weight block); Wt is the weight
 // packed transposed, [Nout x ldw] with K contiguous, so both MFMA operands are read from LDS rows of
-// the same shape.  fp32 data uses v_mfma_f32_32x32x2_f32, bf16 data v_mfma_f32_32x32x16_bf16, both with
-// fp32 accumulators.  A workgroup of 4 wavefronts owns a BM x BN output tile; each k-step stages a
+// the same shape.  bf16 data uses v_mfma_f32_32x32x16_bf16 with fp32 accumulators.  fp32 data runs on the same
+// instruction (gemm_split_kernel below): both operands are split exactly into three bf16 terms, x = x1 + x2 + x3,
+// and the six products of combined order up to 2^-16 are accumulated in fp32 (what is dropped is of relative size
+// 2^-24, an fp32 rounding) -- 6 bf16 MFMAs instead of 8 fp32 ones per 16 elements of K, each at a quarter of the time.
+// A workgroup of 4 wavefronts owns a BM x BN output tile; each k-step stages a
 // 128-byte slab of every tile row in LDS (global -> registers -> LDS, the next slab's global loads are
 // in flight while the current one is multiplied).  LDS rows are padded by 16 bytes so that the 16-byte
 // fragment reads of 8 consecutive lanes cover all banks.
@@ -21,6 +24,17 @@ namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+// Build-time switch for measurements: 1 runs fp32 GEMMs on v_mfma_f32_32x32x2_f32 instead of the three-term bf16 split.
+#ifndef DGI_GEMM_F32_MFMA
+#define DGI_GEMM_F32_MFMA 0
+#endif
+constexpr bool kF32OnF32Mfma = DGI_GEMM_F32_MFMA != 0;
+// ... and 1 here keeps bf16 GEMMs on the tiled kernel where the weights-stationary one would run.
+#ifndef DGI_GEMM_BF16_TILED
+#define DGI_GEMM_BF16_TILED 0
+#endif
+constexpr bool kTiledBf16 = DGI_GEMM_BF16_TILED != 0;
 
 struct GemmParams {
     const void* A1; int64_t ld_a1; int K1; int a1_vec;
@@ -49,129 +63,23 @@ __device__ __forceinline__ uint4 load_chunk(const T* base, int64_t ld, int64_t r
     return *reinterpret_cast<uint4*>(tmp);
 }
 
-// The register budget is pinned to the occupancy the accumulators allow (16 registers per 32x32 block):
-// the kernel hides memory latency with resident workgroups, and measured slower whenever one was lost.
-template <typename T, int WGM, int WGN, int TM, int TN>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(TM * TN >= 6 ? 2 : TM * TN >= 4 ? 3 : 4)))
-void gemm_kernel(GemmParams p) {
-    constexpr int E = 16 / sizeof(T);      // elements per 16-byte chunk
-    constexpr int BK = 8 * E;              // 128 bytes of K per step
-    constexpr int LDS_LD = BK + E;         // padded row, in elements
-    constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
-    constexpr int A_CHUNKS = BM * 8 / 256, B_CHUNKS = BN * 8 / 256;
-    static_assert(WGM * WGN == 4, "4 wavefronts per workgroup");
-    // the epilogue stages each wavefront's 32-row strip (TN*32 columns, up to 4 bytes each, rows padded by
-    // 16 bytes) in the same memory once the last slab has been multiplied
-    constexpr int MAIN_BYTES = (BM + BN) * LDS_LD * (int)sizeof(T);
-    constexpr int EPI_BYTES = 4 * 32 * (TN * 32 * 4 + 16);
-    __shared__ __attribute__((aligned(16))) unsigned char smem[MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES];
-    T* As = reinterpret_cast<T*>(smem);
-    T* Bs = As + BM * LDS_LD;
+// Workgroups are handed to the 8 XCDs round-robin by their index, and each XCD has its own L2.  The logical tile of
+// a workgroup is chosen so that one XCD walks a contiguous run of tiles: the column tiles of one row tile, which read
+// the same rows of A, then meet in one L2.
+__device__ __forceinline__ int64_t xcd_contiguous_tile() {
+    const int64_t b = blockIdx.x, G = gridDim.x;
+    const int64_t x = b % 8, j = b / 8, q = G / 8, r = G % 8;
+    return x * q + (x < r ? x : r) + j;
+}
 
+// Epilogue shared by the two GEMM kernels: bias, activation, per-row factor, conversion, and the store of the
+// workgroup's output tile (through LDS as whole 16-byte row pieces when the output layout allows it).  `smem` is the
+// kernel's LDS, free for reuse once the last slab has been multiplied (the caller has synchronised).
+template <int WGM, int WGN, int TM, int TN>
+__device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[TM][TN], const GemmParams& p, unsigned char* smem, int64_t m0, int n0) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
-    const int64_t tile_m = blockIdx.x / p.tiles_n;
-    const int tile_n = blockIdx.x % p.tiles_n;
-    const int64_t m0 = tile_m * BM;
-    const int n0 = tile_n * BN;
-
-    floatx16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    const int S1 = (p.K1 + BK - 1) / BK;
-    const int S2 = p.A2 ? (p.K2 + BK - 1) / BK : 0;
-    const int S = S1 + S2 + (p.A3 ? S2 : 0);
-    uint4 ra[A_CHUNKS], rb[B_CHUNKS];
-
-    auto load_step = [&](int s) {
-        const bool second = s >= S1;
-        const bool third = s >= S1 + S2;
-        const T* A = static_cast<const T*>(third ? p.A3 : second ? p.A2 : p.A1);
-        const int64_t lda = second ? p.ld_a2 : p.ld_a1;
-        const int K = second ? p.K2 : p.K1;
-        const bool vec = second ? p.a2_vec : p.a1_vec;
-        const int k0 = (third ? s - S1 - S2 : second ? s - S1 : s) * BK;
-        const int wcol = second ? p.K1p : 0;
-#pragma unroll
-        for (int i = 0; i < A_CHUNKS; ++i) {
-            const int c = tid + 256 * i;
-            ra[i] = load_chunk<T>(A, lda, m0 + c / 8, p.M, k0 + (c % 8) * E, K, vec);
-        }
-        const T* W = static_cast<const T*>(p.Wt) + wcol;
-#pragma unroll
-        for (int i = 0; i < B_CHUNKS; ++i) {
-            const int c = tid + 256 * i;
-            const int n = n0 + c / 8, k = k0 + (c % 8) * E;
-            // the packed weight is zero-padded to a multiple of E after each block, so a chunk that starts
-            // below K may be read whole
-            rb[i] = (n < p.Nout && k < K) ? *reinterpret_cast<const uint4*>(W + (int64_t)n * p.ldw + k) : make_uint4(0u, 0u, 0u, 0u);
-        }
-    };
-    auto store_step = [&]() {
-#pragma unroll
-        for (int i = 0; i < A_CHUNKS; ++i) {
-            const int c = tid + 256 * i;
-            *reinterpret_cast<uint4*>(&As[(c / 8) * LDS_LD + (c % 8) * E]) = ra[i];
-        }
-#pragma unroll
-        for (int i = 0; i < B_CHUNKS; ++i) {
-            const int c = tid + 256 * i;
-            *reinterpret_cast<uint4*>(&Bs[(c / 8) * LDS_LD + (c % 8) * E]) = rb[i];
-        }
-    };
-
-    if (S > 0) {
-        load_step(0);
-        store_step();
-    }
-    __syncthreads();
     const int lrow = lane & 31, lhalf = lane >> 5;
-    for (int s = 0; s < S; ++s) {
-        if (s + 1 < S) load_step(s + 1);
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {  // BK = 4 sub-steps of 2E elements
-            uint4 fa[TM], fb[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-                fa[i] = *reinterpret_cast<const uint4*>(&As[((wm * TM + i) * 32 + lrow) * LDS_LD + kk * 2 * E + lhalf * E]);
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                fb[j] = *reinterpret_cast<const uint4*>(&Bs[((wn * TN + j) * 32 + lrow) * LDS_LD + kk * 2 * E + lhalf * E]);
-            if constexpr (sizeof(T) == 4) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-#pragma unroll
-                        for (int j = 0; j < TN; ++j) {
-                            const float a = __uint_as_float(e == 0 ? fa[i].x : e == 1 ? fa[i].y : e == 2 ? fa[i].z : fa[i].w);
-                            const float b = __uint_as_float(e == 0 ? fb[j].x : e == 1 ? fb[j].y : e == 2 ? fb[j].z : fb[j].w);
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[i][j], 0, 0, 0);
-                        }
-            } else {
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) {
-                        bf16x8 a, b;
-                        __builtin_memcpy(&a, &fa[i], 16);
-                        __builtin_memcpy(&b, &fb[j], 16);
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i][j], 0, 0, 0);
-                    }
-            }
-        }
-        __syncthreads();
-        if (s + 1 < S) {
-            store_step();
-            __syncthreads();
-        }
-    }
-
     // epilogue: lane holds column (lane % 32) of rows 8*(r/4) + 4*(lane/32) + r%4 of each 32x32 block
     auto value = [&](int i, int j, int r, int64_t m, float b) {
         float v = activate(acc[i][j][r] + b, p.act, p.act_slope);
@@ -243,6 +151,462 @@ void gemm_kernel(GemmParams p) {
                 else static_cast<float*>(p.Y)[m * p.ld_y + n] = v;
             }
         }
+}
+
+// The register budget is pinned to the occupancy the accumulators allow (16 registers per 32x32 block):
+// the kernel hides memory latency with resident workgroups, and measured slower whenever one was lost.
+template <typename T, int WGM, int WGN, int TM, int TN>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(TM * TN >= 6 ? 2 : TM * TN >= 4 ? 3 : 4)))
+void gemm_kernel(GemmParams p) {
+    constexpr int E = 16 / sizeof(T);      // elements per 16-byte chunk
+    constexpr int BK = 8 * E;              // 128 bytes of K per step
+    constexpr int LDS_LD = BK + E;         // padded row, in elements
+    constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
+    constexpr int A_CHUNKS = BM * 8 / 256, B_CHUNKS = BN * 8 / 256;
+    static_assert(WGM * WGN == 4, "4 wavefronts per workgroup");
+    // the epilogue stages each wavefront's 32-row strip (TN*32 columns, up to 4 bytes each, rows padded by
+    // 16 bytes) in the same memory once the last slab has been multiplied
+    constexpr int MAIN_BYTES = (BM + BN) * LDS_LD * (int)sizeof(T);
+    constexpr int EPI_BYTES = 4 * 32 * (TN * 32 * 4 + 16);
+    __shared__ __attribute__((aligned(16))) unsigned char smem[MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES];
+    T* As = reinterpret_cast<T*>(smem);
+    T* Bs = As + BM * LDS_LD;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int64_t tile = xcd_contiguous_tile();
+    const int64_t tile_m = tile / p.tiles_n;
+    const int tile_n = (int)(tile % p.tiles_n);
+    const int64_t m0 = tile_m * BM;
+    const int n0 = tile_n * BN;
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int S1 = (p.K1 + BK - 1) / BK;
+    const int S2 = p.A2 ? (p.K2 + BK - 1) / BK : 0;
+    const int S = S1 + S2 + (p.A3 ? S2 : 0);
+    // the next slab's global loads are in flight while the current one is multiplied
+    uint4 ra[A_CHUNKS], rb[B_CHUNKS];
+
+    auto block_of = [&](int s, const T*& A, int64_t& lda, int& K, bool& vec, int& k0, int& wcol) {
+        const bool second = s >= S1;
+        const bool third = s >= S1 + S2;
+        A = static_cast<const T*>(third ? p.A3 : second ? p.A2 : p.A1);
+        lda = second ? p.ld_a2 : p.ld_a1;
+        K = second ? p.K2 : p.K1;
+        vec = second ? p.a2_vec : p.a1_vec;
+        k0 = (third ? s - S1 - S2 : second ? s - S1 : s) * BK;
+        wcol = second ? p.K1p : 0;
+    };
+    auto load_a = [&](int s) {
+        const T* A; int64_t lda; int K, k0, wcol; bool vec;
+        block_of(s, A, lda, K, vec, k0, wcol);
+#pragma unroll
+        for (int i = 0; i < A_CHUNKS; ++i) {
+            const int c = tid + 256 * i;
+            ra[i] = load_chunk<T>(A, lda, m0 + c / 8, p.M, k0 + (c % 8) * E, K, vec);
+        }
+    };
+    auto load_b = [&](int s) {
+        const T* A; int64_t lda; int K, k0, wcol; bool vec;
+        block_of(s, A, lda, K, vec, k0, wcol);
+        const T* W = static_cast<const T*>(p.Wt) + wcol;
+#pragma unroll
+        for (int i = 0; i < B_CHUNKS; ++i) {
+            const int c = tid + 256 * i;
+            const int n = n0 + c / 8, k = k0 + (c % 8) * E;
+            // the packed weight is zero-padded to a multiple of E after each block, so a chunk that starts
+            // below K may be read whole
+            rb[i] = (n < p.Nout && k < K) ? *reinterpret_cast<const uint4*>(W + (int64_t)n * p.ldw + k) : make_uint4(0u, 0u, 0u, 0u);
+        }
+    };
+    auto store_step = [&]() {
+#pragma unroll
+        for (int i = 0; i < A_CHUNKS; ++i) {
+            const int c = tid + 256 * i;
+            *reinterpret_cast<uint4*>(&As[(c / 8) * LDS_LD + (c % 8) * E]) = ra[i];
+        }
+#pragma unroll
+        for (int i = 0; i < B_CHUNKS; ++i) {
+            const int c = tid + 256 * i;
+            *reinterpret_cast<uint4*>(&Bs[(c / 8) * LDS_LD + (c % 8) * E]) = rb[i];
+        }
+    };
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    auto multiply = [&]() {
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {  // BK = 4 sub-steps of 2E elements
+            uint4 fa[TM], fb[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                fa[i] = *reinterpret_cast<const uint4*>(&As[((wm * TM + i) * 32 + lrow) * LDS_LD + kk * 2 * E + lhalf * E]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                fb[j] = *reinterpret_cast<const uint4*>(&Bs[((wn * TN + j) * 32 + lrow) * LDS_LD + kk * 2 * E + lhalf * E]);
+            if constexpr (sizeof(T) == 4) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) {
+                            const float a = __uint_as_float(e == 0 ? fa[i].x : e == 1 ? fa[i].y : e == 2 ? fa[i].z : fa[i].w);
+                            const float b = __uint_as_float(e == 0 ? fb[j].x : e == 1 ? fb[j].y : e == 2 ? fb[j].z : fb[j].w);
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[i][j], 0, 0, 0);
+                        }
+            } else {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        bf16x8 a, b;
+                        __builtin_memcpy(&a, &fa[i], 16);
+                        __builtin_memcpy(&b, &fb[j], 16);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i][j], 0, 0, 0);
+                    }
+            }
+        }
+    };
+
+    if (S > 0) {
+        load_b(0);
+        load_a(0);
+        store_step();
+    }
+    __syncthreads();
+    for (int s = 0; s < S; ++s) {
+        if (s + 1 < S) {
+            load_b(s + 1);
+            load_a(s + 1);
+        }
+        multiply();
+        __syncthreads();
+        if (s + 1 < S) {
+            store_step();
+            __syncthreads();
+        }
+    }
+
+    gemm_epilogue<WGM, WGN, TM, TN>(acc, p, smem, m0, n0);
+}
+
+// x = t[0] + t[1] + t[2] exactly, each term a bf16 value: the value rounded to nearest, then twice the same of what is left
+// (the second remainder has at most 8 significant bits).  Non-finite x gives NaN terms.
+__device__ __forceinline__ void split3(float x, uint16_t (&t)[3]) {
+    t[0] = float_to_bf16(x);
+    const float r1 = x - bf16_to_float(t[0]);
+    t[1] = float_to_bf16(r1);
+    const float r2 = r1 - bf16_to_float(t[1]);
+    t[2] = float_to_bf16(r2);
+}
+
+// The fp32 GEMM on the bf16 matrix instruction.  Operands are fp32 in memory; the staging step splits every element
+// into its three bf16 terms (split3) and writes them as three 64-byte planes of the tile row's LDS slab
+// (32 elements of K per step; 16 bytes of padding make the row 52 words, so 8 lanes' 16-byte reads cover all banks).
+// For every 16 elements of K the products t_a[i] * t_b[j] with i + j <= 2 are accumulated: the terms fall off by
+// 2^-8 each, so what is left out is below 2^-23 of |a||b|, with random sign.
+template <int WGM, int WGN, int TM, int TN>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(TM * TN >= 6 ? 2 : TM * TN >= 4 ? 3 : 4)))
+void gemm_split_kernel(GemmParams p) {
+    constexpr int BK = 32;                 // fp32 elements of K per step: 128 bytes of every tile row
+    constexpr int ROW_B = 3 * 2 * BK + 16; // LDS row: three bf16 planes and the padding, in bytes
+    constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
+    constexpr int A_CHUNKS = BM * 8 / 256, B_CHUNKS = BN * 8 / 256;
+    static_assert(WGM * WGN == 4, "4 wavefronts per workgroup");
+    constexpr int MAIN_BYTES = (BM + BN) * ROW_B;
+    constexpr int EPI_BYTES = 4 * 32 * (TN * 32 * 4 + 16);
+    __shared__ __attribute__((aligned(16))) unsigned char smem[MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES];
+    unsigned char* As = smem;
+    unsigned char* Bs = smem + BM * ROW_B;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int64_t tile = xcd_contiguous_tile();
+    const int64_t tile_m = tile / p.tiles_n;
+    const int tile_n = (int)(tile % p.tiles_n);
+    const int64_t m0 = tile_m * BM;
+    const int n0 = tile_n * BN;
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int S1 = (p.K1 + BK - 1) / BK;
+    const int S2 = p.A2 ? (p.K2 + BK - 1) / BK : 0;
+    const int S = S1 + S2;
+    uint4 ra[A_CHUNKS], rb[B_CHUNKS];
+
+    auto load_a = [&](int s) {
+        const bool second = s >= S1;
+        const float* A = static_cast<const float*>(second ? p.A2 : p.A1);
+        const int64_t lda = second ? p.ld_a2 : p.ld_a1;
+        const int K = second ? p.K2 : p.K1;
+        const bool vec = second ? p.a2_vec : p.a1_vec;
+        const int k0 = (second ? s - S1 : s) * BK;
+#pragma unroll
+        for (int i = 0; i < A_CHUNKS; ++i) {
+            const int c = tid + 256 * i;
+            ra[i] = load_chunk<float>(A, lda, m0 + c / 8, p.M, k0 + (c % 8) * 4, K, vec);
+        }
+    };
+    auto load_b = [&](int s) {
+        const bool second = s >= S1;
+        const int K = second ? p.K2 : p.K1;
+        const int k0 = (second ? s - S1 : s) * BK;
+        const float* W = static_cast<const float*>(p.Wt) + (second ? p.K1p : 0);
+#pragma unroll
+        for (int i = 0; i < B_CHUNKS; ++i) {
+            const int c = tid + 256 * i;
+            const int n = n0 + c / 8, k = k0 + (c % 8) * 4;
+            // the packed weight is zero-padded to a multiple of 4 after each block
+            rb[i] = (n < p.Nout && k < K) ? *reinterpret_cast<const uint4*>(W + (int64_t)n * p.ldw + k) : make_uint4(0u, 0u, 0u, 0u);
+        }
+    };
+    auto store_split = [&](unsigned char* row, int chunk, const uint4& v) {
+        const float x[4] = {__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
+        uint16_t t[4][3];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) split3(x[e], t[e]);
+#pragma unroll
+        for (int q = 0; q < 3; ++q) {
+            uint2 w;
+            w.x = (uint32_t)t[0][q] | ((uint32_t)t[1][q] << 16);
+            w.y = (uint32_t)t[2][q] | ((uint32_t)t[3][q] << 16);
+            *reinterpret_cast<uint2*>(row + q * 2 * BK + chunk * 8) = w;
+        }
+    };
+    auto store_step = [&]() {
+#pragma unroll
+        for (int i = 0; i < A_CHUNKS; ++i) {
+            const int c = tid + 256 * i;
+            store_split(As + (c / 8) * ROW_B, c % 8, ra[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < B_CHUNKS; ++i) {
+            const int c = tid + 256 * i;
+            store_split(Bs + (c / 8) * ROW_B, c % 8, rb[i]);
+        }
+    };
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    auto multiply = [&]() {
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {  // 16 elements of K per MFMA: lane half h holds elements 8h .. 8h+7
+            bf16x8 fa[TM][3], fb[TN][3];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int q = 0; q < 3; ++q)
+                    fa[i][q] = *reinterpret_cast<const bf16x8*>(As + ((wm * TM + i) * 32 + lrow) * ROW_B + q * 2 * BK + ks * 32 + lhalf * 16);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int q = 0; q < 3; ++q)
+                    fb[j][q] = *reinterpret_cast<const bf16x8*>(Bs + ((wn * TN + j) * 32 + lrow) * ROW_B + q * 2 * BK + ks * 32 + lhalf * 16);
+            // smallest products first
+#pragma unroll
+            for (int order = 2; order >= 0; --order)
+#pragma unroll
+                for (int qa = 0; qa <= order; ++qa)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i][qa], fb[j][order - qa], acc[i][j], 0, 0, 0);
+        }
+    };
+
+    if (S > 0) {
+        load_b(0);
+        load_a(0);
+        store_step();
+    }
+    __syncthreads();
+    for (int s = 0; s < S; ++s) {
+        if (s + 1 < S) {
+            load_b(s + 1);
+            load_a(s + 1);
+        }
+        multiply();
+        __syncthreads();
+        if (s + 1 < S) {
+            store_step();
+            __syncthreads();
+        }
+    }
+
+    gemm_epilogue<WGM, WGN, TM, TN>(acc, p, smem, m0, n0);
+}
+
+// LDS writes of some lanes are read by other lanes of the same wavefront: order them without a workgroup barrier and
+// without waiting for global loads and stores in flight (a fence over all address spaces would).
+__device__ __forceinline__ void wave_lds_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+}
+
+// The bf16 GEMM of tall matrices with a small weight: weights-stationary and persistent.  A layer's GEMM here has millions
+// of rows and a weight of at most a few hundred rows and columns, so it is a stream of A through the matrix cores
+// and its bound is HBM.  The tiled kernel above falls well short of that bound on such shapes (measured 4.5 TB/s of A, hi, lo
+// and output traffic on 111 M rows, K = 3 x 128, N = 128): every tile stages the same weight slabs again, and its two
+// workgroup barriers per slab leave loads in flight only while a slab is multiplied.  Here one workgroup per CU stays for
+// the whole launch and holds the weight in LDS as the B fragments of v_mfma_f32_32x32x16_bf16 (loaded once); after that its
+// wavefronts never meet again.  Each wavefront loops over its own tiles of 32 rows, reads A from global memory straight
+// into A-fragment layout (lane l: row l % 32, 8 elements of K from 8 (l / 32) of each 16; the four loads that cover one
+// 64-byte stretch of a row follow each other), with the next 128 elements of K always in flight while the current ones
+// are multiplied, and sends the finished 32 x N tile through a private LDS stage so that it leaves as 16-byte pieces of
+// whole rows.  NB = column blocks of 32.
+template <int NB>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void gemm_stationary_kernel(GemmParams p, int stage_blocks, int stage_bytes) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    using T = uint16_t;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, waves = blockDim.x >> 6;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int KS1 = (p.K1 + 15) / 16, KS2 = p.A2 ? (p.K2 + 15) / 16 : 0;
+    const int kstot = KS1 + KS2;   // k-steps of 16 over the weight's two column blocks
+
+    // the weight -> LDS in fragment order: piece (cb, kg, lane) = W^T[32 cb + lane % 32][8 elements from 16 kg' + 8 (lane / 32)]
+    {
+        const T* Wt = static_cast<const T*>(p.Wt);
+        const int pieces = NB * kstot * 64;
+        for (int i = threadIdx.x; i < pieces; i += blockDim.x) {
+            const int l = i & 63, kg = (i >> 6) % kstot, cb = (i >> 6) / kstot;
+            const int n = cb * 32 + (l & 31);
+            const bool second = kg >= KS1;
+            const int k = (second ? kg - KS1 : kg) * 16 + (l >> 5) * 8;
+            uint4 w = make_uint4(0u, 0u, 0u, 0u);
+            // the packed weight is zero-padded to a multiple of 8 after each block, so a piece that starts below K may be read whole
+            if (n < p.Nout && k < (second ? p.K2 : p.K1)) w = *reinterpret_cast<const uint4*>(Wt + (int64_t)n * p.ldw + (second ? p.K1p : 0) + k);
+            *reinterpret_cast<uint4*>(lds + (size_t)i * 16) = w;
+        }
+    }
+    float* bias_lds = reinterpret_cast<float*>(lds + (size_t)NB * kstot * 1024);
+    for (int i = threadIdx.x; i < NB * 32; i += blockDim.x) bias_lds[i] = (p.bias && i < p.Nout) ? p.bias[i] : 0.f;
+    __syncthreads();  // the only workgroup barrier
+    const unsigned char* wl = lds + lane * 16;
+    unsigned char* stage = lds + (size_t)NB * kstot * 1024 + (size_t)NB * 128 + (size_t)wave * stage_bytes;
+
+    // a step = up to 8 k-steps (128 elements of K) of one A block
+    const int P1 = (KS1 + 7) / 8, P2 = (KS2 + 7) / 8;
+    const int nsteps = P1 + P2 + (p.A3 ? P2 : 0);
+    const int64_t tiles = (p.M + 31) / 32;
+    const int64_t stride = (int64_t)gridDim.x * waves;
+    auto load_step = [&](int64_t t, int i, uint4 (&a)[8]) {
+        const bool second = i >= P1, third = i >= P1 + P2;
+        const T* A = static_cast<const T*>(third ? p.A3 : second ? p.A2 : p.A1);
+        const int64_t lda = second ? p.ld_a2 : p.ld_a1;
+        const int K = second ? p.K2 : p.K1;
+        const int part = third ? i - P1 - P2 : second ? i - P1 : i;
+        const int64_t row = t * 32 + lrow;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) a[ks] = load_chunk<T>(A, lda, row, p.M, (part * 8 + ks) * 16 + lhalf * 8, K, true);
+    };
+    const int ob = p.out_bf16 ? 2 : 4, epc = 16 / ob;
+    const int rs = stage_blocks * 32 * ob + 16;   // staged row pitch in bytes
+
+    int64_t t = (int64_t)blockIdx.x * waves + wave;
+    uint4 a_cur[8], a_nxt[8];
+    if (t < tiles) load_step(t, 0, a_nxt);
+    for (; t < tiles; t += stride) {
+        floatx16 acc[NB];
+#pragma unroll
+        for (int cb = 0; cb < NB; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
+        for (int i = 0; i < nsteps; ++i) {
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) a_cur[ks] = a_nxt[ks];
+            const bool last = i + 1 == nsteps;
+            const int64_t tn = last ? t + stride : t;
+            if (tn < tiles) load_step(tn, last ? 0 : i + 1, a_nxt);
+            const bool second = i >= P1, third = i >= P1 + P2;
+            const int part = third ? i - P1 - P2 : second ? i - P1 : i;
+            const int kg0 = (second ? KS1 : 0) + part * 8;           // first k-step of the step in the weight's order
+            const int nks = (second ? KS2 : KS1) - part * 8;         // k-steps left in the block (>= 1)
+            const unsigned char* wk = wl + (size_t)kg0 * 1024;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                if (ks < nks) {  // wave-uniform
+                    bf16x8 a;
+                    __builtin_memcpy(&a, &a_cur[ks], 16);
+#pragma unroll
+                    for (int cb = 0; cb < NB; ++cb) {
+                        const bf16x8 b = *reinterpret_cast<const bf16x8*>(wk + ((size_t)cb * kstot + ks) * 1024);
+                        acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[cb], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        // epilogue: lane holds column (lane % 32) of rows 8*(r/4) + 4*(lane/32) + r%4 of each 32 x 32 block; the stage takes
+        // stage_blocks column blocks at a time
+        const int64_t m0 = t * 32;
+        float osc[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) osc[r] = 1.f;
+        if (p.out_scale) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t m = m0 + 8 * (r / 4) + 4 * lhalf + (r % 4);
+                if (m < p.M) osc[r] = p.out_scale[p.row0 + m];
+            }
+        }
+#pragma unroll
+        for (int cb = 0; cb < NB; ++cb) {
+            const int j = cb % stage_blocks;
+            const float b = bias_lds[cb * 32 + lrow];
+            float v[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) v[r] = acc[cb][r] + b;
+            if (p.act == DGI_ACT_RELU) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) v[r] = fmaxf(v[r], 0.f);
+            } else if (p.act != DGI_ACT_NONE) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) v[r] = activate(v[r], p.act, p.act_slope);
+            }
+            unsigned char* dst = stage + (4 * lhalf) * rs + (j * 32 + lrow) * ob;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                unsigned char* d = dst + (8 * (r / 4) + (r % 4)) * rs;
+                if (p.out_bf16) *reinterpret_cast<uint16_t*>(d) = float_to_bf16(v[r] * osc[r]);
+                else *reinterpret_cast<float*>(d) = v[r] * osc[r];
+            }
+            if (j + 1 == stage_blocks || cb + 1 == NB) {  // wave-uniform: the stage is full
+                wave_lds_fence();
+                const int n_first = (cb - j) * 32;
+                const int ncols = (p.Nout - n_first) < (j + 1) * 32 ? (p.Nout - n_first) : (j + 1) * 32;
+                if (ncols > 0) {
+                    const int cpr = (ncols * ob + 15) / 16;
+                    unsigned char* Yb = static_cast<unsigned char*>(p.Y);
+                    for (int c = lane; c < 32 * cpr; c += 64) {
+                        const int row = c / cpr, cc = c - row * cpr;
+                        const int64_t m = m0 + row;
+                        if (m >= p.M) continue;
+                        const int n = cc * epc;   // column inside the staged stretch
+                        const unsigned char* src = stage + row * rs + cc * 16;
+                        unsigned char* y = Yb + (m * p.ld_y + n_first + n) * ob;
+                        if (n + epc <= ncols) {
+                            *reinterpret_cast<uint4*>(y) = *reinterpret_cast<const uint4*>(src);
+                        } else {
+                            for (int e = 0; e < (ncols - n) * ob; e += 2) *reinterpret_cast<uint16_t*>(y + e) = *reinterpret_cast<const uint16_t*>(src + e);
+                        }
+                    }
+                }
+                wave_lds_fence();  // the stage may be written again
+            }
+        }
+    }
 }
 
 template <typename T>
@@ -336,9 +700,72 @@ dgi_status_t launch_cfg(GemmParams p, hipStream_t stream) {
     p.tiles_n = (p.Nout + BN - 1) / BN;
     const int64_t grid = tiles_m * p.tiles_n;
     DGI_REQUIRE(grid * 256 < (int64_t)1 << 32, DGI_ERR_INVALID_ARG, "gemm: too many tiles for one launch");
-    hipLaunchKernelGGL((gemm_kernel<T, WGM, WGN, TM, TN>), dim3((unsigned)grid), dim3(256), 0, stream, p);
+    if constexpr (sizeof(T) == 4 && !kF32OnF32Mfma) hipLaunchKernelGGL((gemm_split_kernel<WGM, WGN, TM, TN>), dim3((unsigned)grid), dim3(256), 0, stream, p);
+    else hipLaunchKernelGGL((gemm_kernel<T, WGM, WGN, TM, TN>), dim3((unsigned)grid), dim3(256), 0, stream, p);
     DGI_HIP(hipGetLastError());
     return DGI_OK;
+}
+
+constexpr int kStationaryWaves = 8;
+
+int device_cu_count() {
+    static const int n = [] {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+        return v;
+    }();
+    return n;
+}
+
+// LDS one workgroup may have: all of a CU's 160 KB on gfx950 (the device says how much it grants)
+size_t stationary_lds_bytes() {
+    static const size_t n = [] {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess || v <= 0) v = 64 * 1024;
+        return std::min<size_t>((size_t)v, 160 * 1024);
+    }();
+    return n;
+}
+
+// LDS plan of the stationary kernel: weight fragments, bias, one output stage per wavefront that holds as many column
+// blocks as fit (whole rows when it can).  Returns the column blocks per stage, 0 if the weight leaves no room.
+// the kernel is built for 2, 4, 6 and 8 column blocks of 32
+int stationary_blocks(int Nout) { return ((Nout + 63) / 64) * 2; }
+
+int stationary_stage_blocks(const GemmParams& p, size_t* weight_bytes) {
+    const int NB = stationary_blocks(p.Nout);
+    const int kstot = (p.K1 + 15) / 16 + (p.A2 ? (p.K2 + 15) / 16 : 0);
+    const size_t wb = (size_t)NB * kstot * 1024 + (size_t)NB * 128;
+    if (weight_bytes) *weight_bytes = wb;
+    const size_t kStationaryLds = stationary_lds_bytes();
+    if (NB > 8 || wb >= kStationaryLds) return 0;
+    const int ob = p.out_bf16 ? 2 : 4;
+    const int64_t per_row = (int64_t)((kStationaryLds - wb) / kStationaryWaves / 32);   // bytes of one staged row
+    const int64_t sb = (per_row - 16) / (32 * ob);
+    return (int)std::min<int64_t>(NB, std::max<int64_t>(sb, 0));
+}
+
+template <int NB>
+dgi_status_t launch_stationary_nb(const GemmParams& p, int sb, size_t wb, hipStream_t stream) {
+    const int ob = p.out_bf16 ? 2 : 4;
+    const int stage_bytes = 32 * (sb * 32 * ob + 16);
+    const size_t lds = wb + (size_t)kStationaryWaves * stage_bytes;
+    const int64_t tiles = (p.M + 31) / 32;
+    const int64_t grid = std::min<int64_t>(device_cu_count(), (tiles + kStationaryWaves - 1) / kStationaryWaves);
+    auto kernel = gemm_stationary_kernel<NB>;
+    if (lds > 48 * 1024)
+        DGI_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kStationaryWaves * 64), lds, stream, p, sb, stage_bytes);
+    DGI_HIP(hipGetLastError());
+    return DGI_OK;
+}
+
+dgi_status_t launch_stationary(const GemmParams& p, int sb, size_t wb, hipStream_t stream) {
+    const int NB = stationary_blocks(p.Nout);
+    if (NB <= 2) return launch_stationary_nb<2>(p, sb, wb, stream);
+    if (NB <= 4) return launch_stationary_nb<4>(p, sb, wb, stream);
+    if (NB <= 6) return launch_stationary_nb<6>(p, sb, wb, stream);
+    return launch_stationary_nb<8>(p, sb, wb, stream);
 }
 
 }  // namespace
@@ -347,6 +774,7 @@ dgi_status_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
     if (a.M <= 0 || a.Nout <= 0) return DGI_OK;
     const int eb = a.dtype == DGI_BF16 ? 2 : 4, E = 16 / eb;
     DGI_REQUIRE(a.A1 && a.Wt && a.Y, DGI_ERR_INVALID_ARG, "gemm: null operand");
+    DGI_REQUIRE(a.dtype == DGI_BF16 || !a.A3, DGI_ERR_INVALID_ARG, "gemm: the low-order block is a bf16 operand");
     DGI_REQUIRE((uintptr_t)a.Wt % 16 == 0 && a.ldw % E == 0 && a.K1p % E == 0, DGI_ERR_INVALID_ARG, "gemm: packed weight misaligned");
     GemmParams p{};
     p.A1 = a.A1; p.ld_a1 = a.ld_a1; p.K1 = a.K1;
@@ -365,6 +793,11 @@ dgi_status_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
     p.out_scale = a.out_scale; p.row0 = a.row0;
     // 128-wide column tiles: a 256-wide tile would read A once but leaves one wavefront per SIMD and measured slower
     if (a.dtype == DGI_BF16) {
+        if (p.a1_vec && (!p.A2 || p.a2_vec) && p.y_vec && !kTiledBf16) {
+            size_t wb = 0;
+            const int sb = stationary_stage_blocks(p, &wb);
+            if (sb > 0) return launch_stationary(p, sb, wb, stream);
+        }
         if (a.Nout <= 64) return launch_cfg<uint16_t, 4, 1, 1, 2>(p, stream);
         if (a.Nout > 128 && a.Nout <= 192) return launch_cfg<uint16_t, 2, 2, 2, 3>(p, stream);
         return launch_cfg<uint16_t, 2, 2, 2, 2>(p, stream);

@@ -507,6 +507,44 @@ def test_split_and_transform_first_paths_with_many_rows(storage, dims):
         assert max_rel_err(got, want) <= (TOL_BF16 if storage == "bf16" else TOL_F32), (order,)
 
 
+@pytest.mark.parametrize("agg,dims,act", [("mean", (104, 40), "relu"), ("gcn", (320, 64), "leaky_relu"), ("sum", (136, 200), "none"),
+                                          ("mean", (8, 8), "relu"), ("gcn", (128, 256), "relu")])
+def test_weights_stationary_bf16_gemm_shapes(agg, dims, act):
+    # the bf16 GEMM that keeps the weight in LDS: a last k-step of 8 elements (K = 104, 136), several 128-element parts per
+    # block (K = 320), the per-row factor of GCN, 2 to 8 column blocks with ragged last ones, a row count that leaves the
+    # last 32-row tile ragged; split order (three A blocks: own rows, aggregate, its remainder) and transform-first (one)
+    n = 4111
+    d_in, d_out = dims
+    indptr, indices = random_csr(n, 5.0, seed=d_in + d_out)
+    X, Ws, Wn = rnd((n, d_in), 1), rnd((d_in, d_out), 2, 0.15), rnd((d_in, d_out), 3, 0.15)
+    X, Ws, Wn = [torch.from_numpy(a).to(torch.bfloat16).float().numpy() for a in (X, Ws, Wn)]
+    g = B().graph_load(indptr, indices)
+    for order in ("agg_first_split", "transform_first"):
+        for out_storage in ("bf16", "f32"):
+            layer = dict(agg=agg, act=act, W_self=None if agg == "gcn" else Ws, W_neigh=Wn, bias=rnd((d_out,), 4),
+                         order=order, out_storage=out_storage)
+            got = gpu_layer(g, layer, X, storage="bf16")
+            want = oracle.layer_forward(indptr, indices, layer, X)
+            assert max_rel_err(got, want) <= TOL_BF16, (order, out_storage)
+
+@pytest.mark.parametrize("order", ["agg_first_split", "transform_first"])
+def test_fp32_gemm_on_three_bf16_terms_keeps_fp32_accuracy(order):
+    # fp32 GEMMs run on the bf16 matrix instruction with every operand split into three bf16 terms; one or two terms
+    # would leave errors of 2^-9 or 2^-17, far above this bound.  Features and weights span six orders of magnitude.
+    n, d = 6000, 256
+    indptr, indices = random_csr(n, 6.0, seed=77)
+    rng = np.random.default_rng(3)
+    X = (rng.standard_normal((n, d)) * 10.0 ** rng.uniform(-3, 3, (n, 1))).astype(np.float32)
+    Ws = (rng.standard_normal((d, d)) * 10.0 ** rng.uniform(-3, 0, (d, 1))).astype(np.float32)
+    Wn = (rng.standard_normal((d, d)) * 10.0 ** rng.uniform(-3, 0, (1, d))).astype(np.float32)
+    layer = dict(agg="mean", act="none", W_self=Ws, W_neigh=Wn, bias=None, order=order)
+    g = B().graph_load(indptr, indices)
+    got = gpu_layer(g, layer, X)
+    want = oracle.layer_forward(indptr, indices, layer, X)
+    # per output row: the rows' magnitudes differ by 10^6, so a single floor for the whole tensor would hide the small ones
+    err = np.abs(got - want) / np.maximum(np.abs(want), np.sqrt(np.mean(want ** 2, axis=1, keepdims=True)))
+    assert err.max() <= 2e-5
+
 @pytest.mark.parametrize("storage,dims", [("f32", (256, 256)), ("f32", (72, 300)), ("bf16", (256, 320)), ("bf16", (128, 256))])
 @pytest.mark.parametrize("agg", ["sum", "mean"])
 def test_fused_layer_with_eight_or_more_column_blocks(storage, dims, agg):
