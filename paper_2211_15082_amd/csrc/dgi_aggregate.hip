@@ -56,6 +56,7 @@ struct AggParams {
     int width;
     void* out;
     void* out_lo;          // bf16 output only: receives the part of each value its bf16 rounding dropped (or null)
+    int lo_bytes;          // ... as a second bf16 value (2) or as a byte in units of 2^-8 of the value's last place (1)
     int64_t ld_out;
     int64_t out_row0;
     int out_bf16;
@@ -245,6 +246,19 @@ __device__ __forceinline__ void combine_groups(float (&acc)[VEC]) {
     }
 }
 
+// What rounding `val` to the bf16 value `hi` dropped, in units of 2^-8 of hi's last place, as a byte with offset 128:
+// val = hi + (byte - 128) * 2^(e - 15) up to 2^(e - 16), e = hi's exponent (the remainder is at most half a last place
+// = 128 units; 128 itself is stored as 127).  hi + byte carry 16 significant bits in 3 bytes.  Zero, denormal-range
+// (e < -112) and non-finite hi get the byte of a zero remainder.
+__device__ __forceinline__ uint32_t remainder_byte(float val, uint32_t hi) {
+    const uint32_t eb = (hi >> 7) & 0xffu;
+    if (eb < 15u || eb == 255u) return 128u;
+    const float scale = __uint_as_float((269u - eb) << 23);   // 2^(15 - e)
+    float q = rintf((val - bf16_to_float(hi)) * scale);
+    q = fminf(fmaxf(q, -127.f), 127.f);
+    return (uint32_t)((int)q + 128);
+}
+
 // scale, self addend, bias, activation, store of one output element
 template <typename T>
 __device__ __forceinline__ void finish_store(const AggParams& p, int64_t v, int64_t out_row, int c, float sum, float scale) {
@@ -257,7 +271,10 @@ __device__ __forceinline__ void finish_store(const AggParams& p, int64_t v, int6
     if (p.out_bf16) {
         const uint16_t hi = float_to_bf16(val);
         static_cast<uint16_t*>(p.out)[o] = hi;
-        if (p.out_lo) static_cast<uint16_t*>(p.out_lo)[o] = float_to_bf16(val - bf16_to_float(hi));
+        if (p.out_lo) {
+            if (p.lo_bytes == 1) static_cast<uint8_t*>(p.out_lo)[o] = (uint8_t)remainder_byte(val, hi);
+            else static_cast<uint16_t*>(p.out_lo)[o] = float_to_bf16(val - bf16_to_float(hi));
+        }
     } else {
         static_cast<float*>(p.out)[o] = val;
     }
@@ -308,7 +325,21 @@ __device__ __forceinline__ void store_chunk(const AggParams& p, int64_t v, int64
         // VEC bf16 values are 8 bytes (fp32 sources) or 16 bytes (bf16 sources)
         if constexpr (VEC == 4) *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + o) = make_uint2(w[0], w[1]);
         else *reinterpret_cast<uint4*>(static_cast<uint16_t*>(p.out) + o) = make_uint4(w[0], w[1], w[(VEC > 4) ? 2 : 0], w[(VEC > 4) ? 3 : 0]);
-        if (p.out_lo) {  // what the rounding above dropped, as a second bf16 value per element
+        if (p.out_lo && p.lo_bytes == 1) {  // what the rounding above dropped, one byte per element
+            uint32_t q[(VEC + 3) / 4];
+#pragma unroll
+            for (int i = 0; i < VEC / 4; ++i) {
+                q[i] = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int e = 4 * i + j;
+                    const uint32_t hi = (e & 1) ? (w[e / 2] >> 16) : (w[e / 2] & 0xffffu);
+                    q[i] |= remainder_byte(val[e], hi) << (8 * j);
+                }
+            }
+            if constexpr (VEC == 4) *reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(p.out_lo) + o) = q[0];
+            else *reinterpret_cast<uint2*>(static_cast<uint8_t*>(p.out_lo) + o) = make_uint2(q[0], q[(VEC > 4) ? 1 : 0]);
+        } else if (p.out_lo) {  // ... or as a second bf16 value per element
             uint32_t l[(VEC + 1) / 2];
 #pragma unroll
             for (int i = 0; i < VEC / 2; ++i) {
@@ -726,16 +757,25 @@ void fused_layer_kernel(FusedParams fp) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[i] = 0.f;
         }
+        // All loops below are free of branches around loads: a step past the end re-reads the last one (a valid address)
+        // and multiplies an A fragment masked to zero.  A load inside a branch, even a wave-uniform one, makes the
+        // compiler wait for every outstanding load at the next use (it can no longer count the younger ones), which
+        // turned the three-batch rotation below into one L2 round trip per batch.
+        auto masked = [](uint4 v, bool keep) {
+            const uint32_t m = keep ? 0xffffffffu : 0u;
+            return make_uint4(v.x & m, v.y & m, v.z & m, v.w & m);
+        };
         constexpr int U = 4;
         if (!SL && fp.has_self) {  // K block of the rows' own features: columns [0, Kp) of the packed weight
             for (int ks = 0; ks < ksteps; ks += U) {
                 uint4 a[U], b[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    const int k = (ks + u) * 2 * VEC;  // + lhalf * VEC is inside the base pointers
-                    const bool in = ks + u < ksteps;
-                    a[u] = (in && self_row && k + lhalf * VEC < K) ? *reinterpret_cast<const uint4*>(a_self + k) : make_uint4(0u, 0u, 0u, 0u);
-                    b[u] = in ? *reinterpret_cast<const uint4*>(w + (int64_t)(ks + u) * 64 * VEC) : make_uint4(0u, 0u, 0u, 0u);
+                    const int kc = ks + u < ksteps ? ks + u : ksteps - 1;
+                    const int k = kc * 2 * VEC;  // + lhalf * VEC is inside the base pointers
+                    const bool in = ks + u < ksteps && self_row && k + lhalf * VEC < K;
+                    a[u] = masked(*reinterpret_cast<const uint4*>(a_self + (k + lhalf * VEC < K ? k : 0)), in);
+                    b[u] = *reinterpret_cast<const uint4*>(w + (int64_t)kc * 64 * VEC);
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) mma(acc, a[u], b[u]);
@@ -751,29 +791,41 @@ void fused_layer_kernel(FusedParams fp) {
         constexpr int R = DGI_FUSED_RING_STEPS;
         auto load_b = [&](uint4 (&b)[R], int ks) {
 #pragma unroll
-            for (int u = 0; u < R; ++u)
-                b[u] = ks + u < lsteps ? *reinterpret_cast<const uint4*>(w + (int64_t)(wks + ks + u) * 64 * VEC) : make_uint4(0u, 0u, 0u, 0u);
+            for (int u = 0; u < R; ++u) {
+                const int kc = ks + u < lsteps ? ks + u : lsteps - 1;
+                b[u] = *reinterpret_cast<const uint4*>(w + (int64_t)(wks + kc) * 64 * VEC);
+            }
         };
-        auto batch = [&](const uint4 (&b)[R], int ks) {  // R steps from K step ks on (wave-uniform guard)
-            if (ks >= lsteps) return;
+        auto batch = [&](const uint4 (&b)[R], int ks) {  // R steps from K step ks on
             uint4 a[R];
 #pragma unroll
-            for (int u = 0; u < R; ++u)
-                a[u] = ks + u < lsteps ? *reinterpret_cast<const uint4*>(a_lds + (ks + u) * 2 * VEC) : make_uint4(0u, 0u, 0u, 0u);
+            for (int u = 0; u < R; ++u) {
+                const int kc = ks + u < lsteps ? ks + u : lsteps - 1;
+                a[u] = masked(*reinterpret_cast<const uint4*>(a_lds + kc * 2 * VEC), ks + u < lsteps);
+            }
 #pragma unroll
             for (int u = 0; u < R; ++u) mma(acc, a[u], b[u]);
         };
         const int ks0 = resumed ? ksteps : 0;
         uint4 b0[R], b1[R], b2[R];
+        // (the scheduling barriers keep the compiler from sinking each batch's loads down to their first use, which it
+        // does to shorten register lifetimes and which would expose the whole latency again)
         load_b(b0, ks0);
         load_b(b1, ks0 + R);
+        __builtin_amdgcn_sched_barrier(0);
         for (int ks = ks0; ks < lsteps; ks += 3 * R) {
             load_b(b2, ks + 2 * R);
+            __builtin_amdgcn_sched_barrier(0);
             batch(b0, ks);
+            __builtin_amdgcn_sched_barrier(0);
             load_b(b0, ks + 3 * R);
+            __builtin_amdgcn_sched_barrier(0);
             batch(b1, ks + R);
+            __builtin_amdgcn_sched_barrier(0);
             load_b(b1, ks + 4 * R);
+            __builtin_amdgcn_sched_barrier(0);
             batch(b2, ks + 2 * R);
+            __builtin_amdgcn_sched_barrier(0);
         }
         if constexpr (HL) {  // the rounding remainders of m_v against the neighbour weights once more
             const T* a_lo = a_lds + acol + Kp;
@@ -782,9 +834,9 @@ void fused_layer_kernel(FusedParams fp) {
                 uint4 a[R], b[R];
 #pragma unroll
                 for (int u = 0; u < R; ++u) {
-                    const bool in = ks + u < ksteps;
-                    b[u] = in ? *reinterpret_cast<const uint4*>(w + (int64_t)(wn + ks + u) * 64 * VEC) : make_uint4(0u, 0u, 0u, 0u);
-                    a[u] = in ? *reinterpret_cast<const uint4*>(a_lo + (ks + u) * 2 * VEC) : make_uint4(0u, 0u, 0u, 0u);
+                    const int kc = ks + u < ksteps ? ks + u : ksteps - 1;
+                    b[u] = *reinterpret_cast<const uint4*>(w + (int64_t)(wn + kc) * 64 * VEC);
+                    a[u] = masked(*reinterpret_cast<const uint4*>(a_lo + kc * 2 * VEC), ks + u < ksteps);
                 }
 #pragma unroll
                 for (int u = 0; u < R; ++u) mma(acc, a[u], b[u]);
@@ -1097,9 +1149,9 @@ dgi_status_t launch_aggregate(const AggArgs& a, int stage, hipStream_t stream) {
     p.S = a.S; p.ld_s = a.ld_s; p.width = a.width;
     p.out = a.out; p.ld_out = a.ld_out; p.out_row0 = a.out_row0;
     p.out_bf16 = a.out_dtype == DGI_BF16;
-    DGI_REQUIRE(a.out_lo == nullptr || (p.out_bf16 && (uintptr_t)a.out_lo % 16 == (uintptr_t)a.out % 16), DGI_ERR_INVALID_ARG,
-                "aggregate: a low-order output needs a bf16 output of the same alignment");
-    p.out_lo = a.out_lo;
+    DGI_REQUIRE(a.out_lo == nullptr || (p.out_bf16 && (uintptr_t)a.out_lo % 16 == (uintptr_t)a.out % 16 && (a.lo_bytes == 1 || a.lo_bytes == 2)),
+                DGI_ERR_INVALID_ARG, "aggregate: a low-order output needs a bf16 output of the same alignment");
+    p.out_lo = a.out_lo; p.lo_bytes = a.lo_bytes;
     p.self = a.self; p.ld_self = a.ld_self;
     p.bias = a.bias; p.act = a.act; p.act_slope = a.act_slope; p.out_scale = a.out_scale;
     p.row_begin = a.row_begin; p.row_end = a.row_end;

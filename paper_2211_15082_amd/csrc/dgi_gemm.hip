@@ -35,11 +35,16 @@ constexpr bool kF32OnF32Mfma = DGI_GEMM_F32_MFMA != 0;
 #define DGI_GEMM_BF16_TILED 0
 #endif
 constexpr bool kTiledBf16 = DGI_GEMM_BF16_TILED != 0;
+// The weights-stationary kernel: wavefronts per workgroup.
+#ifndef DGI_STATIONARY_WAVES
+#define DGI_STATIONARY_WAVES 8
+#endif
 
 struct GemmParams {
     const void* A1; int64_t ld_a1; int K1; int a1_vec;
     const void* A2; int64_t ld_a2; int K2; int a2_vec;
     const void* A3;  // optional third block: same shape, leading dimension and weight columns as A2
+    const uint8_t* Q; int64_t ld_q;  // or the last block's remainder bytes (weights-stationary kernel only)
     const void* Wt; int64_t ldw; int K1p;
     const float* bias;
     int act; float act_slope;
@@ -462,19 +467,41 @@ __device__ __forceinline__ void wave_lds_fence() {
 // workgroup barriers per slab leave loads in flight only while a slab is multiplied.  Here one workgroup per CU stays for
 // the whole launch and holds the weight in LDS as the B fragments of v_mfma_f32_32x32x16_bf16 (loaded once); after that its
 // wavefronts never meet again.  Each wavefront loops over its own tiles of 32 rows, reads A from global memory straight
-// into A-fragment layout (lane l: row l % 32, 8 elements of K from 8 (l / 32) of each 16; the four loads that cover one
-// 64-byte stretch of a row follow each other), with the next 128 elements of K always in flight while the current ones
-// are multiplied, and sends the finished 32 x N tile through a private LDS stage so that it leaves as 16-byte pieces of
-// whole rows.  NB = column blocks of 32.
-template <int NB>
+// into fragment layout (lane l: row l % 32, 8 elements of K from 8 (l / 32) of each 16; the four loads that cover one
+// 64-byte stretch of a row follow each other) in steps of 128 elements of K, each step into registers of its own that are
+// refilled for the wavefront's next tile as soon as the step is multiplied, and sends the finished 32 x N tile through a
+// private LDS stage so that it leaves as 16-byte pieces of whole rows.  The kernel is bound by the loads it keeps in
+// flight (8, 6 and 4 wavefronts with one step in flight each: 23, 26 and 32 ms on the 111 M-row GEMM).
+// NB = column blocks of 32, NS = steps per tile, of which the last NS - QS (those of the last K block) come with
+// remainder bytes.
+// The bf16 values (value - 128) * 2^(e - 15) that the bytes q stand for, e = exponent of the bf16 value they belong to
+// (remainder_byte of the aggregation kernel): 8 elements, hi and the result packed two per word.  Each has at most 7
+// significant bits, so cutting the fp32 product to its upper half is exact.
+__device__ __forceinline__ uint4 remainder_values(const uint4& hi, const uint2& q) {
+    const uint32_t h[4] = {hi.x, hi.y, hi.z, hi.w};
+    uint32_t out[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t qw = i < 2 ? q.x : q.y;
+        const float q0 = (float)((qw >> (16 * (i & 1))) & 0xffu) - 128.f, q1 = (float)((qw >> (16 * (i & 1) + 8)) & 0xffu) - 128.f;
+        const float s0 = __uint_as_float((h[i] << 16) & 0x7f800000u) * 0x1p-15f, s1 = __uint_as_float(h[i] & 0x7f800000u) * 0x1p-15f;
+        out[i] = (__float_as_uint(q0 * s0) >> 16) | (__float_as_uint(q1 * s1) & 0xffff0000u);
+    }
+    return make_uint4(out[0], out[1], out[2], out[3]);
+}
+
+template <int NB, int NS, int QS>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void gemm_stationary_kernel(GemmParams p, int stage_blocks, int stage_bytes) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     using T = uint16_t;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, waves = blockDim.x >> 6;
     const int lrow = lane & 31, lhalf = lane >> 5;
-    const int KS1 = (p.K1 + 15) / 16, KS2 = p.A2 ? (p.K2 + 15) / 16 : 0;
-    const int kstot = KS1 + KS2;   // k-steps of 16 over the weight's two column blocks
+    // a step = 8 k-steps of 16 (128 elements of K) of one A block; a block's last step is padded with zero weights, so
+    // that the loops below have no branches and the compiler can overlap fragment reads, decoding and products
+    const int P1 = (p.K1 + 127) / 128, P2 = p.A2 ? (p.K2 + 127) / 128 : 0;
+    const int KS1 = 8 * P1, KS2 = 8 * P2;
+    const int kstot = KS1 + KS2;   // k-steps over the weight's two column blocks
 
     // the weight -> LDS in fragment order: piece (cb, kg, lane) = W^T[32 cb + lane % 32][8 elements from 16 kg' + 8 (lane / 32)]
     {
@@ -497,107 +524,139 @@ void gemm_stationary_kernel(GemmParams p, int stage_blocks, int stage_bytes) {
     const unsigned char* wl = lds + lane * 16;
     unsigned char* stage = lds + (size_t)NB * kstot * 1024 + (size_t)NB * 128 + (size_t)wave * stage_bytes;
 
-    // a step = up to 8 k-steps (128 elements of K) of one A block
-    const int P1 = (KS1 + 7) / 8, P2 = (KS2 + 7) / 8;
-    const int nsteps = P1 + P2 + (p.A3 ? P2 : 0);
+    constexpr bool Q = QS < NS;   // steps QS .. NS-1 (those of the last K block) come with remainder bytes
     const int64_t tiles = (p.M + 31) / 32;
     const int64_t stride = (int64_t)gridDim.x * waves;
-    auto load_step = [&](int64_t t, int i, uint4 (&a)[8]) {
-        const bool second = i >= P1, third = i >= P1 + P2;
+    struct Buffers {
+        uint4 a[NS][8];
+        uint2 q[Q ? NS - QS : 1][8];   // the remainder bytes of the same 8 elements per k-step
+    };
+    auto load_step = [&](int64_t t, int i, Buffers& bf) {
+        const bool second = i >= P1, third = i >= P1 + P2;   // the third block (A3) repeats the second one's shape and weights
         const T* A = static_cast<const T*>(third ? p.A3 : second ? p.A2 : p.A1);
         const int64_t lda = second ? p.ld_a2 : p.ld_a1;
         const int K = second ? p.K2 : p.K1;
         const int part = third ? i - P1 - P2 : second ? i - P1 : i;
         const int64_t row = t * 32 + lrow;
+        // every lane issues every load (out-of-range ones read the block's first bytes and are zeroed on arrival): the
+        // number of loads in flight is then known at compile time, and waiting for one step's registers does not have
+        // to wait for the younger loads and stores as well
+        const T* arow = A + (row < p.M ? row : 0) * lda;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) a[ks] = load_chunk<T>(A, lda, row, p.M, (part * 8 + ks) * 16 + lhalf * 8, K, true);
+        for (int ks = 0; ks < 8; ++ks) {
+            const int k = (part * 8 + ks) * 16 + lhalf * 8;   // K is a multiple of 8 (host-checked): a piece is in or out as a whole
+            bf.a[i][ks] = *reinterpret_cast<const uint4*>(arow + (k < K ? k : 0));
+        }
+        if constexpr (Q) {
+            if (i >= QS) {
+                const uint8_t* qrow = p.Q + (row < p.M ? row : 0) * p.ld_q;
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) {
+                    const int k = (part * 8 + ks) * 16 + lhalf * 8;
+                    bf.q[i >= QS ? i - QS : 0][ks] = *reinterpret_cast<const uint2*>(qrow + (k < K ? k : 0));   // out of range: meets zero values
+                }
+            }
+        }
     };
     const int ob = p.out_bf16 ? 2 : 4, epc = 16 / ob;
     const int rs = stage_blocks * 32 * ob + 16;   // staged row pitch in bytes
 
     int64_t t = (int64_t)blockIdx.x * waves + wave;
-    uint4 a_cur[8], a_nxt[8];
-    if (t < tiles) load_step(t, 0, a_nxt);
+    // One register buffer per step of a tile (NS = nsteps, checked by the host).  A buffer is refilled with the same step
+    // of the wavefront's next tile as soon as its products are issued, so the loads of a whole tile are in flight behind
+    // the multiplication (no buffer is ever copied: moving a register that a load is still to fill would wait for it).
+    Buffers buf;
+    if (t < tiles) {
+#pragma unroll
+        for (int i = 0; i < NS; ++i) load_step(t, i, buf);
+    }
+    const floatx16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (; t < tiles; t += stride) {
+        // The products are taken as (W^T fragment) x (A fragment): the accumulator block is then the transposed output
+        // block, lane l holds row l % 32 of the tile and, in register r, column 8 (r / 4) + 4 (l / 32) + r % 4 of the
+        // block: four consecutive columns per group of four registers, which leave as one packed store.  A row's result
+        // depends on that row of A alone, so rows past M and pieces past K need no masking: the former are never stored,
+        // the latter meet zero weights (they re-read the row's first bytes, finite whenever the row is).
         floatx16 acc[NB];
 #pragma unroll
-        for (int cb = 0; cb < NB; ++cb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
-        for (int i = 0; i < nsteps; ++i) {
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) a_cur[ks] = a_nxt[ks];
-            const bool last = i + 1 == nsteps;
-            const int64_t tn = last ? t + stride : t;
-            if (tn < tiles) load_step(tn, last ? 0 : i + 1, a_nxt);
+        for (int i = 0; i < NS; ++i) {
             const bool second = i >= P1, third = i >= P1 + P2;
             const int part = third ? i - P1 - P2 : second ? i - P1 : i;
             const int kg0 = (second ? KS1 : 0) + part * 8;           // first k-step of the step in the weight's order
-            const int nks = (second ? KS2 : KS1) - part * 8;         // k-steps left in the block (>= 1)
             const unsigned char* wk = wl + (size_t)kg0 * 1024;
+            const bool with_q = Q && i >= QS;   // known at compile time: i is unrolled
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) {
-                if (ks < nks) {  // wave-uniform
-                    bf16x8 a;
-                    __builtin_memcpy(&a, &a_cur[ks], 16);
+                bf16x8 w[NB];   // the fragments of all column blocks first, then the products: independent accumulators back to back
 #pragma unroll
-                    for (int cb = 0; cb < NB; ++cb) {
-                        const bf16x8 b = *reinterpret_cast<const bf16x8*>(wk + ((size_t)cb * kstot + ks) * 1024);
-                        acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[cb], 0, 0, 0);
-                    }
+                for (int cb = 0; cb < NB; ++cb) w[cb] = *reinterpret_cast<const bf16x8*>(wk + ((size_t)cb * kstot + ks) * 1024);
+                bf16x8 a, lo;
+                __builtin_memcpy(&a, &buf.a[i][ks], 16);
+                if (with_q) {
+                    const uint4 l = remainder_values(buf.a[i][ks], buf.q[i >= QS ? i - QS : 0][ks]);
+                    __builtin_memcpy(&lo, &l, 16);
+                }
+                // the tile's first product starts from zero
+#pragma unroll
+                for (int cb = 0; cb < NB; ++cb)
+                    acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[cb], a, (i == 0 && ks == 0) ? zero16 : acc[cb], 0, 0, 0);
+                if (with_q) {
+#pragma unroll
+                    for (int cb = 0; cb < NB; ++cb) acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[cb], lo, acc[cb], 0, 0, 0);
                 }
             }
+            load_step(t + stride < tiles ? t + stride : t, i, buf);   // the last tile once more rather than a conditional load (see load_step)
         }
-        // epilogue: lane holds column (lane % 32) of rows 8*(r/4) + 4*(lane/32) + r%4 of each 32 x 32 block; the stage takes
-        // stage_blocks column blocks at a time
+        // epilogue; the stage takes stage_blocks column blocks at a time
         const int64_t m0 = t * 32;
-        float osc[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) osc[r] = 1.f;
-        if (p.out_scale) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t m = m0 + 8 * (r / 4) + 4 * lhalf + (r % 4);
-                if (m < p.M) osc[r] = p.out_scale[p.row0 + m];
-            }
-        }
+        const float osc = (p.out_scale && m0 + lrow < p.M) ? p.out_scale[p.row0 + m0 + lrow] : 1.f;
 #pragma unroll
         for (int cb = 0; cb < NB; ++cb) {
             const int j = cb % stage_blocks;
-            const float b = bias_lds[cb * 32 + lrow];
-            float v[16];
+            unsigned char* dst = stage + lrow * rs + (j * 32 + 4 * lhalf) * ob;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) v[r] = acc[cb][r] + b;
-            if (p.act == DGI_ACT_RELU) {
+            for (int g = 0; g < 4; ++g) {
+                const float4 b = *reinterpret_cast<const float4*>(bias_lds + cb * 32 + 8 * g + 4 * lhalf);
+                float v[4] = {acc[cb][4 * g] + b.x, acc[cb][4 * g + 1] + b.y, acc[cb][4 * g + 2] + b.z, acc[cb][4 * g + 3] + b.w};
+                if (p.act == DGI_ACT_RELU) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) v[r] = fmaxf(v[r], 0.f);
-            } else if (p.act != DGI_ACT_NONE) {
+                    for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
+                } else if (p.act != DGI_ACT_NONE) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) v[r] = activate(v[r], p.act, p.act_slope);
-            }
-            unsigned char* dst = stage + (4 * lhalf) * rs + (j * 32 + lrow) * ob;
+                    for (int e = 0; e < 4; ++e) v[e] = activate(v[e], p.act, p.act_slope);
+                }
+                if (p.out_scale) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                unsigned char* d = dst + (8 * (r / 4) + (r % 4)) * rs;
-                if (p.out_bf16) *reinterpret_cast<uint16_t*>(d) = float_to_bf16(v[r] * osc[r]);
-                else *reinterpret_cast<float*>(d) = v[r] * osc[r];
+                    for (int e = 0; e < 4; ++e) v[e] *= osc;
+                }
+                if (p.out_bf16) {
+                    *reinterpret_cast<uint2*>(dst + 8 * g * ob) = make_uint2((uint32_t)float_to_bf16(v[0]) | ((uint32_t)float_to_bf16(v[1]) << 16),
+                                                                            (uint32_t)float_to_bf16(v[2]) | ((uint32_t)float_to_bf16(v[3]) << 16));
+                } else {
+                    *reinterpret_cast<float4*>(dst + 8 * g * ob) = make_float4(v[0], v[1], v[2], v[3]);
+                }
             }
             if (j + 1 == stage_blocks || cb + 1 == NB) {  // wave-uniform: the stage is full
                 wave_lds_fence();
                 const int n_first = (cb - j) * 32;
                 const int ncols = (p.Nout - n_first) < (j + 1) * 32 ? (p.Nout - n_first) : (j + 1) * 32;
                 if (ncols > 0) {
+                    // piece c of the stage is 16 bytes of staged row c / cpr; cpr is a power of two for the usual row
+                    // lengths, and then the split is a shift (a division by a run-time value costs some twenty instructions)
                     const int cpr = (ncols * ob + 15) / 16;
+                    const int shift = (cpr & (cpr - 1)) == 0 ? 31 - __clz(cpr) : -1;   // wave-uniform
                     unsigned char* Yb = static_cast<unsigned char*>(p.Y);
                     for (int c = lane; c < 32 * cpr; c += 64) {
-                        const int row = c / cpr, cc = c - row * cpr;
+                        const int row = shift >= 0 ? c >> shift : c / cpr, cc = c - row * cpr;
                         const int64_t m = m0 + row;
                         if (m >= p.M) continue;
                         const int n = cc * epc;   // column inside the staged stretch
                         const unsigned char* src = stage + row * rs + cc * 16;
                         unsigned char* y = Yb + (m * p.ld_y + n_first + n) * ob;
-                        if (n + epc <= ncols) {
+                        if (n + epc <= ncols && p.y_vec) {
                             *reinterpret_cast<uint4*>(y) = *reinterpret_cast<const uint4*>(src);
+                        } else if (n + epc <= ncols) {  // output rows that are not 16-byte aligned
+                            for (int e = 0; e < 16; e += 2) *reinterpret_cast<uint16_t*>(y + e) = *reinterpret_cast<const uint16_t*>(src + e);
                         } else {
                             for (int e = 0; e < (ncols - n) * ob; e += 2) *reinterpret_cast<uint16_t*>(y + e) = *reinterpret_cast<const uint16_t*>(src + e);
                         }
@@ -706,7 +765,7 @@ dgi_status_t launch_cfg(GemmParams p, hipStream_t stream) {
     return DGI_OK;
 }
 
-constexpr int kStationaryWaves = 8;
+constexpr int kStationaryWaves = DGI_STATIONARY_WAVES;
 
 int device_cu_count() {
     static const int n = [] {
@@ -732,32 +791,72 @@ size_t stationary_lds_bytes() {
 // the kernel is built for 2, 4, 6 and 8 column blocks of 32
 int stationary_blocks(int Nout) { return ((Nout + 63) / 64) * 2; }
 
-int stationary_stage_blocks(const GemmParams& p, size_t* weight_bytes) {
-    const int NB = stationary_blocks(p.Nout);
-    const int kstot = (p.K1 + 15) / 16 + (p.A2 ? (p.K2 + 15) / 16 : 0);
+// steps of 128 elements of K per tile
+int stationary_steps(const GemmParams& p) { return (p.K1 + 127) / 128 + (p.A2 ? (p.K2 + 127) / 128 : 0) * (p.A3 ? 2 : 1); }
+
+// steps (of the NS) without remainder bytes: all of them, or those of the first block when there are two
+int stationary_plain_steps(const GemmParams& p, bool with_bytes) {
+    return !with_bytes ? stationary_steps(p) : p.A2 ? (p.K1 + 127) / 128 : 0;
+}
+
+// registers of the accumulators and step buffers, in units the compiler's results were fitted to (176 builds without
+// spilling at two wavefronts per SIMD, 192 does not)
+constexpr int stationary_regs(int NB, int NS, int QS) { return 16 * NB + 32 * NS + 16 * (NS - QS); }
+
+// LDS plan of the stationary kernel: weight fragments, bias, one output stage per wavefront that holds as many column
+// blocks as fit (whole rows when it can).  Returns the column blocks per stage; 0 if the weight leaves no room, or if the
+// accumulators and the steps' buffers (and their remainder bytes: with_bytes) would not fit the registers of a wavefront.
+int stationary_stage_blocks(const GemmParams& p, bool with_bytes, size_t* weight_bytes) {
+    const int NB = stationary_blocks(p.Nout), NS = stationary_steps(p);
+    const int kstot = 8 * ((p.K1 + 127) / 128 + (p.A2 ? (p.K2 + 127) / 128 : 0));   // whole steps: see the kernel
     const size_t wb = (size_t)NB * kstot * 1024 + (size_t)NB * 128;
     if (weight_bytes) *weight_bytes = wb;
     const size_t kStationaryLds = stationary_lds_bytes();
-    if (NB > 8 || wb >= kStationaryLds) return 0;
+    if (NB > 8 || NS > 3 || wb >= kStationaryLds || p.K1 % 8 != 0 || (p.A2 && p.K2 % 8 != 0)) return 0;
+    if (stationary_regs(NB, NS, stationary_plain_steps(p, with_bytes)) > 176) return 0;
     const int ob = p.out_bf16 ? 2 : 4;
     const int64_t per_row = (int64_t)((kStationaryLds - wb) / kStationaryWaves / 32);   // bytes of one staged row
     const int64_t sb = (per_row - 16) / (32 * ob);
     return (int)std::min<int64_t>(NB, std::max<int64_t>(sb, 0));
 }
 
+template <int NB, int NS, int QS>
+dgi_status_t launch_stationary_k(const GemmParams& p, int sb, size_t wb, hipStream_t stream) {
+    if constexpr (QS < 0 || QS > NS || stationary_regs(NB, NS, QS) > 176) {
+        set_error("gemm: the weights-stationary kernel is not built for this shape");
+        return DGI_ERR_UNSUPPORTED;
+    } else {
+        const int ob = p.out_bf16 ? 2 : 4;
+        const int stage_bytes = 32 * (sb * 32 * ob + 16);
+        const size_t lds = wb + (size_t)kStationaryWaves * stage_bytes;
+        const int64_t tiles = (p.M + 31) / 32;
+        const int64_t grid = std::min<int64_t>(device_cu_count(), (tiles + kStationaryWaves - 1) / kStationaryWaves);
+        auto kernel = gemm_stationary_kernel<NB, NS, QS>;
+        if (lds > 48 * 1024)
+            DGI_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kStationaryWaves * 64), lds, stream, p, sb, stage_bytes);
+        DGI_HIP(hipGetLastError());
+        return DGI_OK;
+    }
+}
+
+template <int NB, int NS>
+dgi_status_t launch_stationary_ns(const GemmParams& p, int sb, size_t wb, hipStream_t stream) {
+    switch (stationary_plain_steps(p, p.Q != nullptr)) {
+        case 0: return launch_stationary_k<NB, NS, 0>(p, sb, wb, stream);
+        case 1: return launch_stationary_k<NB, NS, 1>(p, sb, wb, stream);
+        case 2: return launch_stationary_k<NB, NS, 2>(p, sb, wb, stream);
+        default: return launch_stationary_k<NB, NS, 3>(p, sb, wb, stream);
+    }
+}
+
 template <int NB>
 dgi_status_t launch_stationary_nb(const GemmParams& p, int sb, size_t wb, hipStream_t stream) {
-    const int ob = p.out_bf16 ? 2 : 4;
-    const int stage_bytes = 32 * (sb * 32 * ob + 16);
-    const size_t lds = wb + (size_t)kStationaryWaves * stage_bytes;
-    const int64_t tiles = (p.M + 31) / 32;
-    const int64_t grid = std::min<int64_t>(device_cu_count(), (tiles + kStationaryWaves - 1) / kStationaryWaves);
-    auto kernel = gemm_stationary_kernel<NB>;
-    if (lds > 48 * 1024)
-        DGI_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kStationaryWaves * 64), lds, stream, p, sb, stage_bytes);
-    DGI_HIP(hipGetLastError());
-    return DGI_OK;
+    switch (stationary_steps(p)) {
+        case 1: return launch_stationary_ns<NB, 1>(p, sb, wb, stream);
+        case 2: return launch_stationary_ns<NB, 2>(p, sb, wb, stream);
+        default: return launch_stationary_ns<NB, 3>(p, sb, wb, stream);
+    }
 }
 
 dgi_status_t launch_stationary(const GemmParams& p, int sb, size_t wb, hipStream_t stream) {
@@ -770,11 +869,22 @@ dgi_status_t launch_stationary(const GemmParams& p, int sb, size_t wb, hipStream
 
 }  // namespace
 
+bool gemm_stationary_applies(const void* A1, int64_t ld_a1, int K1, int blocks, int K2, int Nout, int out_dtype, bool with_bytes) {
+    if ((uintptr_t)A1 % 16 != 0 || (ld_a1 * 2) % 16 != 0) return false;
+    GemmParams p{};
+    const void* some = reinterpret_cast<const void*>(16);   // only the presence of a block matters to the plan
+    p.K1 = K1; p.K2 = K2; p.A2 = blocks >= 2 ? some : nullptr; p.A3 = blocks >= 3 ? some : nullptr;
+    p.Nout = Nout; p.out_bf16 = out_dtype == DGI_BF16;
+    return stationary_stage_blocks(p, with_bytes, nullptr) > 0;
+}
+
 dgi_status_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
     if (a.M <= 0 || a.Nout <= 0) return DGI_OK;
     const int eb = a.dtype == DGI_BF16 ? 2 : 4, E = 16 / eb;
     DGI_REQUIRE(a.A1 && a.Wt && a.Y, DGI_ERR_INVALID_ARG, "gemm: null operand");
-    DGI_REQUIRE(a.dtype == DGI_BF16 || !a.A3, DGI_ERR_INVALID_ARG, "gemm: the low-order block is a bf16 operand");
+    DGI_REQUIRE(a.dtype == DGI_BF16 || (!a.A3 && !a.A_lo8), DGI_ERR_INVALID_ARG, "gemm: the low-order block is a bf16 operand");
+    DGI_REQUIRE(!(a.A3 && a.A_lo8), DGI_ERR_INVALID_ARG, "gemm: one form of low-order block at a time");
+    DGI_REQUIRE(!a.A_lo8 || (uintptr_t)a.A_lo8 % 8 == 0, DGI_ERR_INVALID_ARG, "gemm: remainder bytes misaligned");
     DGI_REQUIRE((uintptr_t)a.Wt % 16 == 0 && a.ldw % E == 0 && a.K1p % E == 0, DGI_ERR_INVALID_ARG, "gemm: packed weight misaligned");
     GemmParams p{};
     p.A1 = a.A1; p.ld_a1 = a.ld_a1; p.K1 = a.K1;
@@ -793,11 +903,16 @@ dgi_status_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
     p.out_scale = a.out_scale; p.row0 = a.row0;
     // 128-wide column tiles: a 256-wide tile would read A once but leaves one wavefront per SIMD and measured slower
     if (a.dtype == DGI_BF16) {
-        if (p.a1_vec && (!p.A2 || p.a2_vec) && p.y_vec && !kTiledBf16) {
+        // the weights-stationary kernel where it applies
+        if (p.a1_vec && (!p.A2 || p.a2_vec) && (!kTiledBf16 || a.A_lo8)) {
             size_t wb = 0;
-            const int sb = stationary_stage_blocks(p, &wb);
-            if (sb > 0) return launch_stationary(p, sb, wb, stream);
+            const int sb = stationary_stage_blocks(p, a.A_lo8 != nullptr, &wb);
+            if (sb > 0) {
+                p.Q = static_cast<const uint8_t*>(a.A_lo8); p.ld_q = p.A2 ? a.ld_a2 : a.ld_a1;
+                return launch_stationary(p, sb, wb, stream);
+            }
         }
+        DGI_REQUIRE(!a.A_lo8, DGI_ERR_UNSUPPORTED, "gemm: remainder bytes need the weights-stationary kernel (ask gemm_stationary_applies first)");
         if (a.Nout <= 64) return launch_cfg<uint16_t, 4, 1, 1, 2>(p, stream);
         if (a.Nout > 128 && a.Nout <= 192) return launch_cfg<uint16_t, 2, 2, 2, 3>(p, stream);
         return launch_cfg<uint16_t, 2, 2, 2, 2>(p, stream);

@@ -112,8 +112,10 @@ struct AggArgs {
     int s_dtype = DGI_F32;
     int width = 0;            // columns gathered
     void* out = nullptr;      // element (v, c) at out[(v - out_row0) * ld_out + c]
-    void* out_lo = nullptr;   // bf16 output only, optional: a second matrix of the same layout that receives
-                              // bf16(value - float(bf16(value))), so that out + out_lo carries 16 mantissa bits
+    void* out_lo = nullptr;   // bf16 output only, optional: a second matrix of the same shape and leading dimension that
+                              // receives what the bf16 rounding dropped, so that out + out_lo carries 16 mantissa bits:
+    int lo_bytes = 2;         // as bf16(value - float(bf16(value))) (2), or as one byte per element (1): the remainder in
+                              // units of 2^-8 of the bf16 value's last place, plus 128
     int64_t ld_out = 0;
     int64_t out_row0 = 0;
     int out_dtype = DGI_F32;
@@ -178,7 +180,10 @@ struct GemmArgs {
     int dtype = DGI_F32;        // dtype of A1, A2 and Wt
     const void* A1 = nullptr; int64_t ld_a1 = 0; int K1 = 0;
     const void* A2 = nullptr; int64_t ld_a2 = 0; int K2 = 0;
-    const void* A3 = nullptr;
+    const void* A3 = nullptr;     // bf16 only, optional: the remainders of A2 as a second bf16 matrix (same shape and ld)
+    const void* A_lo8 = nullptr;  // bf16 only, optional: the remainders of the last block (A2 if present, else A1) as one byte
+                                  // per element, same shape, leading dimension in bytes = that block's in elements
+                                  // (AggArgs.lo_bytes == 1); needs gemm_stationary_applies()
     const void* Wt = nullptr; int64_t ldw = 0; int K1p = 0;
     const float* bias = nullptr;
     int act = DGI_ACT_NONE; float act_slope = 0.f;
@@ -187,6 +192,11 @@ struct GemmArgs {
     const float* out_scale = nullptr; int64_t row0 = 0;  // optional: Y[r,:] *= out_scale[row0 + r] after the activation
 };
 dgi_status_t launch_gemm(const GemmArgs& a, hipStream_t stream);
+// Whether a bf16 GEMM of this shape runs on the weights-stationary kernel whatever the output's alignment (the weight
+// fragments and an output stage fit in LDS, accumulators and row buffers in registers, A1 rows are 16-byte aligned; the
+// other blocks live in the library's own aligned temporaries).  blocks: 1 = A1, 2 = A1 A2, 3 = A1 A2 A3; with_bytes: the
+// last block comes with remainder bytes (A_lo8), which only this kernel reads.
+bool gemm_stationary_applies(const void* A1, int64_t ld_a1, int K1, int blocks, int K2, int Nout, int out_dtype, bool with_bytes);
 
 // Wt[n, koff + k] = W[k, n] for k < K, n < Nout (W row-major [K x Nout]); dtype preserved.
 dgi_status_t launch_pack_weight(const void* W, int dtype, int K, int Nout, void* Wt, int64_t ldw, int koff,
