@@ -22,6 +22,15 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
 
+# what "dtype" stands for, spelled out
+ARITHMETIC = {
+    "bf16": "inputs, weights and hidden layers stored bf16; sums and products accumulated in fp32 (aggregates reach the bf16 "
+            "matrix instruction as a bf16 value plus its rounding remainder, 16 significant bits)",
+    "f32": "fp32 storage and accumulation; the GEMMs outside the fused kernel run on the bf16 matrix instruction with both "
+           "operands split exactly into three bf16 terms and six products per fp32 product (error at the fp32 instruction's level)",
+}
+
+
 def algorithmic_bytes(n, e, width, elem, indptr_bytes, heads=0, out_width=None, out_elem=None, self_width=0):
     """Bytes the aggregation of one layer must move when nothing is reused: per edge one source row and
     its index (plus the GAT score terms), per destination node its indptr entry and its output row (for
@@ -386,6 +395,7 @@ def main():
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16" if storage == "bf16" else "f32",
+        "arithmetic": ARITHMETIC[storage],
         "data": "synthetic",
         "config": {"workload": cfg["name"], "num_nodes": n, "num_edges": e, "max_in_degree": info["max_in_degree"],
                    "in_degree": degree_stats, "hub_rows": info["num_hub_rows"], "hub_edges": info["num_hub_edges"], "scale": args.scale, "batch_size": args.batch_size or "dynamic",
@@ -502,7 +512,7 @@ def other_config(B, configs, k, dev, steps=5, warmup=2, reorder=None):
     if reorder:
         r["traffic"] = None   # the offline counter figure belongs to the graph as generated
     res = {"workload": cfg["name"] + (" [ids renumbered by dgi_graph_reorder(%s), %.2f s once per graph; x and the output stay in the caller's order]" % (reorder, reorder_s) if reorder else ""),
-           "num_nodes": cfg["num_nodes"], "num_edges": e, "steps": steps, "warmup": warmup,
+           "num_nodes": cfg["num_nodes"], "num_edges": e, "steps": steps, "warmup": warmup, "dtype": "f32", "arithmetic": ARITHMETIC["f32"],
            "ms_per_step": sec * 1e3, "first_call_ms": first_ms, "edges_per_s": len(structs) * e / sec,
            "per_layer_ms": per_layer_ms(stats, steps),
            "dominant_kernel": {k2: r[k2] for k2 in ("kernel", "achieved", "frac", "avg_launch_ms", "traffic")}}

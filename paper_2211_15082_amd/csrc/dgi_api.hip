@@ -66,12 +66,12 @@ struct LayerPlan {
 // latency-bound sweep.  It pays when a row's gather (avg_degree * K elements) outweighs its share of that
 // sweep (ldw * N / 32 elements).  Measured on MI355X (fused vs split, whole layer):
 //   GCN fp32 256->256, degree 52 (ratio 6.5): 18.8 vs 22.0 ms;  GraphSAGE fp32 256->256, degree 20 (ratio 1.25):
-//   125 vs 133 ms;  GraphSAGE bf16 128->128, degree 14 (ratio 1.8): 155 vs 118 ms.
-// The split path's fp32 GEMM is MFMA-bound and expensive, its bf16 GEMM is cheap, hence the two thresholds.
-// The fp32 threshold comes from a 20 M-node graph sampled down to average degrees 2..12 (fused / split, ms per layer):
-//   GraphSAGE 256->256 (threshold ratio 1 = degree 16): degree 2 62/60, 4 63/66, 6 64/74, 8 66/82, 12 77/95;
-//   GCN 256->256 (degree 8): 2 41/41, 4 43/46, 6 45/53, 8 48/61;  GraphSAGE 128->128 (degree 8): 4 26/26, 6 27/28, 8 28/32;
-//   GraphSAGE 128->256 (degree 16): 6 41/40, 8 42/43, 12 44/51.  The crossovers sit at ratios 0.2-0.6: 0.5 it is.
+//   99 vs 108 ms;  GraphSAGE bf16 128->128, degree 14 (ratio 1.8): 129-155 vs 87 ms.
+// The split path's bf16 GEMM is cheap next to its fp32 GEMM, hence the two thresholds.
+// The fp32 threshold comes from a 20 M-node graph sampled down to average degrees 4..16 (fused / split, ms per layer):
+//   GraphSAGE 256->256 (threshold ratio 1 = degree 16): degree 4 61/52, 8 64/70, 12 76/80, 16 82/101;
+//   GCN 256->256 (degree 8): 4 40/39, 8 48/54, 12 58/75;  GraphSAGE 128->128 (degree 8): 4 26/22, 8 28/26, 12 32/33;
+//   GraphSAGE 128->256 (degree 16): 4 40/31, 8 42/37, 12 43/45.  The crossovers sit at ratios 0.4-1.4: 0.5 it is.
 // dgi_layer_t.order = AGG_FIRST_FUSED / AGG_FIRST_SPLIT overrides this choice per layer.
 bool want_fused(const dgi_graph* g, int dtype, int K, int64_t ldw, int N) {
     const double avg_deg = g && g->N > 0 ? (double)g->E / (double)g->N : 0.0;
