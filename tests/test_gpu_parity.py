@@ -508,11 +508,14 @@ def test_split_and_transform_first_paths_with_many_rows(storage, dims):
 
 
 @pytest.mark.parametrize("agg,dims,act", [("mean", (104, 40), "relu"), ("gcn", (320, 64), "leaky_relu"), ("sum", (136, 200), "none"),
-                                          ("mean", (8, 8), "relu"), ("gcn", (128, 256), "relu")])
+                                          ("mean", (8, 8), "relu"), ("gcn", (128, 256), "relu"), ("mean", (64, 64), "relu"),
+                                          ("gcn", (384, 32), "none"), ("mean", (128, 172), "elu")])
 def test_weights_stationary_bf16_gemm_shapes(agg, dims, act):
-    # the bf16 GEMM that keeps the weight in LDS: a last k-step of 8 elements (K = 104, 136), several 128-element parts per
-    # block (K = 320), the per-row factor of GCN, 2 to 8 column blocks with ragged last ones, a row count that leaves the
-    # last 32-row tile ragged; split order (three A blocks: own rows, aggregate, its remainder) and transform-first (one)
+    # the bf16 GEMM that keeps the weight in LDS: a last k-step of 8 elements (K = 104, 136), K blocks shorter than a step
+    # (K = 8, 64: the rest of the step re-reads the row's first bytes against zero weights), several 128-element steps per
+    # block (K = 320, 384), the per-row factor of GCN, 2 to 8 column blocks with ragged last ones, a row count that leaves
+    # the last 32-row tile ragged; split order (own rows, aggregate and its remainder as bytes, or as a third bf16 block on
+    # the tiled kernel where the shape does not fit: 136 -> 200) and transform-first (one block)
     n = 4111
     d_in, d_out = dims
     indptr, indices = random_csr(n, 5.0, seed=d_in + d_out)
